@@ -1,0 +1,156 @@
+/*
+ * bimamba.h -- C ABI of the MI355X (gfx950) bidirectional Mamba mixer path.
+ *
+ * What the library computes (paper Sec. 3.2, eqs. 4-6, and the block variant of Sec. 4.3), per
+ * batch element b, direction s in {f (left-to-right), b (right-to-left)}, channel d
+ * (head h = d / (d_inner/n_heads), B/C group g = h / (n_heads/n_groups)):
+ *
+ *   xc_s[t,d] = SiLU(conv_b_s[d] + sum_k conv_w_s[d,k] * x_s[t -/+ (K-1-k), d])      short depthwise conv; causal for f,
+ *                                                                                  anti-causal for b; zero outside [0,L)
+ *   Delta[t,h] = dt_s[t,h]                       (dt_softplus = 0)
+ *              = softplus(dt_s[t,h] + dt_bias_s[h])                (dt_softplus = 1)
+ *   h_t[n]    = exp(Delta[t,h] * A_s[h,n]) * h_prev[n] + Delta[t,h] * B_s[t,g,n] * xc_s[t,d]     eq. 4 (t = 0..L-1) / eq. 5 (t = L-1..0)
+ *   y_s[t,d]  = sum_n C_s[t,g,n] * h_t[n] + D_s[d] * xc_s[t,d]
+ *   g_s[t,d]  = y_s[t,d] * SiLU(z_s[t,d])
+ *   out[t,d]  = g_f[t,d] + g_b[t,d]                                                 eq. 6 (BIMAMBA_COMBINE_ADD)
+ *   out[t,:]  = [g_f[t,:] | g_b[t,:]]                                               (BIMAMBA_COMBINE_SEPARATE, width 2*d_inner)
+ *
+ * With conv_bc = 1 (the Mamba-2 form) B and C pass through the same conv + SiLU as x, using rows
+ * d_inner .. d_inner+2*n_groups*d_state-1 of conv_w / conv_b (channel order x | B | C).
+ *
+ * Memory: every pointer is device memory owned by the caller unless marked "host".  The library
+ * allocates nothing, keeps no pointer after a call returns and has no global state.  Activations are
+ * token-major with the channel dimension contiguous; batch and token strides are given in elements.
+ * All math is fp32; bf16 I/O is widened on load and rounded to nearest-even once at the final store.
+ *
+ * Execution: calls validate their arguments on the host, enqueue kernels on the caller's HIP stream
+ * and return without synchronising.  Calls on different streams are independent as long as their
+ * workspaces do not overlap.
+ *
+ * Errors: every entry point returns BIMAMBA_OK (0) or a negative bimamba_status.  All codes except
+ * BIMAMBA_ERR_HIP are decided on the host before anything is launched.  Nothing throws or aborts.
+ */
+#ifndef BIMAMBA_H
+#define BIMAMBA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BIMAMBA_VERSION 1
+
+enum bimamba_status {
+    BIMAMBA_OK = 0,
+    BIMAMBA_ERR_NULL_POINTER = -1,        /* a required pointer is NULL */
+    BIMAMBA_ERR_BAD_SHAPE = -2,           /* non-positive or inconsistent dimension, stride smaller than the row */
+    BIMAMBA_ERR_UNSUPPORTED = -3,         /* dtype / d_state / d_conv / grouping outside the compiled set */
+    BIMAMBA_ERR_MISALIGNED = -4,          /* pointer not aligned to its element size (or 16 bytes for the workspace) */
+    BIMAMBA_ERR_WORKSPACE_TOO_SMALL = -5, /* workspace_bytes < bimamba_workspace_bytes() */
+    BIMAMBA_ERR_HIP = -6                  /* a kernel launch failed (hipGetLastError) */
+};
+
+enum bimamba_dtype { BIMAMBA_F32 = 0, BIMAMBA_BF16 = 1 };
+enum bimamba_a_kind {
+    BIMAMBA_A_PER_HEAD_STATE = 0,  /* A[n_heads, d_state]; the selective-scan layout has n_heads = d_inner */
+    BIMAMBA_A_SCALAR_PER_HEAD = 1  /* A[n_heads]: one decay rate per head (the Mamba-2 form) */
+};
+enum bimamba_d_kind { BIMAMBA_D_PER_CHANNEL = 0, BIMAMBA_D_PER_HEAD = 1 };
+enum bimamba_combine { BIMAMBA_COMBINE_ADD = 0, BIMAMBA_COMBINE_SEPARATE = 1 };
+
+/* Host struct.  Supported: d_state in {4, 8, 16, 32, 64, 128}; 1 <= d_conv <= 4; d_inner % n_heads == 0;
+ * n_heads % n_groups == 0; with n_groups > 1, d_inner / n_groups must be a multiple of 64. */
+typedef struct bimamba_desc {
+    uint32_t struct_size;   /* sizeof(bimamba_desc), checked */
+    int32_t batch;          /* >= 0 (0 is a no-op) */
+    int32_t seqlen;         /* L >= 0; for bimamba_block_fwd the block length */
+    int32_t d_inner;
+    int32_t d_state;        /* N */
+    int32_t n_heads;        /* H; dt has H channels */
+    int32_t n_groups;       /* G; B and C have G*N channels */
+    int32_t d_conv;         /* K */
+    int32_t io_dtype;       /* bimamba_dtype of x, z, dt, B, C, out, tail_in, tail_out */
+    int32_t a_kind;         /* bimamba_a_kind */
+    int32_t d_kind;         /* bimamba_d_kind */
+    int32_t dt_softplus;    /* 0 or 1 */
+    int32_t conv_bc;        /* 0 or 1 */
+    int32_t combine;        /* bimamba_combine */
+    int32_t time_chunks;    /* 0 = let the library choose; n >= 1 forces n time segments per sequence
+                               (segments are scanned in parallel and stitched by a carry pass) */
+    int32_t reserved;       /* must be 0 */
+} bimamba_desc;
+
+/* Per-direction parameters, device pointers, fp32, contiguous.
+ * conv_w [conv_ch, d_conv] with conv_ch = d_inner (+ 2*n_groups*d_state if conv_bc); tap d_conv-1 multiplies the
+ * current token.  conv_b [conv_ch] or NULL (= 0).  A [n_heads, d_state] or [n_heads].  D [d_inner] or [n_heads].
+ * dt_bias [n_heads] or NULL (= 0), read only when dt_softplus = 1. */
+typedef struct bimamba_params {
+    const float* conv_w;
+    const float* conv_b;
+    const float* A;
+    const float* D;
+    const float* dt_bias;
+} bimamba_params;
+
+/* One activation tensor [batch, L, channels]: element (b, t, c) lives at ptr + b*stride_batch + t*stride_token + c
+ * (in elements of io_dtype).  stride_token >= channels.  Strided views let x, z, dt, B, C be column slices of one
+ * projection output.  ptr may be NULL only when batch == 0 or seqlen == 0 (nothing is accessed). */
+typedef struct bimamba_tensor {
+    void* ptr;
+    int64_t stride_batch;
+    int64_t stride_token;
+} bimamba_tensor;
+
+/* The activations one direction reads: x, z [batch, L, d_inner]; dt [batch, L, n_heads]; B, C [batch, L, n_groups*d_state]. */
+typedef struct bimamba_inputs {
+    bimamba_tensor x, z, dt, B, C;
+} bimamba_inputs;
+
+/*
+ * Full-sequence bidirectional mixer path (eqs. 4-6).
+ *   desc        host.  pf, pb: host structs of device pointers; pb may equal pf (tied weights).
+ *   in_f, in_b  host structs; in_b == NULL or in_b == in_f means both directions read the same activations.
+ *   out         [batch, L, d_inner] (ADD) or [batch, L, 2*d_inner] (SEPARATE), io_dtype; must not alias an input.
+ *   workspace   device scratch of at least bimamba_workspace_bytes(desc, 0) bytes, 16-byte aligned (may be NULL if 0).
+ *   hip_stream  a hipStream_t (NULL = the default stream).
+ */
+int bimamba_fwd(const bimamba_desc* desc, const bimamba_params* pf, const bimamba_params* pb,
+                const bimamba_inputs* in_f, const bimamba_inputs* in_b, const bimamba_tensor* out,
+                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Block variant (Sec. 4.3: the forward state is carried across blocks, right-to-left updates stay inside the
+ * block).  desc->seqlen is the block length.  The forward scan starts from h_in and its causal conv sees tail_in
+ * to the left of the block; the reverse scan starts from zero at the block's right edge with zeros beyond it.
+ *   h_in      fp32 [batch, d_inner, d_state] or NULL (= zero state).
+ *   tail_in   io_dtype [batch, d_conv-1, tail_ch], the raw (pre-conv) tokens preceding the block, oldest first, or
+ *             NULL (= zeros); tail_ch = d_inner (+ 2*n_groups*d_state if conv_bc, channel order x | B | C).
+ *   h_out     fp32 [batch, d_inner, d_state]: forward state after the block's last token, or NULL = do not commit.
+ *             May alias h_in.
+ *   tail_out  io_dtype, same shape as tail_in: last d_conv-1 raw tokens of (tail_in || block), or NULL.  May alias tail_in.
+ * A denoising loop calls this once per step with h_out = tail_out = NULL and commits on the block's last step.
+ * Everything else as bimamba_fwd; workspace size is bimamba_workspace_bytes(desc, 1).
+ */
+int bimamba_block_fwd(const bimamba_desc* desc, const bimamba_params* pf, const bimamba_params* pb,
+                      const bimamba_inputs* in_f, const bimamba_inputs* in_b,
+                      const float* h_in, const void* tail_in, float* h_out, void* tail_out,
+                      const bimamba_tensor* out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of device scratch the two calls above need for this descriptor (0 on an invalid descriptor).  Pure host code. */
+size_t bimamba_workspace_bytes(const bimamba_desc* desc, int block_variant);
+
+/* Number of time segments the library would use for this descriptor (>= 1; 0 on an invalid descriptor).  Pure host code. */
+int bimamba_time_chunks(const bimamba_desc* desc);
+
+/* Static, NUL-terminated description of a status code. */
+const char* bimamba_status_string(int status);
+
+/* BIMAMBA_VERSION the library was built from. */
+int bimamba_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BIMAMBA_H */

@@ -1,0 +1,49 @@
+"""Compile the HIP library for gfx950 into paper_2511_15927_amd/libbimamba.so (in-tree, hipcc)."""
+import os
+import subprocess
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
+LIB = os.path.join(HERE, "libbimamba.so")
+D_STATES = (4, 8, 16, 32, 64, 128)
+# packed fp32 VALU forms are switched off for every kernel in this library
+FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
+         "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include"),
+         "-I", CSRC]
+NOISE = "is not a recognized feature for this target"
+
+
+def _run(cmd):
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    log = "\n".join(l for l in r.stdout.splitlines() if NOISE not in l)
+    if r.returncode != 0:
+        raise RuntimeError("failed: " + " ".join(cmd) + "\n" + log)
+    return log
+
+
+def sources():
+    return [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC))] + [os.path.join(ROOT, "include", "bimamba.h")]
+
+
+def build(force: bool = True, jobs: int = 8):
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= max(os.path.getmtime(p) for p in sources()):
+        return LIB
+    os.makedirs(OBJ, exist_ok=True)
+    units = [(os.path.join(CSRC, "bimamba_api.hip"), os.path.join(OBJ, "bimamba_api.o"), [])]
+    for n in D_STATES:
+        units.append((os.path.join(CSRC, "scan_inst.hip"), os.path.join(OBJ, "scan_n%d.o" % n), ["-DBM_N=%d" % n]))
+    cmds = [["hipcc"] + FLAGS + extra + ["-c", src, "-o", obj] for src, obj, extra in units]
+    with ThreadPoolExecutor(max_workers=max(1, min(jobs, len(cmds)))) as ex:
+        logs = list(ex.map(_run, cmds))
+    logs.append(_run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + [u[1] for u in units]))
+    out = "\n".join(l for l in logs if l.strip())
+    if out.strip():
+        print(out)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build())

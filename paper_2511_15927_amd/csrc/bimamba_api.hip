@@ -1,0 +1,300 @@
+// Host side of the C ABI declared in include/bimamba.h: argument validation, workspace carving, kernel dispatch.
+#include "bimamba.h"
+#include "kernels.h"
+#include "launch.h"
+
+#include <hip/hip_runtime.h>
+
+namespace {
+
+using namespace bm;
+
+constexpr int kTargetWaves = 1024;  // one wave per SIMD on 256 CUs x 4 SIMDs
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool is_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int check_desc(const bimamba_desc* d)
+{
+    if (!d) return BIMAMBA_ERR_NULL_POINTER;
+    if (d->struct_size != sizeof(bimamba_desc)) return BIMAMBA_ERR_BAD_SHAPE;
+    if (d->batch < 0 || d->seqlen < 0 || d->d_inner < 1 || d->d_state < 1 || d->n_heads < 1 || d->n_groups < 1 ||
+        d->d_conv < 1)
+        return BIMAMBA_ERR_BAD_SHAPE;
+    if (d->d_inner % d->n_heads || d->n_heads % d->n_groups) return BIMAMBA_ERR_BAD_SHAPE;
+    if (d->time_chunks < 0 || d->reserved != 0) return BIMAMBA_ERR_BAD_SHAPE;
+    if (d->batch > 65535) return BIMAMBA_ERR_UNSUPPORTED;
+    if (d->io_dtype != BIMAMBA_F32 && d->io_dtype != BIMAMBA_BF16) return BIMAMBA_ERR_UNSUPPORTED;
+    if (d->a_kind != BIMAMBA_A_PER_HEAD_STATE && d->a_kind != BIMAMBA_A_SCALAR_PER_HEAD) return BIMAMBA_ERR_UNSUPPORTED;
+    if (d->d_kind != BIMAMBA_D_PER_CHANNEL && d->d_kind != BIMAMBA_D_PER_HEAD) return BIMAMBA_ERR_UNSUPPORTED;
+    if (d->combine != BIMAMBA_COMBINE_ADD && d->combine != BIMAMBA_COMBINE_SEPARATE) return BIMAMBA_ERR_UNSUPPORTED;
+    if ((d->dt_softplus | 1) != 1 || (d->conv_bc | 1) != 1) return BIMAMBA_ERR_UNSUPPORTED;
+    if (d->d_conv > 4) return BIMAMBA_ERR_UNSUPPORTED;
+    switch (d->d_state) {
+        case 4: case 8: case 16: case 32: case 64: case 128: break;
+        default: return BIMAMBA_ERR_UNSUPPORTED;
+    }
+    if (d->n_groups > 1 && (d->d_inner / d->n_groups) % 64 != 0) return BIMAMBA_ERR_UNSUPPORTED;
+    return BIMAMBA_OK;
+}
+
+int pick_chunks(const bimamba_desc* d)
+{
+    const int L = d->seqlen;
+    if (L <= 0) return 1;
+    int n;
+    if (d->time_chunks > 0) {
+        n = d->time_chunks;
+    } else {
+        // Each extra segment re-evaluates the decay exponentials in a summary pass, so only split when the
+        // (batch x channel-tile x direction) chains cannot fill the chip on their own.
+        const long long waves = 2LL * d->batch * ((d->d_inner + 63) / 64);
+        n = 1;
+        if (waves > 0 && waves < kTargetWaves) n = (int)((kTargetWaves + waves - 1) / waves);
+        const int max_by_len = L / 256 > 0 ? L / 256 : 1;  // keep segments at least 256 tokens long
+        if (n > max_by_len) n = max_by_len;
+    }
+    if (n > L) n = L;
+    if (n > 4096) n = 4096;
+    if (n < 1) n = 1;
+    return n;
+}
+
+struct Plan {
+    int nseg, seg_len;
+    bool two_bc;  // the two directions consume different prepared B|C buffers
+    size_t off_bc[2], off_partial, off_carry, off_sumdt, total;
+};
+
+Plan make_plan(const bimamba_desc* d, bool inputs_shared)
+{
+    Plan p{};
+    p.nseg = pick_chunks(d);
+    p.seg_len = d->seqlen > 0 ? (d->seqlen + p.nseg - 1) / p.nseg : 1;
+    p.nseg = d->seqlen > 0 ? (d->seqlen + p.seg_len - 1) / p.seg_len : 1;
+    p.two_bc = d->conv_bc || !inputs_shared;
+    const size_t bc_bytes = align_up((size_t)d->batch * d->seqlen * d->n_groups * 2 * d->d_state * sizeof(float), 256);
+    size_t off = 0;
+    p.off_bc[0] = off; off += bc_bytes;
+    if (p.two_bc) { p.off_bc[1] = off; off += bc_bytes; } else { p.off_bc[1] = p.off_bc[0]; }
+    p.off_partial = off;
+    if (d->combine == BIMAMBA_COMBINE_ADD) off += align_up((size_t)d->batch * d->seqlen * d->d_inner * sizeof(float), 256);
+    p.off_carry = off;
+    p.off_sumdt = off;
+    if (p.nseg > 1) {
+        off += align_up((size_t)2 * d->batch * p.nseg * d->d_inner * d->d_state * sizeof(float), 256);
+        p.off_sumdt = off;
+        off += align_up((size_t)2 * d->batch * p.nseg * d->d_inner * sizeof(float), 256);
+    }
+    p.total = off;
+    return p;
+}
+
+int check_tensor(const bimamba_tensor& t, int channels, size_t elem, const bimamba_desc* d)
+{
+    const bool empty = d->batch == 0 || d->seqlen == 0;  // nothing is read or written: the pointer may be NULL
+    if (!t.ptr && !empty) return BIMAMBA_ERR_NULL_POINTER;
+    if (!is_aligned(t.ptr, elem)) return BIMAMBA_ERR_MISALIGNED;
+    if (t.stride_token < channels) return BIMAMBA_ERR_BAD_SHAPE;
+    if (d->batch > 1 && t.stride_batch < (int64_t)d->seqlen * t.stride_token - (t.stride_token - channels))
+        return BIMAMBA_ERR_BAD_SHAPE;
+    return BIMAMBA_OK;
+}
+
+int check_params(const bimamba_params* p)
+{
+    if (!p) return BIMAMBA_ERR_NULL_POINTER;
+    if (!p->conv_w || !p->A || !p->D) return BIMAMBA_ERR_NULL_POINTER;
+    if (!is_aligned(p->conv_w, 4) || !is_aligned(p->A, 4) || !is_aligned(p->D, 4) || !is_aligned(p->conv_b, 4) ||
+        !is_aligned(p->dt_bias, 4))
+        return BIMAMBA_ERR_MISALIGNED;
+    return BIMAMBA_OK;
+}
+
+int check_inputs(const bimamba_inputs* in, const bimamba_desc* d, size_t elem)
+{
+    if (!in) return BIMAMBA_ERR_NULL_POINTER;
+    int rc;
+    if ((rc = check_tensor(in->x, d->d_inner, elem, d))) return rc;
+    if ((rc = check_tensor(in->z, d->d_inner, elem, d))) return rc;
+    if ((rc = check_tensor(in->dt, d->n_heads, elem, d))) return rc;
+    if ((rc = check_tensor(in->B, d->n_groups * d->d_state, elem, d))) return rc;
+    if ((rc = check_tensor(in->C, d->n_groups * d->d_state, elem, d))) return rc;
+    return BIMAMBA_OK;
+}
+
+bool same_tensor(const bimamba_tensor& a, const bimamba_tensor& b)
+{
+    return a.ptr == b.ptr && a.stride_batch == b.stride_batch && a.stride_token == b.stride_token;
+}
+
+bool same_inputs(const bimamba_inputs* a, const bimamba_inputs* b)
+{
+    return a == b || (same_tensor(a->x, b->x) && same_tensor(a->z, b->z) && same_tensor(a->dt, b->dt) &&
+                      same_tensor(a->B, b->B) && same_tensor(a->C, b->C));
+}
+
+TensorArg targ(const bimamba_tensor& t) { return TensorArg{t.ptr, (long long)t.stride_batch, (long long)t.stride_token}; }
+
+void launch_scan(const bimamba_desc* d, const SweepArgs& sa, const CarryArgs& ca, dim3 grid, hipStream_t st)
+{
+    const int scalar_a = d->a_kind == BIMAMBA_A_SCALAR_PER_HEAD, bf16 = d->io_dtype == BIMAMBA_BF16;
+    switch (d->d_state) {
+        case 4: launch_scan_n4(scalar_a, bf16, sa, ca, grid, st); break;
+        case 8: launch_scan_n8(scalar_a, bf16, sa, ca, grid, st); break;
+        case 16: launch_scan_n16(scalar_a, bf16, sa, ca, grid, st); break;
+        case 32: launch_scan_n32(scalar_a, bf16, sa, ca, grid, st); break;
+        case 64: launch_scan_n64(scalar_a, bf16, sa, ca, grid, st); break;
+        case 128: launch_scan_n128(scalar_a, bf16, sa, ca, grid, st); break;
+        default: break;
+    }
+}
+
+int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* pb, const bimamba_inputs* in_f,
+        const bimamba_inputs* in_b, const float* h_in, const void* tail_in, float* h_out, void* tail_out,
+        const bimamba_tensor* out, void* workspace, size_t workspace_bytes, void* hip_stream, bool block_variant)
+{
+    int rc = check_desc(d);
+    if (rc) return rc;
+    const size_t elem = d->io_dtype == BIMAMBA_BF16 ? 2 : 4;
+    if ((rc = check_params(pf))) return rc;
+    if ((rc = check_params(pb))) return rc;
+    if (!in_b) in_b = in_f;
+    if ((rc = check_inputs(in_f, d, elem))) return rc;
+    if ((rc = check_inputs(in_b, d, elem))) return rc;
+    if (!out) return BIMAMBA_ERR_NULL_POINTER;
+    const int out_ch = d->combine == BIMAMBA_COMBINE_SEPARATE ? 2 * d->d_inner : d->d_inner;
+    if ((rc = check_tensor(*out, out_ch, elem, d))) return rc;
+    if (!is_aligned(h_in, 4) || !is_aligned(h_out, 4) || !is_aligned(tail_in, elem) || !is_aligned(tail_out, elem))
+        return BIMAMBA_ERR_MISALIGNED;
+    const bool shared = same_inputs(in_f, in_b);
+    const Plan plan = make_plan(d, shared);
+    if (plan.total > 0) {
+        if (!workspace) return BIMAMBA_ERR_NULL_POINTER;
+        if (!is_aligned(workspace, 16)) return BIMAMBA_ERR_MISALIGNED;
+        if (workspace_bytes < plan.total) return BIMAMBA_ERR_WORKSPACE_TOO_SMALL;
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    const int GN = d->n_groups * d->d_state;
+    const int tail_ch = d->d_inner + (d->conv_bc ? 2 * GN : 0);
+    char* ws = static_cast<char*>(workspace);
+
+    if (d->batch > 0 && d->seqlen > 0) {
+        // 1. fp32 B|C rows per direction
+        const int nbuf = plan.two_bc ? 2 : 1;
+        for (int s = 0; s < nbuf; s++) {
+            const bimamba_inputs* in = s == 0 ? in_f : in_b;
+            const bimamba_params* p = s == 0 ? pf : pb;
+            PrepArgs pa{};
+            pa.B = targ(in->B);
+            pa.C = targ(in->C);
+            pa.conv_w = p->conv_w;
+            pa.conv_b = p->conv_b;
+            pa.tail_in = (s == 0 && block_variant) ? tail_in : nullptr;
+            pa.dst = reinterpret_cast<float*>(ws + plan.off_bc[s]);
+            pa.batch = d->batch; pa.L = d->seqlen; pa.G = d->n_groups; pa.N = d->d_state; pa.K = d->d_conv;
+            pa.Dn = d->d_inner; pa.tail_ch = tail_ch; pa.conv_bc = d->conv_bc; pa.dir = s == 0 ? 1 : -1;
+            const long long total = (long long)d->batch * d->seqlen * 2 * GN;
+            const dim3 grid((unsigned)((total + 255) / 256));
+            if (d->io_dtype == BIMAMBA_BF16) hipLaunchKernelGGL(prep_bc_kernel<IoBF16>, grid, dim3(256), 0, st, pa);
+            else hipLaunchKernelGGL(prep_bc_kernel<IoF32>, grid, dim3(256), 0, st, pa);
+        }
+        // 2. scan (summary + carry when the sequence is cut into segments) and combine
+        SweepArgs sa{};
+        for (int s = 0; s < 2; s++) {
+            const bimamba_inputs* in = s == 0 ? in_f : in_b;
+            const bimamba_params* p = s == 0 ? pf : pb;
+            DirArgs& da = sa.dir[s];
+            da.x = targ(in->x); da.z = targ(in->z); da.dt = targ(in->dt);
+            da.bc = reinterpret_cast<const float*>(ws + plan.off_bc[s]);
+            da.conv_w = p->conv_w; da.conv_b = p->conv_b; da.A = p->A; da.D = p->D; da.dt_bias = p->dt_bias;
+        }
+        sa.out = out->ptr; sa.out_sb = out->stride_batch; sa.out_st = out->stride_token;
+        sa.partial = reinterpret_cast<float*>(ws + plan.off_partial);
+        sa.h_in = block_variant ? h_in : nullptr;
+        sa.h_out = block_variant ? h_out : nullptr;
+        sa.tail_in = block_variant ? tail_in : nullptr;
+        sa.carry = reinterpret_cast<float*>(ws + plan.off_carry);
+        sa.sumdt = reinterpret_cast<float*>(ws + plan.off_sumdt);
+        sa.L = d->seqlen; sa.Dn = d->d_inner; sa.P = d->d_inner / d->n_heads; sa.HG = d->n_heads / d->n_groups;
+        sa.G = d->n_groups; sa.K = d->d_conv; sa.nseg = plan.nseg; sa.seg_len = plan.seg_len; sa.tail_ch = tail_ch;
+        sa.dt_softplus = d->dt_softplus; sa.d_per_head = d->d_kind == BIMAMBA_D_PER_HEAD;
+        sa.separate = d->combine == BIMAMBA_COMBINE_SEPARATE;
+        CarryArgs ca{};
+        ca.carry = sa.carry; ca.sumdt = sa.sumdt; ca.A[0] = pf->A; ca.A[1] = pb->A;
+        ca.h_in = sa.h_in; ca.h_out = sa.h_out;
+        ca.batch = d->batch; ca.nseg = plan.nseg; ca.Dn = d->d_inner; ca.P = sa.P;
+        const dim3 grid((unsigned)((d->d_inner + 63) / 64), (unsigned)plan.nseg, (unsigned)d->batch);
+        launch_scan(d, sa, ca, grid, st);
+    } else if (block_variant && d->batch > 0 && h_out && h_out != h_in) {
+        // empty block: the state passes through unchanged
+        const size_t bytes = (size_t)d->batch * d->d_inner * d->d_state * sizeof(float);
+        if (h_in) (void)hipMemcpyAsync(h_out, h_in, bytes, hipMemcpyDeviceToDevice, st);
+        else (void)hipMemsetAsync(h_out, 0, bytes, st);
+    }
+    // 3. conv tail for the next block
+    if (block_variant && tail_out && d->batch > 0 && d->d_conv > 1) {
+        TailArgs ta{};
+        ta.x = targ(in_f->x); ta.B = targ(in_f->B); ta.C = targ(in_f->C);
+        ta.tail_in = tail_in; ta.tail_out = tail_out;
+        ta.batch = d->batch; ta.L = d->seqlen; ta.K = d->d_conv; ta.Dn = d->d_inner; ta.GN = GN; ta.tail_ch = tail_ch;
+        const long long total = (long long)d->batch * tail_ch;
+        const dim3 grid((unsigned)((total + 255) / 256));
+        if (d->io_dtype == BIMAMBA_BF16) hipLaunchKernelGGL(tail_kernel<IoBF16>, grid, dim3(256), 0, st, ta);
+        else hipLaunchKernelGGL(tail_kernel<IoF32>, grid, dim3(256), 0, st, ta);
+    }
+    return hipGetLastError() == hipSuccess ? BIMAMBA_OK : BIMAMBA_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int bimamba_fwd(const bimamba_desc* desc, const bimamba_params* pf, const bimamba_params* pb,
+                const bimamba_inputs* in_f, const bimamba_inputs* in_b, const bimamba_tensor* out, void* workspace,
+                size_t workspace_bytes, void* hip_stream)
+{
+    return run(desc, pf, pb, in_f, in_b, nullptr, nullptr, nullptr, nullptr, out, workspace, workspace_bytes, hip_stream,
+               false);
+}
+
+int bimamba_block_fwd(const bimamba_desc* desc, const bimamba_params* pf, const bimamba_params* pb,
+                      const bimamba_inputs* in_f, const bimamba_inputs* in_b, const float* h_in, const void* tail_in,
+                      float* h_out, void* tail_out, const bimamba_tensor* out, void* workspace, size_t workspace_bytes,
+                      void* hip_stream)
+{
+    return run(desc, pf, pb, in_f, in_b, h_in, tail_in, h_out, tail_out, out, workspace, workspace_bytes, hip_stream,
+               true);
+}
+
+size_t bimamba_workspace_bytes(const bimamba_desc* desc, int block_variant)
+{
+    (void)block_variant;
+    if (check_desc(desc)) return 0;
+    // sized for the larger case (the two directions reading different activations)
+    return make_plan(desc, false).total;
+}
+
+int bimamba_time_chunks(const bimamba_desc* desc)
+{
+    if (check_desc(desc)) return 0;
+    return make_plan(desc, true).nseg;
+}
+
+const char* bimamba_status_string(int status)
+{
+    switch (status) {
+        case BIMAMBA_OK: return "ok";
+        case BIMAMBA_ERR_NULL_POINTER: return "a required pointer is NULL";
+        case BIMAMBA_ERR_BAD_SHAPE: return "bad shape: non-positive or inconsistent dimension or stride";
+        case BIMAMBA_ERR_UNSUPPORTED: return "unsupported dtype, d_state, d_conv or grouping";
+        case BIMAMBA_ERR_MISALIGNED: return "misaligned pointer";
+        case BIMAMBA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case BIMAMBA_ERR_HIP: return "HIP launch error";
+        default: return "unknown status";
+    }
+}
+
+int bimamba_version(void) { return BIMAMBA_VERSION; }
+
+}  // extern "C"

@@ -1,0 +1,100 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, and rejects bad arguments on the
+host before anything is launched (no GPU is touched by these calls)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2511_15927_amd import binding as bd
+from paper_2511_15927_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "bimamba.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bimamba_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert set(names) == set(bd.EXPORTS)
+    lib = bd.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert bd.bimamba_version() == 1
+
+
+def good():
+    cfg = synth.mixer_cfg(2, 64, 128, io="bf16")
+    desc = bd.make_desc(cfg)
+    fake = 0x1000
+    p = bd.Params(fake, fake, fake, fake, None)
+    t = lambda ch: bd.Tensor(fake, 64 * ch, ch)
+    inp = bd.Inputs(t(128), t(128), t(128), t(16), t(16))
+    return cfg, desc, p, inp, t(128)
+
+
+def call_fwd(desc, pf, pb, inp, out, ws=0x1000, ws_bytes=1 << 40):
+    return bd.lib().bimamba_fwd(C.byref(desc), C.byref(pf) if pf else None, C.byref(pb) if pb else None,
+                                C.byref(inp) if inp else None, None, C.byref(out) if out else None,
+                                C.c_void_p(ws), ws_bytes, None)
+
+
+def test_null_and_shape_errors_are_decided_on_the_host():
+    cfg, desc, p, inp, out = good()
+    assert call_fwd(desc, None, p, inp, out) == -1
+    assert call_fwd(desc, p, p, None, out) == -1
+    assert call_fwd(desc, p, p, inp, None) == -1
+    assert call_fwd(desc, bd.Params(None, None, 0x1000, 0x1000, None), p, inp, out) == -1
+    assert call_fwd(desc, p, p, inp, out, ws=None) == -1
+    assert call_fwd(desc, p, p, inp, out, ws_bytes=16) == -5
+    assert call_fwd(desc, p, p, inp, out, ws=0x1004) == -4
+    bad = bd.Inputs(bd.Tensor(0x1001, 64 * 128, 128), inp.z, inp.dt, inp.B, inp.C)
+    assert call_fwd(desc, p, p, bad, out) == -4
+    narrow = bd.Inputs(bd.Tensor(0x1000, 64 * 128, 100), inp.z, inp.dt, inp.B, inp.C)
+    assert call_fwd(desc, p, p, narrow, out) == -2
+    overlap = bd.Inputs(bd.Tensor(0x1000, 128, 128), inp.z, inp.dt, inp.B, inp.C)
+    assert call_fwd(desc, p, p, overlap, out) == -2
+
+
+@pytest.mark.parametrize("field,value,code", [
+    ("struct_size", 8, -2), ("batch", -1, -2), ("seqlen", -5, -2), ("d_inner", 0, -2), ("n_heads", 3, -2),
+    ("n_groups", 5, -2), ("d_state", 12, -3), ("d_conv", 5, -3), ("d_conv", 0, -2), ("io_dtype", 7, -3),
+    ("a_kind", 2, -3), ("d_kind", 9, -3), ("combine", 2, -3), ("dt_softplus", 2, -3), ("conv_bc", -1, -3),
+    ("time_chunks", -1, -2), ("reserved", 1, -2),
+])
+def test_descriptor_validation(field, value, code):
+    cfg, desc, p, inp, out = good()
+    setattr(desc, field, value)
+    assert call_fwd(desc, p, p, inp, out) == code
+    assert bd.bimamba_workspace_bytes(desc) == 0
+    assert bd.bimamba_time_chunks(desc) == 0
+
+
+def test_group_tiling_rule():
+    cfg = synth.mixer_cfg(1, 8, 96, n_heads=96, n_groups=2)      # 48 channels per group: a wave would straddle groups
+    desc = bd.make_desc(cfg)
+    assert bd.bimamba_workspace_bytes(desc) == 0
+
+
+def test_workspace_and_chunk_planning():
+    d1 = bd.make_desc(synth.CONFIGS["headline"])
+    assert bd.bimamba_time_chunks(d1) == 1                       # 1024 chains-of-64 already fill the chip
+    d2 = bd.make_desc(synth.CONFIGS["cfg2"])
+    assert bd.bimamba_time_chunks(d2) == 8                       # batch 1: the sequence is cut to fill it
+    assert bd.bimamba_time_chunks(bd.make_desc(synth.CONFIGS["cfg3_block"])) == 1
+    assert bd.bimamba_time_chunks(bd.make_desc(synth.mixer_cfg(1, 100, 64, time_chunks=7))) == 7
+    assert bd.bimamba_time_chunks(bd.make_desc(synth.mixer_cfg(1, 5, 64, time_chunks=7))) == 5
+    sep = bd.make_desc(synth.mixer_cfg(8, 8192, 4096, combine=1))
+    assert bd.bimamba_workspace_bytes(sep) < bd.bimamba_workspace_bytes(d1)     # no partial buffer without ADD
+    assert bd.bimamba_workspace_bytes(d1) % 256 == 0
+
+
+def test_status_strings():
+    lib = bd.lib()
+    for code in range(0, -7, -1):
+        assert lib.bimamba_status_string(code).decode() not in ("", "unknown status")
+    assert lib.bimamba_status_string(-99).decode() == "unknown status"

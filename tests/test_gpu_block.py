@@ -1,0 +1,148 @@
+"""GPU parity of the state-carrying block variant (Sec. 4.3) against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import rel_l2, to_np
+from paper_2511_15927_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import gpu_util
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return gpu_util
+
+
+def params(cfg, seed, random_a=True):
+    pf, pb = synth.make_params(cfg, seed, 0), synth.make_params(cfg, seed, 1)
+    if random_a:
+        pf["A"], pb["A"] = synth.random_A(cfg, seed), synth.random_A(cfg, seed + 1)
+    return pf, pb
+
+
+def raw_tail(cfg, inp, upto):
+    """Last K-1 raw tokens before index `upto` (zeros where the sequence has not started), [Bt, K-1, tail_ch]."""
+    K, Bt = cfg["d_conv"], cfg["batch"]
+    cols = [inp["x"]]
+    if cfg["conv_bc"]:
+        cols += [inp["B"].reshape(Bt, inp["B"].shape[1], -1), inp["C"].reshape(Bt, inp["C"].shape[1], -1)]
+    raw = torch.cat(cols, dim=2)
+    tail = torch.zeros(Bt, K - 1, raw.shape[2])
+    take = min(upto, K - 1)
+    if take:
+        tail[:, K - 1 - take:] = raw[:, upto - take:upto]
+    return tail
+
+
+@pytest.mark.parametrize("variant", ["s_f32", "s_bf16", "m2_f32", "sep"])
+def test_block_matches_oracle_with_carried_state(gpu, oracle, variant):
+    if variant == "m2_f32":
+        cfg = synth.m2_cfg(2, 48, 128, headdim=32, d_state=16, io="f32")
+    else:
+        cfg = synth.mixer_cfg(2, 48, 100, io="bf16" if variant == "s_bf16" else "f32",
+                              combine=1 if variant == "sep" else 0)
+    pf, pb = params(cfg, 11)
+    inp = synth.make_inputs(cfg, 11)
+    m, G = 21, 16                                           # prefix length and block length
+    pre = {k: v[:, :m].contiguous() for k, v in inp.items()}
+    blk = {k: v[:, m:m + G].contiguous() for k, v in inp.items()}
+    _, h_pre = oracle.one_direction(dict(cfg, seqlen=m), to_np(pf), to_np(pre), +1)
+    h_in = h_pre.astype(np.float32)                          # the cached state is fp32 on both sides
+    tail = raw_tail(cfg, inp, m)
+    cb = dict(cfg, seqlen=G)
+    ref, h_ref, t_ref = oracle.bimamba_block_fwd(cb, to_np(pf), to_np(pb), to_np(blk), h_in=h_in, tail_in=tail.numpy())
+    got, h_got, t_got = gpu.gpu_block_fwd(cb, pf, pb, blk, h_in=h_in, tail_in=tail)
+    assert rel_l2(got, ref) < gpu.TOL[cfg["io"]]
+    assert rel_l2(h_got, h_ref) < 1e-5
+    assert np.array_equal(t_got, t_ref)
+
+
+def test_block_chain_equals_full_forward_scan(gpu, oracle):
+    """Chaining committed blocks reproduces the full-sequence forward state; every block's forward half equals the
+    full scan's rows and its reverse half the block-local reverse scan."""
+    cfg = synth.mixer_cfg(2, 96, 70, io="f32", combine=1)
+    pf, pb = params(cfg, 12)
+    inp = synth.make_inputs(cfg, 12)
+    g_full, h_full = oracle.one_direction(cfg, to_np(pf), to_np(inp), +1)
+    h, tail = None, None
+    for t0, t1 in ((0, 32), (32, 33), (33, 35), (35, 35), (35, 96)):
+        blk = {k: v[:, t0:t1].contiguous() for k, v in inp.items()}
+        cb = dict(cfg, seqlen=t1 - t0)
+        out, h, tail = gpu.gpu_block_fwd(cb, pf, pb, blk, h_in=h, tail_in=tail)
+        if t1 > t0:
+            g_rev, _ = oracle.one_direction(cb, to_np(pb), to_np(blk), -1)
+            assert rel_l2(out[:, :, 0], g_full[:, t0:t1]) < 1e-5, (t0, t1)
+            assert rel_l2(out[:, :, 1], g_rev) < 1e-5, (t0, t1)
+    assert rel_l2(h, h_full) < 1e-5
+    assert np.array_equal(tail, inp["x"][:, 93:96].numpy().astype(np.float64))
+
+
+def test_block_no_commit_and_in_place_commit(gpu, oracle):
+    from paper_2511_15927_amd import binding as bd
+    cfg = synth.mixer_cfg(2, 32, 128, io="bf16")
+    pf, pb = params(cfg, 13)
+    inp = synth.make_inputs(cfg, 13)
+    h0 = (0.1 * torch.randn(2, 128, 16, generator=torch.Generator().manual_seed(5))).float()
+    tail0 = synth.round_io(torch.randn(2, 3, 128, generator=torch.Generator().manual_seed(6)), "bf16")
+    ref, h_ref, t_ref = oracle.bimamba_block_fwd(cfg, to_np(pf), to_np(pb), to_np(inp), h_in=h0.numpy(), tail_in=tail0.numpy())
+    # denoising steps that do not commit leave the cache untouched
+    got, h_none, t_none = gpu.gpu_block_fwd(cfg, pf, pb, inp, h_in=h0, tail_in=tail0, commit=False)
+    assert h_none is None and t_none is None
+    assert rel_l2(got, ref) < gpu.TOL["bf16"]
+    # committing in place (h_out aliases h_in, tail_out aliases tail_in)
+    desc = bd.make_desc(cfg)
+    dh, dt = h0.cuda(), tail0.to(torch.bfloat16).cuda()
+    out = bd.alloc_out(cfg)
+    dpf, dpb, dinp, ws = bd.to_device(pf), bd.to_device(pb), bd.to_device(inp, cfg), bd.alloc_workspace(desc, 1)
+    bd.bimamba_block_fwd(desc, bd.make_params(dpf), bd.make_params(dpb), bd.make_inputs(dinp), None, dh, dt, dh, dt,
+                         bd.make_tensor(out), ws)
+    torch.cuda.synchronize()
+    assert rel_l2(out.float().cpu().numpy(), ref) < gpu.TOL["bf16"]
+    assert rel_l2(dh.cpu().numpy(), h_ref) < 1e-5
+    assert np.array_equal(dt.float().cpu().numpy().astype(np.float64), t_ref)
+
+
+@pytest.mark.parametrize("chunks", [2, 5])
+def test_block_long_prefix_time_chunked(gpu, oracle, chunks):
+    """A long clean prefix scanned once through the block entry point, cut into time segments: the committed state
+    must equal the sequential scan's (and may be written in place)."""
+    cfg = synth.mixer_cfg(1, 333, 96, io="f32", time_chunks=chunks)
+    pf, pb = params(cfg, 14)
+    inp = synth.make_inputs(cfg, 14)
+    h0 = (0.1 * torch.randn(1, 96, 16, generator=torch.Generator().manual_seed(7))).float()
+    ref, h_ref, _ = oracle.bimamba_block_fwd(cfg, to_np(pf), to_np(pb), to_np(inp), h_in=h0.numpy())
+    got, h_got, _ = gpu.gpu_block_fwd(cfg, pf, pb, inp, h_in=h0)
+    assert rel_l2(got, ref) < 1e-5
+    assert rel_l2(h_got, h_ref) < 1e-5
+
+
+def test_cfg3_block_diffusion_shapes(gpu, oracle):
+    """batch 16, d_inner 4096: a clean prefix scanned once (forward state cached), then 32-token blocks re-scanned
+    several denoising steps from the cached state, committing on a block's last step."""
+    cfg_p = dict(synth.CONFIGS["cfg3_prefix"], seqlen=1024)       # shortened prefix keeps the test quick
+    cfg_b = synth.CONFIGS["cfg3_block"]
+    Bt, Dn, N, G = 16, 4096, 16, 32
+    seed = synth.config_seed(3)
+    pf, pb = params(cfg_p, seed, random_a=False)
+    sel = sorted(np.random.default_rng(6).choice(Dn, size=16, replace=False).tolist())
+    prefix = synth.make_inputs(cfg_p, seed)
+    out_p, h_gpu, tail_gpu = gpu.gpu_block_fwd(cfg_p, pf, pb, prefix)
+    ref_p, h_ref, tail_ref = oracle.bimamba_block_fwd(cfg_p, to_np(pf), to_np(pb), to_np(prefix), sel=sel)
+    assert rel_l2(out_p[..., sel], ref_p) < gpu.TOL["bf16"]
+    assert rel_l2(h_gpu[:, sel], h_ref[:, sel]) < 1e-5
+    assert np.array_equal(tail_gpu, tail_ref)
+    for blk in range(2):
+        for step in range(3):
+            last = step == 2
+            inp = synth.make_inputs(cfg_b, seed + 10 * blk + step + 1)      # the block's tokens change every step
+            got, h_new, tail_new = gpu.gpu_block_fwd(cfg_b, pf, pb, inp, h_in=h_gpu, tail_in=tail_gpu, commit=last)
+            ref, h_ref_new, tail_ref_new = oracle.bimamba_block_fwd(cfg_b, to_np(pf), to_np(pb), to_np(inp),
+                                                                   h_in=h_ref, tail_in=tail_ref, sel=sel)
+            assert rel_l2(got[..., sel], ref) < gpu.TOL["bf16"], (blk, step)
+            if last:
+                h_gpu, tail_gpu, h_ref, tail_ref = h_new, tail_new, h_ref_new, tail_ref_new
+                assert rel_l2(h_gpu[:, sel], h_ref[:, sel]) < 1e-5
+                assert np.array_equal(tail_gpu, tail_ref)

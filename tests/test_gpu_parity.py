@@ -1,0 +1,165 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle, element by element, on seeded inputs.
+
+Tolerances (max over batch elements of relative L2 error): 1e-5 for fp32 I/O, 2e-2 for bf16 I/O with fp32 state.
+"""
+import numpy as np
+import pytest
+import torch
+
+from helpers import rel_l2, to_np
+from paper_2511_15927_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import gpu_util
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return gpu_util
+
+
+def case(cfg, seed, random_a=False):
+    pf, pb = synth.make_params(cfg, seed, 0), synth.make_params(cfg, seed, 1)
+    if random_a:
+        pf["A"], pb["A"] = synth.random_A(cfg, seed), synth.random_A(cfg, seed + 1)
+    return pf, pb, synth.make_inputs(cfg, seed)
+
+
+def check_fwd(gpu, oracle, cfg, seed, random_a=False, untied=False, sel=None, **override):
+    pf, pb, inp = case(cfg, seed, random_a)
+    inp_b = synth.make_inputs(cfg, seed + 500) if untied else None
+    c = dict(cfg, **override)
+    got = gpu.gpu_fwd(c, pf, pb, inp, inp_b)
+    ref = oracle.bimamba_fwd(c, to_np(pf), to_np(pb), to_np(inp), None if inp_b is None else to_np(inp_b), sel=sel)
+    if sel is not None:
+        got = got[..., sel]
+    err = rel_l2(got, ref)
+    assert err < gpu.TOL[c["io"]], (err, c)
+    return err
+
+
+def test_cfg0_tiny_fp32(gpu, oracle):
+    cfg = synth.CONFIGS["cfg0"]
+    check_fwd(gpu, oracle, cfg, synth.config_seed(0))
+    check_fwd(gpu, oracle, cfg, synth.config_seed(0), random_a=True)
+    check_fwd(gpu, oracle, cfg, synth.config_seed(0), untied=True)
+    check_fwd(gpu, oracle, cfg, synth.config_seed(0), combine=synth.COMBINE_SEPARATE)
+    check_fwd(gpu, oracle, cfg, synth.config_seed(0), untied=True, combine=synth.COMBINE_SEPARATE, random_a=True)
+    check_fwd(gpu, oracle, dict(cfg, dt_softplus=1), synth.config_seed(0))
+    check_fwd(gpu, oracle, dict(cfg, io="bf16"), synth.config_seed(0))
+
+
+def test_cfg0_mamba2_form(gpu, oracle):
+    check_fwd(gpu, oracle, synth.CONFIGS["cfg0_m2"], synth.config_seed(0))
+    check_fwd(gpu, oracle, dict(synth.CONFIGS["cfg0_m2"], io="bf16"), synth.config_seed(0), untied=True)
+    # the paper's 1.3B layer shape: 120 heads x 32, d_state 128, conv over x|B|C
+    check_fwd(gpu, oracle, dict(synth.CONFIGS["paper_1p3b"], seqlen=96), 7, sel=list(range(0, 3840, 97)))
+
+
+@pytest.mark.parametrize("L", [1, 2, 3, 7, 8, 9, 15, 16, 17, 31, 33, 100])
+def test_ragged_lengths(gpu, oracle, L):
+    for io in ("f32", "bf16"):
+        cfg = synth.mixer_cfg(2, L, 96, io=io)
+        check_fwd(gpu, oracle, cfg, 100 + L, random_a=True)
+        check_fwd(gpu, oracle, cfg, 100 + L, combine=synth.COMBINE_SEPARATE)
+
+
+@pytest.mark.parametrize("Dn", [1, 24, 63, 64, 65, 200])
+def test_ragged_channels(gpu, oracle, Dn):
+    cfg = synth.mixer_cfg(3, 37, Dn, io="f32")
+    check_fwd(gpu, oracle, cfg, 200 + Dn, random_a=True)
+
+
+@pytest.mark.parametrize("N", [4, 8, 16, 32, 64, 128])
+@pytest.mark.parametrize("a_kind", [0, 1])
+def test_state_sizes(gpu, oracle, N, a_kind):
+    cfg = synth.mixer_cfg(2, 40, 128, d_state=N, n_heads=128 if a_kind == 0 else 4, a_kind=a_kind, d_kind=a_kind, io="f32")
+    check_fwd(gpu, oracle, cfg, 300 + N, random_a=True)
+
+
+@pytest.mark.parametrize("K", [1, 2, 3, 4])
+def test_conv_widths(gpu, oracle, K):
+    for L in (1, 2, 5, 19):
+        check_fwd(gpu, oracle, synth.mixer_cfg(2, L, 70, d_conv=K, io="f32"), 400 + K)
+        check_fwd(gpu, oracle, synth.m2_cfg(1, L, 128, headdim=32, d_state=16, d_conv=K, io="f32"), 410 + K)
+
+
+def test_groups_and_heads(gpu, oracle):
+    cfg = synth.mixer_cfg(2, 50, 256, d_state=16, n_heads=8, n_groups=2, a_kind=1, d_kind=1, conv_bc=1, dt_softplus=1, io="f32")
+    check_fwd(gpu, oracle, cfg, 501)
+    cfg = synth.mixer_cfg(2, 50, 256, d_state=8, n_heads=256, n_groups=4, io="bf16")
+    check_fwd(gpu, oracle, cfg, 502, random_a=True)
+
+
+@pytest.mark.parametrize("chunks", [1, 2, 3, 5, 8, 64])
+def test_time_chunking_matches_oracle(gpu, oracle, chunks):
+    cfg = synth.mixer_cfg(2, 203, 130, io="f32", time_chunks=chunks)
+    check_fwd(gpu, oracle, cfg, 600, random_a=True)
+    check_fwd(gpu, oracle, dict(cfg, combine=1), 600, random_a=True, untied=True)
+    m2 = synth.m2_cfg(1, 150, 128, headdim=32, d_state=32, io="f32", time_chunks=chunks)
+    check_fwd(gpu, oracle, m2, 601)
+
+
+def test_strided_views_of_one_projection(gpu, oracle):
+    """x, z, dt, B, C as column slices of one [Bt, L, D_in] buffer (channel stride 1, token stride D_in)."""
+    from paper_2511_15927_amd import binding as bd
+    cfg = synth.mixer_cfg(2, 45, 96, io="bf16")
+    pf, pb, inp = case(cfg, 700)
+    Dn, N = 96, 16
+    widths = dict(z=Dn, x=Dn, B=N, C=N, dt=Dn)
+    big = torch.zeros(2, 45, sum(widths.values()) + 5, dtype=torch.bfloat16, device="cuda")
+    views, off = {}, 3
+    for k in ("z", "x", "B", "C", "dt"):
+        views[k] = big[:, :, off:off + widths[k]]
+        views[k].copy_(inp[k].reshape(2, 45, -1).to(torch.bfloat16))
+        off += widths[k]
+    desc = bd.make_desc(cfg)
+    out_big = torch.zeros(2, 45, Dn + 7, dtype=torch.bfloat16, device="cuda")
+    out = out_big[:, :, 4:4 + Dn]
+    dpf, dpb, ws = bd.to_device(pf), bd.to_device(pb), bd.alloc_workspace(desc)
+    bd.bimamba_fwd(desc, bd.make_params(dpf), bd.make_params(dpb), bd.make_inputs(views), None, bd.make_tensor(out), ws)
+    torch.cuda.synchronize()
+    ref = oracle.bimamba_fwd(cfg, to_np(pf), to_np(pb), to_np(inp))
+    assert rel_l2(out.float().cpu().numpy(), ref) < gpu.TOL["bf16"]
+    assert torch.all(out_big[:, :, :4] == 0) and torch.all(out_big[:, :, 4 + Dn:] == 0)
+
+
+def test_determinism_bitwise(gpu):
+    cfg = synth.mixer_cfg(2, 300, 192, io="bf16", time_chunks=3)
+    pf, pb, inp = case(cfg, 800)
+    a = gpu.gpu_fwd(cfg, pf, pb, inp)
+    b = gpu.gpu_fwd(cfg, pf, pb, inp)
+    assert np.array_equal(a, b)
+
+
+def sampled(n, total, seed):
+    rng = np.random.default_rng(seed)
+    return sorted(rng.choice(total, size=n, replace=False).tolist())
+
+
+def test_cfg1_1p3b_scale_layer(gpu, oracle):
+    cfg = synth.CONFIGS["cfg1"]
+    sel = sampled(96, cfg["d_inner"], 1)
+    check_fwd(gpu, oracle, cfg, synth.config_seed(1), sel=sel)
+
+
+def test_cfg1_general_A(gpu, oracle):
+    cfg = dict(synth.CONFIGS["cfg1"], batch=2)
+    check_fwd(gpu, oracle, cfg, synth.config_seed(1) + 1, random_a=True, sel=sampled(64, 4096, 2))
+
+
+def test_cfg2_long_sequence(gpu, oracle):
+    cfg = synth.CONFIGS["cfg2"]
+    check_fwd(gpu, oracle, cfg, synth.config_seed(2), sel=sampled(64, cfg["d_inner"], 3))
+
+
+def test_headline_shape_sampled(gpu, oracle):
+    """d_inner=4096, L=8192, batch 8, bf16: the launch configuration the benchmark times."""
+    cfg = synth.CONFIGS["headline"]
+    check_fwd(gpu, oracle, cfg, synth.config_seed(9), sel=sampled(24, cfg["d_inner"], 4))
+
+
+def test_mamba2_shapes_sampled(gpu, oracle):
+    cfg = dict(synth.CONFIGS["cfg1_m2"], batch=1, seqlen=1024)
+    check_fwd(gpu, oracle, cfg, synth.config_seed(1) + 7, sel=sampled(48, 4096, 5))
