@@ -1,0 +1,143 @@
+#!/usr/bin/env python3
+"""Benchmark of the bidirectional Mamba mixer path on one MI355X.
+
+A step is one bimamba_fwd call (B|C preparation + bidirectional scan + gate + combine) over one batch of synthetic
+input already resident in HBM.  Prints ONE JSON line: whole-job tokens/s, the roofline of the dominant kernel
+(timed with HIP events around that kernel inside the timed region) and the fp64 oracle timed on the host cores on a
+bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBPS = 8000.0          # MI355X HBM3E
+PEAK_FP32_VECTOR_TFLOPS = 157.3  # MI355X fp32 vector (256 CUs x 2.4 GHz x 256 flop/clk)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="headline", help="name in synth.CONFIGS (default: d_inner=4096, L=8192, batch 8, bf16)")
+    ap.add_argument("--general-a", action="store_true", help="draw A with no structure across states")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-batches", type=int, default=2, help="batch elements the oracle is timed on")
+    return ap.parse_args()
+
+
+def read_traffic(kernel_key):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", kernel_key + "_pmc.txt")
+    vals = {}
+    try:
+        for line in open(path):
+            if "=" in line and not line.lstrip().startswith("#"):
+                k, v = line.split("=", 1)
+                vals[k.strip()] = v.strip()
+        return float(vals["FETCH_BYTES_PER_LAUNCH"]) + float(vals["WRITE_BYTES_PER_LAUNCH"])
+    except Exception:
+        return None
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus %d is not supported: the path shards by batch or "
+              "d_inner with no exchange, and no multi-GPU run is part of it)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2511_15927_amd import binding as bd
+    from paper_2511_15927_amd import shapes, synth
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    bd.lib()  # fail loudly if the HIP library is not built
+    cfg = dict(synth.CONFIGS[args.workload])
+    seed = synth.config_seed(9)
+    t0 = time.time()
+    pf, pb = synth.make_params(cfg, seed, 0), synth.make_params(cfg, seed, 1)
+    if args.general_a:
+        pf["A"], pb["A"] = synth.random_A(cfg, seed), synth.random_A(cfg, seed + 1)
+    inp = synth.make_inputs(cfg, seed)
+    gen_s = time.time() - t0
+
+    desc = bd.make_desc(cfg)
+    dpf, dpb, dinp = bd.to_device(pf), bd.to_device(pb), bd.to_device(inp, cfg)
+    out = bd.alloc_out(cfg)
+    ws = bd.alloc_workspace(desc)
+    cpf, cpb, cin, cout = bd.make_params(dpf), bd.make_params(dpb), bd.make_inputs(dinp), bd.make_tensor(out)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        bd.bimamba_fwd(desc, cpf, cpb, cin, None, cout, ws, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # HIP events around the dominant kernel of every timed step (recorded by the library on the launch stream)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for a, b in evs:
+        a.record(stream)
+        b.record(stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, b in evs:
+        bd.bimamba_profile_next_call(a, b)
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    kernel_ms = sum(a.elapsed_time(b) for a, b in evs) / args.steps
+
+    tokens = cfg["batch"] * cfg["seqlen"]
+    value = tokens / (ms_per_step * 1e-3)
+    flops = shapes.algorithmic_flops(cfg)
+    nbytes = shapes.algorithmic_bytes(cfg)
+    ach_tflops = flops / (kernel_ms * 1e-3) / 1e12
+    ach_gbps = nbytes / (kernel_ms * 1e-3) / 1e9
+    scalar_a = cfg["a_kind"] == 1
+    kernel = "sweep_kernel<N=%d,%s,%s>" % (cfg["d_state"], "scalarA" if scalar_a else "perStateA", cfg["io"])
+    result = {
+        "metric": "bidirectional-scan tokens/s/GPU at d_inner=4096,L=8K; HBM GB/s vs peak",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "batch": cfg["batch"], "seq_len": cfg["seqlen"], "d_inner": cfg["d_inner"],
+                   "d_state": cfg["d_state"], "io_dtype": cfg["io"], "state_dtype": "f32",
+                   "A": "general" if args.general_a else "-(1..N) per state", "inputs": "shared by both directions",
+                   "combine": "add", "time_chunks": bd.bimamba_time_chunks(desc)},
+        "roofline": {"bound": "alu", "achieved": ach_tflops, "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
+                     "frac": ach_tflops / PEAK_FP32_VECTOR_TFLOPS, "traffic": read_traffic("sweep_" + args.workload),
+                     "kernel": kernel, "kernel_ms": kernel_ms, "algorithmic_flops": flops},
+        "hbm": {"achieved": ach_gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach_gbps / PEAK_HBM_GBPS,
+                "algorithmic_bytes": nbytes},
+        "input_generation_s": gen_s,
+    }
+
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle as orc
+        nb = max(1, min(args.cpu_batches, cfg["batch"]))
+        sub = dict(cfg, batch=nb)
+        npy = lambda d: {k: (None if v is None else v.numpy()) for k, v in d.items()}
+        sub_in = {k: v[:nb].contiguous() for k, v in inp.items()}
+        t0 = time.perf_counter()
+        ref = orc.bimamba_fwd(sub, npy(pf), npy(pb), npy(sub_in))
+        cpu_s = time.perf_counter() - t0
+        got = out[:nb].float().cpu().numpy().astype(np.float64)
+        err = max(float(np.linalg.norm(got[b] - ref[b]) / np.linalg.norm(ref[b])) for b in range(nb))
+        result["cpu_baseline"] = {"value": nb * cfg["seqlen"] / cpu_s, "unit": "tokens/s", "cores": orc.num_threads(),
+                                  "kind": "oracle", "seconds": cpu_s,
+                                  "sample": "batch elements 0..%d of %d, all %d tokens and %d channels, fp64" % (
+                                      nb - 1, cfg["batch"], cfg["seqlen"], cfg["d_inner"])}
+        result["rel_l2_vs_oracle"] = err
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -19,7 +19,8 @@
  * d_inner .. d_inner+2*n_groups*d_state-1 of conv_w / conv_b (channel order x | B | C).
  *
  * Memory: every pointer is device memory owned by the caller unless marked "host".  The library
- * allocates nothing, keeps no pointer after a call returns and has no global state.  Activations are
+ * allocates nothing, keeps no pointer after a call returns and has no global state (bimamba_profile_next_call
+ * excepted).  Activations are
  * token-major with the channel dimension contiguous; batch and token strides are given in elements.
  * All math is fp32; bf16 I/O is widened on load and rounded to nearest-even once at the final store.
  *
@@ -143,6 +144,13 @@ size_t bimamba_workspace_bytes(const bimamba_desc* desc, int block_variant);
 
 /* Number of time segments the library would use for this descriptor (>= 1; 0 on an invalid descriptor).  Pure host code. */
 int bimamba_time_chunks(const bimamba_desc* desc);
+
+/* Benchmark diagnostics: arm a one-shot probe on the calling host thread.  The next bimamba_fwd or
+ * bimamba_block_fwd made by this thread records ev_start immediately before and ev_stop immediately after its
+ * scan-and-combine kernel (not the B|C preparation, segment summary or tail kernels) on that call's stream, then
+ * disarms.  Both are hipEvent_t created by the caller with timing enabled; NULL, NULL disarms.  This thread-local
+ * pair is the only state the library keeps between calls. */
+void bimamba_profile_next_call(void* ev_start, void* ev_stop);
 
 /* Static, NUL-terminated description of a status code. */
 const char* bimamba_status_string(int status);

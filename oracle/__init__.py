@@ -12,7 +12,8 @@ import os
 
 import numpy as np
 
-from .build import LIB, build
+from .build import LIB
+from .build import build as build_lib
 
 _lib = None
 
@@ -35,7 +36,7 @@ def lib():
     global _lib
     if _lib is None:
         if not os.path.exists(LIB):
-            build()
+            build_lib()
         _lib = C.CDLL(LIB)
         _lib.orc_bimamba_fwd.restype = C.c_int
         _lib.orc_bimamba_block_fwd.restype = C.c_int

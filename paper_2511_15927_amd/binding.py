@@ -20,7 +20,7 @@ STATUS = {0: "BIMAMBA_OK", -1: "BIMAMBA_ERR_NULL_POINTER", -2: "BIMAMBA_ERR_BAD_
           -4: "BIMAMBA_ERR_MISALIGNED", -5: "BIMAMBA_ERR_WORKSPACE_TOO_SMALL", -6: "BIMAMBA_ERR_HIP"}
 
 EXPORTS = ("bimamba_fwd", "bimamba_block_fwd", "bimamba_workspace_bytes", "bimamba_time_chunks",
-           "bimamba_status_string", "bimamba_version")
+           "bimamba_profile_next_call", "bimamba_status_string", "bimamba_version")
 
 
 class Desc(C.Structure):
@@ -73,6 +73,8 @@ def lib():
         L.bimamba_status_string.restype = C.c_char_p
         L.bimamba_status_string.argtypes = [C.c_int]
         L.bimamba_version.restype = C.c_int
+        L.bimamba_profile_next_call.restype = None
+        L.bimamba_profile_next_call.argtypes = [C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -131,6 +133,14 @@ def bimamba_time_chunks(desc):
 
 def bimamba_version():
     return int(lib().bimamba_version())
+
+
+def bimamba_profile_next_call(ev_start, ev_stop):
+    """ev_start/ev_stop: torch.cuda.Event(enable_timing=True) that have been recorded once (so the HIP event
+    exists), or None to disarm."""
+    h0 = None if ev_start is None else C.c_void_p(ev_start.cuda_event)
+    h1 = None if ev_stop is None else C.c_void_p(ev_stop.cuda_event)
+    lib().bimamba_profile_next_call(h0, h1)
 
 
 def bimamba_fwd(desc, pf, pb, in_f, in_b, out, workspace, stream=None, check=True):

@@ -9,6 +9,8 @@ namespace {
 
 using namespace bm;
 
+thread_local hipEvent_t g_probe_start = nullptr, g_probe_stop = nullptr;  // one-shot, see bimamba_profile_next_call
+
 constexpr int kTargetWaves = 1024;  // one wave per SIMD on 256 CUs x 4 SIMDs
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -136,16 +138,17 @@ bool same_inputs(const bimamba_inputs* a, const bimamba_inputs* b)
 
 TensorArg targ(const bimamba_tensor& t) { return TensorArg{t.ptr, (long long)t.stride_batch, (long long)t.stride_token}; }
 
-void launch_scan(const bimamba_desc* d, const SweepArgs& sa, const CarryArgs& ca, dim3 grid, hipStream_t st)
+void launch_scan(const bimamba_desc* d, const SweepArgs& sa, const CarryArgs& ca, dim3 grid, hipStream_t st,
+                 hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     const int scalar_a = d->a_kind == BIMAMBA_A_SCALAR_PER_HEAD, bf16 = d->io_dtype == BIMAMBA_BF16;
     switch (d->d_state) {
-        case 4: launch_scan_n4(scalar_a, bf16, sa, ca, grid, st); break;
-        case 8: launch_scan_n8(scalar_a, bf16, sa, ca, grid, st); break;
-        case 16: launch_scan_n16(scalar_a, bf16, sa, ca, grid, st); break;
-        case 32: launch_scan_n32(scalar_a, bf16, sa, ca, grid, st); break;
-        case 64: launch_scan_n64(scalar_a, bf16, sa, ca, grid, st); break;
-        case 128: launch_scan_n128(scalar_a, bf16, sa, ca, grid, st); break;
+        case 4: launch_scan_n4(scalar_a, bf16, sa, ca, grid, st, ev_start, ev_stop); break;
+        case 8: launch_scan_n8(scalar_a, bf16, sa, ca, grid, st, ev_start, ev_stop); break;
+        case 16: launch_scan_n16(scalar_a, bf16, sa, ca, grid, st, ev_start, ev_stop); break;
+        case 32: launch_scan_n32(scalar_a, bf16, sa, ca, grid, st, ev_start, ev_stop); break;
+        case 64: launch_scan_n64(scalar_a, bf16, sa, ca, grid, st, ev_start, ev_stop); break;
+        case 128: launch_scan_n128(scalar_a, bf16, sa, ca, grid, st, ev_start, ev_stop); break;
         default: break;
     }
 }
@@ -154,6 +157,8 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
         const bimamba_inputs* in_b, const float* h_in, const void* tail_in, float* h_out, void* tail_out,
         const bimamba_tensor* out, void* workspace, size_t workspace_bytes, void* hip_stream, bool block_variant)
 {
+    const hipEvent_t probe_start = g_probe_start, probe_stop = g_probe_stop;
+    g_probe_start = g_probe_stop = nullptr;
     int rc = check_desc(d);
     if (rc) return rc;
     const size_t elem = d->io_dtype == BIMAMBA_BF16 ? 2 : 4;
@@ -225,7 +230,7 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
         ca.h_in = sa.h_in; ca.h_out = sa.h_out;
         ca.batch = d->batch; ca.nseg = plan.nseg; ca.Dn = d->d_inner; ca.P = sa.P;
         const dim3 grid((unsigned)((d->d_inner + 63) / 64), (unsigned)plan.nseg, (unsigned)d->batch);
-        launch_scan(d, sa, ca, grid, st);
+        launch_scan(d, sa, ca, grid, st, probe_start, probe_stop);
     } else if (block_variant && d->batch > 0 && h_out && h_out != h_in) {
         // empty block: the state passes through unchanged
         const size_t bytes = (size_t)d->batch * d->d_inner * d->d_state * sizeof(float);
@@ -279,6 +284,12 @@ int bimamba_time_chunks(const bimamba_desc* desc)
 {
     if (check_desc(desc)) return 0;
     return make_plan(desc, true).nseg;
+}
+
+void bimamba_profile_next_call(void* ev_start, void* ev_stop)
+{
+    g_probe_start = reinterpret_cast<hipEvent_t>(ev_start);
+    g_probe_stop = reinterpret_cast<hipEvent_t>(ev_stop);
 }
 
 const char* bimamba_status_string(int status)

@@ -1,0 +1,45 @@
+"""Shape bookkeeping for the mixer path: channel counts, the paper's per-token FLOP convention (App. C, Mamba-2
+layer table) and the algorithmic byte / flop counts used by the benchmark's roofline."""
+
+
+def conv_channels(d_inner, n_groups, d_state, conv_bc):
+    return d_inner + (2 * n_groups * d_state if conv_bc else 0)
+
+
+def in_proj_width(d_inner, n_groups, d_state, n_heads):
+    """Width of the projection that produces z, x, B, C, dt for one direction (the paper's D_in)."""
+    return 2 * d_inner + 2 * n_groups * d_state + n_heads
+
+
+def paper_flops_per_token(d_model, d_inner, d_state, d_conv, n_heads, n_groups=1):
+    """Per-token forward FLOPs of one direction of the paper's Mamba-2 layer, by its counting conventions
+    (2mn per linear layer, scan 2*d_inner*d_state, conv conv_ch*d_conv)."""
+    d_in = in_proj_width(d_inner, n_groups, d_state, n_heads)
+    conv_ch = conv_channels(d_inner, n_groups, d_state, 1)
+    parts = dict(in_proj=2 * d_model * d_in, conv=conv_ch * d_conv, scan=2 * d_inner * d_state,
+                 out_proj=2 * d_inner * d_model)
+    parts["one_direction"] = sum(parts.values())
+    parts["bidirectional"] = 2 * parts["one_direction"]
+    return parts
+
+
+def algorithmic_bytes(cfg, shared_inputs=True):
+    """Bytes the path must move once per call: each input read once, the output written once (state, tail and
+    parameters excluded).  Token-channel activations dominate; B and C amortise over d_inner."""
+    e = 2 if cfg["io"] == "bf16" else 4
+    Bt, L, Dn, H, GN = cfg["batch"], cfg["seqlen"], cfg["d_inner"], cfg["n_heads"], cfg["n_groups"] * cfg["d_state"]
+    ndir = 1 if shared_inputs else 2
+    reads = ndir * (2 * Dn + H + 2 * GN)            # x, z, dt, B, C
+    writes = Dn * (2 if cfg["combine"] else 1)
+    return Bt * L * (reads + writes) * e
+
+
+def algorithmic_flops(cfg):
+    """fp32 operations the definition needs per call, both directions: per (token, channel, direction)
+    conv 4 fma (8), two SiLU (mul, exp, add, rcp, mul = 5 each), Delta*xc (1), D*xc fma (2), gate mul (1) = 22,
+    plus per state: decay argument mul, exp, input mul, two fma = 7 (6 without a per-state decay: the exponential
+    and its argument are then per token-channel)."""
+    Bt, L, Dn, N = cfg["batch"], cfg["seqlen"], cfg["d_inner"], cfg["d_state"]
+    per_state = 7 if cfg["a_kind"] == 0 else 5
+    per_tc = 22 + per_state * N + (0 if cfg["a_kind"] == 0 else 2)
+    return 2 * Bt * L * Dn * per_tc + (Bt * L * Dn if not cfg["combine"] else 0)
