@@ -80,7 +80,9 @@ typedef struct bimamba_desc {
     int32_t combine;        /* bimamba_combine */
     int32_t time_chunks;    /* 0 = let the library choose; n >= 1 forces n time segments per sequence
                                (segments are scanned in parallel and stitched by a carry pass) */
-    int32_t reserved;       /* must be 0 */
+    int32_t state_split;    /* 0 = let the library choose; 1, 2 or 4 forces that many lanes per (direction, channel)
+                               chain, each holding d_state / state_split states (2 needs d_state 16 or 32, 4 needs
+                               d_state >= 16); results differ only by the summation order of C_t . h_t */
 } bimamba_desc;
 
 /* Per-direction parameters, device pointers, fp32, contiguous.

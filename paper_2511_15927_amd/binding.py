@@ -26,7 +26,7 @@ EXPORTS = ("bimamba_fwd", "bimamba_block_fwd", "bimamba_workspace_bytes", "bimam
 class Desc(C.Structure):
     _fields_ = [("struct_size", C.c_uint32)] + [(n, C.c_int32) for n in (
         "batch", "seqlen", "d_inner", "d_state", "n_heads", "n_groups", "d_conv", "io_dtype", "a_kind", "d_kind",
-        "dt_softplus", "conv_bc", "combine", "time_chunks", "reserved")]
+        "dt_softplus", "conv_bc", "combine", "time_chunks", "state_split")]
 
 
 class Params(C.Structure):
@@ -85,7 +85,7 @@ def make_desc(cfg, seqlen=None, **override):
     c.update(override)
     return Desc(C.sizeof(Desc), c["batch"], c["seqlen"] if seqlen is None else seqlen, c["d_inner"], c["d_state"],
                 c["n_heads"], c["n_groups"], c["d_conv"], BF16 if c["io"] == "bf16" else F32, c["a_kind"], c["d_kind"],
-                c["dt_softplus"], c["conv_bc"], c["combine"], c.get("time_chunks", 0), 0)
+                c["dt_softplus"], c["conv_bc"], c["combine"], c.get("time_chunks", 0), c.get("state_split", 0))
 
 
 def _ptr(t):

@@ -8,7 +8,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libbimamba.so")
-D_STATES = (4, 8, 16, 32, 64, 128)
+# (d_state, lanes per chain) pairs the scan kernels are instantiated for
+VARIANTS = ((4, 1), (8, 1), (16, 1), (16, 2), (16, 4), (32, 1), (32, 2), (32, 4), (64, 1), (64, 4), (128, 1), (128, 4))
 # packed fp32 VALU forms are switched off for every kernel in this library
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include"),
@@ -20,7 +21,7 @@ def _run(cmd):
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     log = "\n".join(l for l in r.stdout.splitlines() if NOISE not in l)
     if r.returncode != 0:
-        raise RuntimeError("failed: " + " ".join(cmd) + "\n" + log)
+        raise RuntimeError("failed: " + " ".join(cmd) + "\n" + log[:4000])
     return log
 
 
@@ -33,8 +34,9 @@ def build(force: bool = True, jobs: int = 8):
         return LIB
     os.makedirs(OBJ, exist_ok=True)
     units = [(os.path.join(CSRC, "bimamba_api.hip"), os.path.join(OBJ, "bimamba_api.o"), [])]
-    for n in D_STATES:
-        units.append((os.path.join(CSRC, "scan_inst.hip"), os.path.join(OBJ, "scan_n%d.o" % n), ["-DBM_N=%d" % n]))
+    for n, s in VARIANTS:
+        units.append((os.path.join(CSRC, "scan_inst.hip"), os.path.join(OBJ, "scan_n%d_s%d.o" % (n, s)),
+                      ["-DBM_N=%d" % n, "-DBM_S=%d" % s]))
     cmds = [["hipcc"] + FLAGS + extra + ["-c", src, "-o", obj] for src, obj, extra in units]
     with ThreadPoolExecutor(max_workers=max(1, min(jobs, len(cmds)))) as ex:
         logs = list(ex.map(_run, cmds))

@@ -11,10 +11,20 @@ using namespace bm;
 
 thread_local hipEvent_t g_probe_start = nullptr, g_probe_stop = nullptr;  // one-shot, see bimamba_profile_next_call
 
-constexpr int kTargetWaves = 1024;  // one wave per SIMD on 256 CUs x 4 SIMDs
+constexpr int kTargetWaves = 2048;  // two waves per SIMD on 256 CUs x 4 SIMDs
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline bool is_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+bool split_supported(int d_state, int split)
+{
+    switch (d_state * 8 + split) {
+        case 4 * 8 + 1: case 8 * 8 + 1: case 16 * 8 + 1: case 16 * 8 + 2: case 16 * 8 + 4: case 32 * 8 + 1:
+        case 32 * 8 + 2: case 32 * 8 + 4: case 64 * 8 + 1: case 64 * 8 + 4: case 128 * 8 + 1: case 128 * 8 + 4:
+            return true;
+        default: return false;
+    }
+}
 
 int check_desc(const bimamba_desc* d)
 {
@@ -24,7 +34,8 @@ int check_desc(const bimamba_desc* d)
         d->d_conv < 1)
         return BIMAMBA_ERR_BAD_SHAPE;
     if (d->d_inner % d->n_heads || d->n_heads % d->n_groups) return BIMAMBA_ERR_BAD_SHAPE;
-    if (d->time_chunks < 0 || d->reserved != 0) return BIMAMBA_ERR_BAD_SHAPE;
+    if (d->time_chunks < 0 || d->state_split < 0) return BIMAMBA_ERR_BAD_SHAPE;
+    if (d->state_split > 0 && !split_supported(d->d_state, d->state_split)) return BIMAMBA_ERR_UNSUPPORTED;
     if (d->batch > 65535) return BIMAMBA_ERR_UNSUPPORTED;
     if (d->io_dtype != BIMAMBA_F32 && d->io_dtype != BIMAMBA_BF16) return BIMAMBA_ERR_UNSUPPORTED;
     if (d->a_kind != BIMAMBA_A_PER_HEAD_STATE && d->a_kind != BIMAMBA_A_SCALAR_PER_HEAD) return BIMAMBA_ERR_UNSUPPORTED;
@@ -40,7 +51,29 @@ int check_desc(const bimamba_desc* d)
     return BIMAMBA_OK;
 }
 
-int pick_chunks(const bimamba_desc* d)
+long long waves_of(const bimamba_desc* d, int split)
+{
+    const int cpw = 64 / split;
+    return 2LL * d->batch * ((d->d_inner + cpw - 1) / cpw);
+}
+
+// Lanes per chain: spreading a chain's states over 2 or 4 lanes multiplies the number of waves without repeating the
+// decay exponentials (the per-token conv / gate work is repeated instead), so it is the first lever when the
+// (batch x channel x direction) chains alone leave SIMDs with fewer than two waves.
+int pick_split(const bimamba_desc* d)
+{
+    if (d->state_split > 0) return d->state_split;
+    int split = 1;
+    while (waves_of(d, split) < kTargetWaves && split < 4) {
+        int next = split * 2;
+        if (!split_supported(d->d_state, next)) next = split * 4;
+        if (next > 4 || !split_supported(d->d_state, next)) break;
+        split = next;
+    }
+    return split;
+}
+
+int pick_chunks(const bimamba_desc* d, int split)
 {
     const int L = d->seqlen;
     if (L <= 0) return 1;
@@ -48,9 +81,9 @@ int pick_chunks(const bimamba_desc* d)
     if (d->time_chunks > 0) {
         n = d->time_chunks;
     } else {
-        // Each extra segment re-evaluates the decay exponentials in a summary pass, so only split when the
-        // (batch x channel-tile x direction) chains cannot fill the chip on their own.
-        const long long waves = 2LL * d->batch * ((d->d_inner + 63) / 64);
+        // Each extra segment re-evaluates the decay exponentials in a summary pass, so only cut the sequence when
+        // chains and state splitting together cannot fill the chip.
+        const long long waves = waves_of(d, split);
         n = 1;
         if (waves > 0 && waves < kTargetWaves) n = (int)((kTargetWaves + waves - 1) / waves);
         const int max_by_len = L / 256 > 0 ? L / 256 : 1;  // keep segments at least 256 tokens long
@@ -63,7 +96,7 @@ int pick_chunks(const bimamba_desc* d)
 }
 
 struct Plan {
-    int nseg, seg_len;
+    int split, nseg, seg_len;
     bool two_bc;  // the two directions consume different prepared B|C buffers
     size_t off_bc[2], off_partial, off_carry, off_sumdt, total;
 };
@@ -71,7 +104,8 @@ struct Plan {
 Plan make_plan(const bimamba_desc* d, bool inputs_shared)
 {
     Plan p{};
-    p.nseg = pick_chunks(d);
+    p.split = pick_split(d);
+    p.nseg = pick_chunks(d, p.split);
     p.seg_len = d->seqlen > 0 ? (d->seqlen + p.nseg - 1) / p.nseg : 1;
     p.nseg = d->seqlen > 0 ? (d->seqlen + p.seg_len - 1) / p.seg_len : 1;
     p.two_bc = d->conv_bc || !inputs_shared;
@@ -138,19 +172,18 @@ bool same_inputs(const bimamba_inputs* a, const bimamba_inputs* b)
 
 TensorArg targ(const bimamba_tensor& t) { return TensorArg{t.ptr, (long long)t.stride_batch, (long long)t.stride_token}; }
 
-void launch_scan(const bimamba_desc* d, const SweepArgs& sa, const CarryArgs& ca, dim3 grid, hipStream_t st,
+void launch_scan(const bimamba_desc* d, int split, const SweepArgs& sa, const CarryArgs& ca, hipStream_t st,
                  hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     const int scalar_a = d->a_kind == BIMAMBA_A_SCALAR_PER_HEAD, bf16 = d->io_dtype == BIMAMBA_BF16;
-    switch (d->d_state) {
-        case 4: launch_scan_n4(scalar_a, bf16, sa, ca, grid, st, ev_start, ev_stop); break;
-        case 8: launch_scan_n8(scalar_a, bf16, sa, ca, grid, st, ev_start, ev_stop); break;
-        case 16: launch_scan_n16(scalar_a, bf16, sa, ca, grid, st, ev_start, ev_stop); break;
-        case 32: launch_scan_n32(scalar_a, bf16, sa, ca, grid, st, ev_start, ev_stop); break;
-        case 64: launch_scan_n64(scalar_a, bf16, sa, ca, grid, st, ev_start, ev_stop); break;
-        case 128: launch_scan_n128(scalar_a, bf16, sa, ca, grid, st, ev_start, ev_stop); break;
+#define BM_CASE(n, s) \
+    case (n) * 8 + (s): launch_scan_n##n##_s##s(scalar_a, bf16, sa, ca, d->batch, st, ev_start, ev_stop); break;
+    switch (d->d_state * 8 + split) {
+        BM_CASE(4, 1) BM_CASE(8, 1) BM_CASE(16, 1) BM_CASE(16, 2) BM_CASE(16, 4) BM_CASE(32, 1) BM_CASE(32, 2)
+        BM_CASE(32, 4) BM_CASE(64, 1) BM_CASE(64, 4) BM_CASE(128, 1) BM_CASE(128, 4)
         default: break;
     }
+#undef BM_CASE
 }
 
 int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* pb, const bimamba_inputs* in_f,
@@ -225,12 +258,12 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
         sa.G = d->n_groups; sa.K = d->d_conv; sa.nseg = plan.nseg; sa.seg_len = plan.seg_len; sa.tail_ch = tail_ch;
         sa.dt_softplus = d->dt_softplus; sa.d_per_head = d->d_kind == BIMAMBA_D_PER_HEAD;
         sa.separate = d->combine == BIMAMBA_COMBINE_SEPARATE;
+        sa.raw_partial = !sa.separate && same_tensor(in_f->z, in_b->z);
         CarryArgs ca{};
         ca.carry = sa.carry; ca.sumdt = sa.sumdt; ca.A[0] = pf->A; ca.A[1] = pb->A;
         ca.h_in = sa.h_in; ca.h_out = sa.h_out;
         ca.batch = d->batch; ca.nseg = plan.nseg; ca.Dn = d->d_inner; ca.P = sa.P;
-        const dim3 grid((unsigned)((d->d_inner + 63) / 64), (unsigned)plan.nseg, (unsigned)d->batch);
-        launch_scan(d, sa, ca, grid, st, probe_start, probe_stop);
+        launch_scan(d, plan.split, sa, ca, st, probe_start, probe_stop);
     } else if (block_variant && d->batch > 0 && h_out && h_out != h_in) {
         // empty block: the state passes through unchanged
         const size_t bytes = (size_t)d->batch * d->d_inner * d->d_state * sizeof(float);

@@ -1,12 +1,18 @@
 // Device code of the bidirectional Mamba mixer path for gfx950 (CDNA4, wave64).
 //
-// Mapping: one lane owns one channel of one direction and walks the sequence token by token with its d_state
-// recurrence values in registers; a wave covers 64 adjacent channels, so every per-token access of x / dt / z /
-// out is one contiguous run.  B_t and C_t are wave-uniform and arrive through scalar loads from an fp32 copy made
-// by prep_bc_kernel.  A workgroup holds the forward wave and the reverse wave of the same 64 channels.  For the
-// additive combine (eq. 6) the two waves meet in the middle of the segment: in the first half of its walk each
-// wave parks its gated output as an fp32 partial, in the second half it adds the partial the other wave parked
-// there and performs the single rounding to the I/O dtype.
+// Mapping.  A chain is one (direction, batch element, channel): it walks the sequence token by token with its
+// d_state recurrence values in registers.  S adjacent lanes share a chain, each holding d_state/S of the states
+// (S = 1, 2 or 4, chosen by the host so that the launch has enough waves to fill 1024 SIMDs); their partial dot
+// products C_t . h_t are summed with DPP lane swaps.  A wave therefore covers 64/S adjacent channels and every
+// per-token access of x / dt / z / out is one contiguous run, addressed as a wave-uniform row pointer plus a constant
+// lane offset.  A workgroup holds the forward wave and the reverse wave of the same channels.  For the additive
+// combine (eq. 6) the two waves meet in the middle of the segment: in the first half of its walk each wave parks
+// its output as an fp32 partial, in the second half it adds the partial the other wave parked there and performs the
+// single rounding to the I/O dtype.
+//
+// B_t and C_t come from an fp32 copy made by prep_bc_kernel.  With S = 1 they are wave-uniform and are fetched one
+// token ahead with scalar loads; with S > 1 each lane needs its own slice, so a tile of rows is staged through LDS
+// (private to the wave, no barrier) and read back one token ahead.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -14,6 +20,7 @@
 namespace bm {
 
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
 
 // Read-only for the whole kernel and wave-uniform: the constant address space lets the compiler fetch it with
 // scalar loads even when unrelated global stores sit between the loads.
@@ -46,6 +53,7 @@ struct SweepArgs {
     float* sumdt;         // [2][batch][nseg][Dn]
     int L, Dn, P, HG, G, K, nseg, seg_len, tail_ch;
     int dt_softplus, d_per_head, separate;
+    int raw_partial;      // both directions gate with the same z: park y ungated and gate once at the final store
 };
 
 struct IoF32 {
@@ -67,52 +75,126 @@ struct IoBF16 {
 
 __device__ __forceinline__ float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
 __device__ __forceinline__ float silu(float v) { return v * __builtin_amdgcn_rcpf(1.0f + fast_exp2(-kLog2e * v)); }
-__device__ __forceinline__ float softplus(float v) { return v > 20.0f ? v : log1pf(__expf(v)); }
+// softplus(v) = max(v, 0) + log1p(e), e = exp(-|v|) in (0, 1].  log1p(e) is taken as log(w) * e / (w - 1) with
+// w = fl(1 + e), which cancels the rounding of the sum and keeps full relative accuracy for small e.
+__device__ __forceinline__ float softplus(float v)
+{
+    const float e = fast_exp2(-kLog2e * fabsf(v));
+    const float w = 1.0f + e;
+    const float d = w - 1.0f;
+    const float l = d == 0.0f ? e : (__builtin_amdgcn_logf(w) * kLn2) * e * __builtin_amdgcn_rcpf(d);
+    return fmaxf(v, 0.0f) + l;
+}
+
+// Sum over the S adjacent lanes of a chain (S = 1, 2, 4); every lane ends up with the total.
+template <int S>
+__device__ __forceinline__ float sum_over_chain_lanes(float v)
+{
+    if (S >= 2) {  // quad_perm [1,0,3,2]
+        const int o = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true);
+        v += __int_as_float(o);
+    }
+    if (S >= 4) {  // quad_perm [2,3,0,1]
+        const int o = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true);
+        v += __int_as_float(o);
+    }
+    return v;
+}
 
 enum { kSweep = 0, kSummary = 1 };
-enum { kModePartial = 0, kModeFinalAdd = 1, kModeFinalOnly = 2, kModeNoOutput = 3 };
+// What a range of the walk does with its result:
+//   Partial      park g = y * SiLU(z)           PartialRaw   park y (gate later)
+//   FinalAdd     store g + partial              FinalAddRaw  store (y + partial) * SiLU(z)
+//   FinalOnly    store g (separate halves)      NoOutput     state only (segment summary)
+enum { kModePartial = 0, kModeFinalAdd = 1, kModeFinalOnly = 2, kModeNoOutput = 3, kModePartialRaw = 4, kModeFinalAddRaw = 5 };
+__host__ __device__ constexpr bool mode_reads_z(int m) { return m != kModeNoOutput && m != kModePartialRaw; }
+__host__ __device__ constexpr bool mode_reads_partial(int m) { return m == kModeFinalAdd || m == kModeFinalAddRaw; }
 
 constexpr int kTile = 8;  // tokens whose loads are in flight while the previous tile is being computed
 
-// Per-lane constants and running state of one (direction, channel) chain.
-template <int N, int AKIND, typename IO>
+// Per-lane constants and running state of one chain slice.  Row pointers are wave-uniform and advance by signed
+// per-token steps; ch / head are the lane's constant offsets into a row.
+template <int N, int S, int AKIND, typename IO>
 struct Chain {
     using T = typename IO::T;
-    float h[N];
-    float a2[AKIND == 0 ? N : 1];  // A * log2(e)
-    float w4[4];                   // conv taps, w4[3] on the current token
+    static constexpr int NS = N / S;
+    float h[NS];
+    float a2[AKIND == 0 ? NS : 1];  // A * log2(e)
+    float w4[4];                    // conv taps, w4[3] on the current token
     float cb, dval, dtb, sum_dt;
-    float xh[3];                   // previous raw x, xh[0] most recent
-    const T *xp, *zp, *dtp;        // running pointers at the current token
-    T* op;
-    float* pp;                     // running pointer into the partial buffer
-    uniform_ro_ptr bcp;            // uniform running pointer to this token's B|C row
-    long long xs, zs, dts, os, ps, bcs;  // signed per-token steps in elements
+    float xh[3];                    // previous raw x, xh[0] most recent
+    const T *xrow, *zrow, *dtrow;
+    T* orow;
+    float* prow;
+    const float* bcrow;             // this token's B|C row of the tile's group
+    long long xs, zs, dts, os, ps, bcs;
+    unsigned ch, head, sub;         // channel, head, slice index (lane % S)
 };
 
-template <int N, int AKIND, typename IO>
+template <typename IO>
 struct RawTile {
     typename IO::T x[kTile], z[kTile], dt[kTile];
     float part[kTile];
 };
 
-template <int N, int AKIND, typename IO, int MODE>
-__device__ __forceinline__ void load_tile(const Chain<N, AKIND, IO>& c, RawTile<N, AKIND, IO>& r)
+template <int N, int S, int AKIND, typename IO, int MODE>
+__device__ __forceinline__ void load_tile(const Chain<N, S, AKIND, IO>& c, long long ahead, RawTile<IO>& r)
 {
 #pragma unroll
     for (int i = 0; i < kTile; i++) {
-        r.x[i] = c.xp[i * c.xs];
-        r.dt[i] = c.dtp[i * c.dts];
-        if (MODE != kModeNoOutput) r.z[i] = c.zp[i * c.zs];
-        if (MODE == kModeFinalAdd) r.part[i] = c.pp[i * c.ps];
+        r.x[i] = (c.xrow + (ahead + i) * c.xs)[c.ch];
+        r.dt[i] = (c.dtrow + (ahead + i) * c.dts)[c.head];
+        if (mode_reads_z(MODE)) r.z[i] = (c.zrow + (ahead + i) * c.zs)[c.ch];
+        if (mode_reads_partial(MODE)) r.part[i] = (c.prow + (ahead + i) * c.ps)[c.ch];
     }
 }
 
-// One token of one chain: conv + SiLU, discretise, N state updates, skip term, gate, output.
-template <int N, int AKIND, typename IO, int MODE>
-__device__ __forceinline__ void token_step(Chain<N, AKIND, IO>& c, typename IO::T xraw, typename IO::T dtraw,
-                                           typename IO::T zraw, float part, bool softplus_dt)
+// One token's B (first NS) and C (last NS) values for this lane's state slice.
+template <int NS>
+struct BcRow {
+    float v[2 * NS];
+};
+
+// S = 1 rows of up to 16 states are fetched one token ahead into scalar registers; longer rows are read where used.
+template <int N, int S>
+constexpr bool kBcScalarAhead = (S == 1 && N <= 16);
+
+template <int N>
+__device__ __forceinline__ void load_bc_scalar(const float* p, BcRow<N>& r)
 {
+    uniform_ro_ptr q = (uniform_ro_ptr)p;
+#pragma unroll
+    for (int n = 0; n < 2 * N; n++) r.v[n] = q[n];
+}
+
+// Lane-private slice straight from global memory (tokens outside whole tiles).
+template <int N, int S>
+__device__ __forceinline__ void load_bc_direct(const float* row, unsigned sub, BcRow<N / S>& r)
+{
+    constexpr int NS = N / S;
+    const float4* b4 = reinterpret_cast<const float4*>(row + sub * NS);
+    const float4* c4 = reinterpret_cast<const float4*>(row + N + sub * NS);
+#pragma unroll
+    for (int j = 0; j < NS / 4; j++) {
+        const float4 bv = b4[j], cv = c4[j];
+        r.v[4 * j] = bv.x; r.v[4 * j + 1] = bv.y; r.v[4 * j + 2] = bv.z; r.v[4 * j + 3] = bv.w;
+        r.v[NS + 4 * j] = cv.x; r.v[NS + 4 * j + 1] = cv.y; r.v[NS + 4 * j + 2] = cv.z; r.v[NS + 4 * j + 3] = cv.w;
+    }
+}
+
+// Lane-private slice of token i of a staged tile in LDS ([kTile][2N] floats).
+template <int N, int S>
+__device__ __forceinline__ void load_bc_lds(const float* tile, int i, unsigned sub, BcRow<N / S>& r)
+{
+    load_bc_direct<N, S>(tile + i * 2 * N, sub, r);
+}
+
+// One token of one chain slice: conv + SiLU, discretise, state updates, skip term, gate, output.
+template <int N, int S, int AKIND, typename IO, int MODE>
+__device__ __forceinline__ void token_step(Chain<N, S, AKIND, IO>& c, typename IO::T xraw, typename IO::T dtraw,
+                                           typename IO::T zraw, float part, bool softplus_dt, const BcRow<N / S>& row)
+{
+    constexpr int NS = N / S;
     const float x0 = IO::cvt(xraw);
     float pre = c.cb;
     pre = fmaf(c.w4[0], c.xh[2], pre);
@@ -126,94 +208,158 @@ __device__ __forceinline__ void token_step(Chain<N, AKIND, IO>& c, typename IO::
     float delta = IO::cvt(dtraw);
     if (softplus_dt) delta = softplus(delta + c.dtb);
     const float u = delta * xc;
-    float y = c.dval * xc;
-    uniform_ro_ptr bc = c.bcp;
+    float y = 0.0f;
+    uniform_ro_ptr bcmem = (uniform_ro_ptr)c.bcrow;  // only for S = 1 rows too long to prefetch
+    constexpr bool kFromMem = (S == 1 && N > 16);
+    auto bc = [&](int n) -> float { return kFromMem ? bcmem[n < NS ? n : n - NS + N] : row.v[n]; };
     if (AKIND == 0) {
 #pragma unroll
-        for (int n = 0; n < N; n++) {
+        for (int n = 0; n < NS; n++) {
             const float a = fast_exp2(delta * c.a2[n]);
-            c.h[n] = fmaf(a, c.h[n], u * bc[n]);
-            if (MODE != kModeNoOutput) y = fmaf(bc[N + n], c.h[n], y);
+            c.h[n] = fmaf(a, c.h[n], u * bc(n));
+            if (MODE != kModeNoOutput) y = fmaf(bc(NS + n), c.h[n], y);
         }
     } else {
         const float a = fast_exp2(delta * c.a2[0]);
 #pragma unroll
-        for (int n = 0; n < N; n++) {
-            c.h[n] = fmaf(a, c.h[n], u * bc[n]);
-            if (MODE != kModeNoOutput) y = fmaf(bc[N + n], c.h[n], y);
+        for (int n = 0; n < NS; n++) {
+            c.h[n] = fmaf(a, c.h[n], u * bc(n));
+            if (MODE != kModeNoOutput) y = fmaf(bc(NS + n), c.h[n], y);
         }
     }
     if (MODE == kModeNoOutput) {
         c.sum_dt += delta;
     } else {
-        const float g = y * silu(IO::cvt(zraw));
-        if (MODE == kModePartial) {
-            *c.pp = g;
+        y = sum_over_chain_lanes<S>(y);
+        y = fmaf(c.dval, xc, y);
+        if (MODE == kModePartialRaw) {
+            c.prow[c.ch] = y;
+        } else if (MODE == kModeFinalAddRaw) {
+            IO::st(c.orow + c.ch, (y + part) * silu(IO::cvt(zraw)));
         } else {
-            const float o = MODE == kModeFinalAdd ? g + part : g;
-            IO::st(c.op, o);
+            const float g = y * silu(IO::cvt(zraw));
+            if (MODE == kModePartial) c.prow[c.ch] = g;
+            else IO::st(c.orow + c.ch, MODE == kModeFinalAdd ? g + part : g);
         }
     }
-    c.xp += c.xs;
-    c.dtp += c.dts;
-    c.zp += c.zs;
-    c.op += c.os;
-    c.pp += c.ps;
-    c.bcp += c.bcs;
+    c.xrow += c.xs;
+    c.dtrow += c.dts;
+    c.zrow += c.zs;
+    c.orow += c.os;
+    c.prow += c.ps;
+    c.bcrow += c.bcs;
 }
 
-// Tokens [0, count) of the chain's walk from its current position, tile by tile with the next tile's loads in flight.
-template <int N, int AKIND, typename IO, int MODE>
-__device__ __forceinline__ void run_range(Chain<N, AKIND, IO>& c, int count, bool softplus_dt)
+// Tokens [0, count) of the chain's walk from its current position, tile by tile with the next tile's loads in flight
+// and the next token's B|C slice requested before the current token is computed.  lds: this wave's private staging
+// area of 2 * kTile * 2N floats (S > 1 only).
+template <int N, int S, int AKIND, typename IO, int MODE>
+__device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, bool softplus_dt, float* lds, int lane)
 {
-    using Tile = RawTile<N, AKIND, IO>;
+    constexpr int NS = N / S;
+    constexpr int kRowF4 = 2 * N / 4;              // float4s per B|C row
+    constexpr int kStage = (kTile * kRowF4 + 63) / 64;  // float4s each lane moves per staged tile
+    using Tile = RawTile<IO>;
+    if (count <= 0) return;
     int done = 0;
     if (count >= kTile) {
         Tile cur;
-        load_tile<N, AKIND, IO, MODE>(c, cur);
+        load_tile<N, S, AKIND, IO, MODE>(c, 0, cur);
+        BcRow<NS> row;
+        float4 stage[kStage];
+        int buf = 0;
+        // lane q moves float4 number (j*64 + q) of the tile: token (scan order) idx / kRowF4, column idx % kRowF4
+        auto stage_load = [&](long long ahead) {
+#pragma unroll
+            for (int j = 0; j < kStage; j++) {
+                const int idx = j * 64 + lane;
+                if (kTile * kRowF4 % 64 == 0 || idx < kTile * kRowF4)
+                    stage[j] = *reinterpret_cast<const float4*>(c.bcrow + (ahead + idx / kRowF4) * c.bcs + (idx % kRowF4) * 4);
+            }
+        };
+        auto stage_store = [&](int which) {
+#pragma unroll
+            for (int j = 0; j < kStage; j++) {
+                const int idx = j * 64 + lane;
+                if (kTile * kRowF4 % 64 == 0 || idx < kTile * kRowF4)
+                    *reinterpret_cast<float4*>(lds + which * (kTile * 2 * N) + idx * 4) = stage[j];
+            }
+            __builtin_amdgcn_wave_barrier();  // other lanes of this wave read these rows next; LDS keeps wave order
+        };
+        if constexpr (S > 1) {
+            stage_load(0);
+            stage_store(0);
+            load_bc_lds<N, S>(lds, 0, c.sub, row);
+        } else if constexpr (kBcScalarAhead<N, S>) {
+            load_bc_scalar<N>(c.bcrow, row);
+        }
         while (true) {
             const bool more = done + 2 * kTile <= count;
             Tile nxt;
             if (more) {
-                // the next tile starts kTile tokens ahead of the running pointers
-                Chain<N, AKIND, IO> ahead = c;
-                ahead.xp += kTile * c.xs;
-                ahead.dtp += kTile * c.dts;
-                ahead.zp += kTile * c.zs;
-                ahead.pp += kTile * c.ps;
-                load_tile<N, AKIND, IO, MODE>(ahead, nxt);
+                load_tile<N, S, AKIND, IO, MODE>(c, kTile, nxt);
+                if constexpr (S > 1) stage_load(kTile);
             }
+            const float* tile_bc = lds + buf * (kTile * 2 * N);
 #pragma unroll
-            for (int i = 0; i < kTile; i++)
-                token_step<N, AKIND, IO, MODE>(c, cur.x[i], cur.dt[i], cur.z[i], cur.part[i], softplus_dt);
+            for (int i = 0; i < kTile; i++) {
+                BcRow<NS> row_next;
+                if constexpr (S > 1) {
+                    if (i + 1 < kTile) load_bc_lds<N, S>(tile_bc, i + 1, c.sub, row_next);
+                } else if constexpr (kBcScalarAhead<N, S>) {
+                    // never read past the walk's last token: the row after it may lie outside the buffer
+                    load_bc_scalar<N>(done + i + 1 < count ? c.bcrow + c.bcs : c.bcrow, row_next);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                token_step<N, S, AKIND, IO, MODE>(c, cur.x[i], cur.dt[i], cur.z[i], cur.part[i], softplus_dt, row);
+                if constexpr (S > 1) {
+                    if (i + 1 < kTile) row = row_next;
+                } else if constexpr (kBcScalarAhead<N, S>) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    row = row_next;
+                }
+            }
             done += kTile;
             if (!more) break;
             cur = nxt;
+            if constexpr (S > 1) {
+                buf ^= 1;
+                stage_store(buf);
+                load_bc_lds<N, S>(lds + buf * (kTile * 2 * N), 0, c.sub, row);
+            }
         }
     }
     for (; done < count; done++) {
-        typename IO::T xr = *c.xp, dr = *c.dtp, zr = 0;
+        typename IO::T xr = c.xrow[c.ch], dr = c.dtrow[c.head], zr = 0;
         float part = 0.0f;
-        if (MODE != kModeNoOutput) zr = *c.zp;
-        if (MODE == kModeFinalAdd) part = *c.pp;
-        token_step<N, AKIND, IO, MODE>(c, xr, dr, zr, part, softplus_dt);
+        if (mode_reads_z(MODE)) zr = c.zrow[c.ch];
+        if (mode_reads_partial(MODE)) part = c.prow[c.ch];
+        BcRow<NS> row;
+        if constexpr (S > 1) load_bc_direct<N, S>(c.bcrow, c.sub, row);
+        else if constexpr (kBcScalarAhead<N, S>) load_bc_scalar<N>(c.bcrow, row);
+        token_step<N, S, AKIND, IO, MODE>(c, xr, dr, zr, part, softplus_dt, row);
     }
 }
 
-// grid (ceil(Dn/64), nseg, batch), block 128: wave 0 walks left-to-right, wave 1 right-to-left.
-template <int N, int AKIND, typename IO, int KIND>
+// grid (ceil(Dn / (64/S)), nseg, batch), block 128: wave 0 walks left-to-right, wave 1 right-to-left.
+template <int N, int S, int AKIND, typename IO, int KIND>
 __global__ __launch_bounds__(128) void sweep_kernel(const SweepArgs a)
 {
     using T = typename IO::T;
+    constexpr int NS = N / S;
+    constexpr int kCpw = 64 / S;  // channels per wave
+    __shared__ __attribute__((aligned(16))) float lds_all[S > 1 ? 2 * 2 * kTile * 2 * N : 4];
     const int lane = threadIdx.x & 63;
     const int s = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    float* lds = lds_all + (S > 1 ? s * (2 * kTile * 2 * N) : 0);
     const DirArgs& da = a.dir[s];
     const int b = blockIdx.z, seg = blockIdx.y;
     // Lanes past the last channel shadow channel Dn-1: they load the same inputs, compute the same values and
     // store them to the same addresses, so no lane needs masking anywhere below.
-    const int ch = min((int)(blockIdx.x * 64 + lane), a.Dn - 1);
+    const int ch = min((int)(blockIdx.x * kCpw + lane / S), a.Dn - 1);
+    const int sub = lane % S;
     const int head = ch / a.P;
-    const int grp = (int)((blockIdx.x * 64) / a.P) / a.HG;  // uniform: a tile never straddles two B/C groups
+    const int grp = (int)((blockIdx.x * kCpw) / a.P) / a.HG;  // uniform: a tile never straddles two B/C groups
     const int t0 = seg * a.seg_len;
     const int t1 = min(a.L, t0 + a.seg_len);
     const int len = t1 - t0;
@@ -221,7 +367,10 @@ __global__ __launch_bounds__(128) void sweep_kernel(const SweepArgs a)
     const int step = s == 0 ? 1 : -1;
     const int tstart = s == 0 ? t0 : t1 - 1;
 
-    Chain<N, AKIND, IO> c;
+    Chain<N, S, AKIND, IO> c;
+    c.ch = ch;
+    c.head = head;
+    c.sub = sub;
     // per-lane constants
     {
         const int K = a.K;
@@ -232,7 +381,7 @@ __global__ __launch_bounds__(128) void sweep_kernel(const SweepArgs a)
         c.dtb = (a.dt_softplus && da.dt_bias) ? da.dt_bias[head] : 0.0f;
         if (AKIND == 0) {
 #pragma unroll
-            for (int n = 0; n < N; n++) c.a2[n] = da.A[(size_t)head * N + n] * kLog2e;
+            for (int n = 0; n < NS; n++) c.a2[n] = da.A[(size_t)head * N + sub * NS + n] * kLog2e;
         } else {
             c.a2[0] = da.A[head] * kLog2e;
         }
@@ -242,11 +391,11 @@ __global__ __launch_bounds__(128) void sweep_kernel(const SweepArgs a)
     {
         const float* src = nullptr;
         if (KIND == kSweep) {
-            if (a.nseg > 1) src = a.carry + ((((size_t)s * gridDim.z + b) * a.nseg + seg) * a.Dn + ch) * N;
-            else if (s == 0 && a.h_in) src = a.h_in + ((size_t)b * a.Dn + ch) * N;
+            if (a.nseg > 1) src = a.carry + ((((size_t)s * gridDim.z + b) * a.nseg + seg) * a.Dn + ch) * N + sub * NS;
+            else if (s == 0 && a.h_in) src = a.h_in + ((size_t)b * a.Dn + ch) * N + sub * NS;
         }
 #pragma unroll
-        for (int n = 0; n < N; n++) c.h[n] = src ? src[n] : 0.0f;
+        for (int n = 0; n < NS; n++) c.h[n] = src ? src[n] : 0.0f;
     }
     // conv history: the K-1 raw tokens that precede the walk's first token in scan order
     {
@@ -263,45 +412,45 @@ __global__ __launch_bounds__(128) void sweep_kernel(const SweepArgs a)
             c.xh[i] = v;
         }
     }
-    // running pointers and signed steps
+    // wave-uniform row pointers at the walk's first token, and signed per-token steps
     c.xs = step * da.x.st;
     c.zs = step * da.z.st;
     c.dts = step * da.dt.st;
     c.os = step * a.out_st;
     c.ps = step * (long long)a.Dn;
     c.bcs = step * (long long)(a.G * 2 * N);
-    c.xp = (const T*)da.x.p + (size_t)b * da.x.sb + (long long)tstart * da.x.st + ch;
-    c.zp = (const T*)da.z.p + (size_t)b * da.z.sb + (long long)tstart * da.z.st + ch;
-    c.dtp = (const T*)da.dt.p + (size_t)b * da.dt.sb + (long long)tstart * da.dt.st + head;
-    c.op = (T*)a.out + (size_t)b * a.out_sb + (long long)tstart * a.out_st + ch + (a.separate ? s * a.Dn : 0);
-    c.pp = a.partial + ((size_t)b * a.L + tstart) * a.Dn + ch;
-    c.bcp = (uniform_ro_ptr)(da.bc + (((size_t)b * a.L + tstart) * a.G + grp) * (2 * N));
+    c.xrow = (const T*)da.x.p + (size_t)b * da.x.sb + (long long)tstart * da.x.st;
+    c.zrow = (const T*)da.z.p + (size_t)b * da.z.sb + (long long)tstart * da.z.st;
+    c.dtrow = (const T*)da.dt.p + (size_t)b * da.dt.sb + (long long)tstart * da.dt.st;
+    c.orow = (T*)a.out + (size_t)b * a.out_sb + (long long)tstart * a.out_st + (a.separate ? s * a.Dn : 0);
+    c.prow = a.partial + ((size_t)b * a.L + tstart) * a.Dn;
+    c.bcrow = da.bc + (((size_t)b * a.L + tstart) * a.G + grp) * (2 * N);
     const bool sp = a.dt_softplus != 0;
 
     if (KIND == kSummary) {
-        run_range<N, AKIND, IO, kModeNoOutput>(c, len, sp);
-        {
-            float* dst = a.carry + ((((size_t)s * gridDim.z + b) * a.nseg + seg) * a.Dn + ch) * N;
+        run_range<N, S, AKIND, IO, kModeNoOutput>(c, len, sp, lds, lane);
+        float* dst = a.carry + ((((size_t)s * gridDim.z + b) * a.nseg + seg) * a.Dn + ch) * N + sub * NS;
 #pragma unroll
-            for (int n = 0; n < N; n++) dst[n] = c.h[n];
-            a.sumdt[(((size_t)s * gridDim.z + b) * a.nseg + seg) * a.Dn + ch] = c.sum_dt;
-        }
+        for (int n = 0; n < NS; n++) dst[n] = c.h[n];
+        a.sumdt[(((size_t)s * gridDim.z + b) * a.nseg + seg) * a.Dn + ch] = c.sum_dt;
         return;
     }
 
     if (a.separate) {
-        run_range<N, AKIND, IO, kModeFinalOnly>(c, len, sp);
+        run_range<N, S, AKIND, IO, kModeFinalOnly>(c, len, sp, lds, lane);
     } else {
         // forward parks [t0, m), reverse parks [m, t1); then each finishes the other's half
         const int n_first = s == 0 ? (len + 1) / 2 : len / 2;
-        run_range<N, AKIND, IO, kModePartial>(c, n_first, sp);
+        if (a.raw_partial) run_range<N, S, AKIND, IO, kModePartialRaw>(c, n_first, sp, lds, lane);
+        else run_range<N, S, AKIND, IO, kModePartial>(c, n_first, sp, lds, lane);
         __syncthreads();  // workgroup-scope release/acquire: the other wave's partials are visible from here on
-        run_range<N, AKIND, IO, kModeFinalAdd>(c, len - n_first, sp);
+        if (a.raw_partial) run_range<N, S, AKIND, IO, kModeFinalAddRaw>(c, len - n_first, sp, lds, lane);
+        else run_range<N, S, AKIND, IO, kModeFinalAdd>(c, len - n_first, sp, lds, lane);
     }
     if (s == 0 && a.nseg == 1 && a.h_out) {
-        float* dst = a.h_out + ((size_t)b * a.Dn + ch) * N;
+        float* dst = a.h_out + ((size_t)b * a.Dn + ch) * N + sub * NS;
 #pragma unroll
-        for (int n = 0; n < N; n++) dst[n] = c.h[n];
+        for (int n = 0; n < NS; n++) dst[n] = c.h[n];
     }
 }
 

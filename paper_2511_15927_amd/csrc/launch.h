@@ -1,16 +1,22 @@
-// Host-callable launchers of the per-d_state scan kernels (defined in scan_inst.hip, one object per d_state).
+// Host-callable launchers of the scan kernels (defined in scan_inst.hip, one object per (d_state, lanes-per-chain)).
 #pragma once
 #include "kernels.h"
 
 namespace bm {
-#define BM_DECLARE_SCAN(n) \
-    void launch_scan_n##n(int a_scalar_per_head, int io_bf16, const SweepArgs& sa, const CarryArgs& ca, dim3 grid, hipStream_t st, \
-                          hipEvent_t ev_start, hipEvent_t ev_stop);
-BM_DECLARE_SCAN(4)
-BM_DECLARE_SCAN(8)
-BM_DECLARE_SCAN(16)
-BM_DECLARE_SCAN(32)
-BM_DECLARE_SCAN(64)
-BM_DECLARE_SCAN(128)
+#define BM_DECLARE_SCAN(n, s)                                                                                      \
+    void launch_scan_n##n##_s##s(int a_scalar_per_head, int io_bf16, const SweepArgs& sa, const CarryArgs& ca,     \
+                                 int batch, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop);
+BM_DECLARE_SCAN(4, 1)
+BM_DECLARE_SCAN(8, 1)
+BM_DECLARE_SCAN(16, 1)
+BM_DECLARE_SCAN(16, 2)
+BM_DECLARE_SCAN(16, 4)
+BM_DECLARE_SCAN(32, 1)
+BM_DECLARE_SCAN(32, 2)
+BM_DECLARE_SCAN(32, 4)
+BM_DECLARE_SCAN(64, 1)
+BM_DECLARE_SCAN(64, 4)
+BM_DECLARE_SCAN(128, 1)
+BM_DECLARE_SCAN(128, 4)
 #undef BM_DECLARE_SCAN
 }  // namespace bm

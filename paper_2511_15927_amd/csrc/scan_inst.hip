@@ -1,40 +1,42 @@
-// Instantiations of the scan kernels for one d_state (BM_N), compiled once per supported state size so the
-// translation units build in parallel.
+// Instantiations of the scan kernels for one d_state (BM_N) and one lanes-per-chain factor (BM_S), compiled once per
+// supported pair so the translation units build in parallel.
 #include "kernels.h"
 #include "launch.h"
 
-#ifndef BM_N
-#error "compile with -DBM_N=<d_state>"
+#if !defined(BM_N) || !defined(BM_S)
+#error "compile with -DBM_N=<d_state> -DBM_S=<lanes per chain>"
 #endif
 
 namespace bm {
 
 template <int AKIND, typename IO>
-static void launch_one(const SweepArgs& sa, const CarryArgs& ca, dim3 grid, hipStream_t st, hipEvent_t ev_start,
+static void launch_one(const SweepArgs& sa, const CarryArgs& ca, int batch, hipStream_t st, hipEvent_t ev_start,
                        hipEvent_t ev_stop)
 {
+    constexpr int kCpw = 64 / BM_S;
+    const dim3 grid((unsigned)((sa.Dn + kCpw - 1) / kCpw), (unsigned)sa.nseg, (unsigned)batch);
     if (sa.nseg > 1) {
-        hipLaunchKernelGGL((sweep_kernel<BM_N, AKIND, IO, kSummary>), grid, dim3(128), 0, st, sa);
+        hipLaunchKernelGGL((sweep_kernel<BM_N, BM_S, AKIND, IO, kSummary>), grid, dim3(128), 0, st, sa);
         const long long threads = 2LL * ca.batch * ca.Dn;
         hipLaunchKernelGGL((carry_kernel<BM_N, AKIND>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, ca);
     }
     if (ev_start) (void)hipEventRecord(ev_start, st);
-    hipLaunchKernelGGL((sweep_kernel<BM_N, AKIND, IO, kSweep>), grid, dim3(128), 0, st, sa);
+    hipLaunchKernelGGL((sweep_kernel<BM_N, BM_S, AKIND, IO, kSweep>), grid, dim3(128), 0, st, sa);
     if (ev_stop) (void)hipEventRecord(ev_stop, st);
 }
 
-#define BM_CAT2(a, b) a##b
-#define BM_CAT(a, b) BM_CAT2(a, b)
+#define BM_CAT4(a, b, c, d) a##b##c##d
+#define BM_NAME(n, s) BM_CAT4(launch_scan_n, n, _s, s)
 
-void BM_CAT(launch_scan_n, BM_N)(int a_scalar_per_head, int io_bf16, const SweepArgs& sa, const CarryArgs& ca, dim3 grid,
-                                 hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop)
+void BM_NAME(BM_N, BM_S)(int a_scalar_per_head, int io_bf16, const SweepArgs& sa, const CarryArgs& ca, int batch,
+                         hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     if (a_scalar_per_head) {
-        if (io_bf16) launch_one<1, IoBF16>(sa, ca, grid, st, ev_start, ev_stop);
-        else launch_one<1, IoF32>(sa, ca, grid, st, ev_start, ev_stop);
+        if (io_bf16) launch_one<1, IoBF16>(sa, ca, batch, st, ev_start, ev_stop);
+        else launch_one<1, IoF32>(sa, ca, batch, st, ev_start, ev_stop);
     } else {
-        if (io_bf16) launch_one<0, IoBF16>(sa, ca, grid, st, ev_start, ev_stop);
-        else launch_one<0, IoF32>(sa, ca, grid, st, ev_start, ev_stop);
+        if (io_bf16) launch_one<0, IoBF16>(sa, ca, batch, st, ev_start, ev_stop);
+        else launch_one<0, IoF32>(sa, ca, batch, st, ev_start, ev_stop);
     }
 }
 

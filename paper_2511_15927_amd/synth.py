@@ -22,12 +22,12 @@ BASE_SEED = 20251115
 
 def mixer_cfg(batch, seqlen, d_inner, d_state=16, n_heads=None, n_groups=1, d_conv=4, io="bf16",
               a_kind=A_PER_HEAD_STATE, d_kind=D_PER_CHANNEL, dt_softplus=0, conv_bc=0, combine=COMBINE_ADD,
-              time_chunks=0):
+              time_chunks=0, state_split=0):
     """Shape/mode descriptor as a plain dict (keys mirror the C descriptor)."""
     return dict(batch=batch, seqlen=seqlen, d_inner=d_inner, d_state=d_state,
                 n_heads=d_inner if n_heads is None else n_heads, n_groups=n_groups, d_conv=d_conv, io=io,
                 a_kind=a_kind, d_kind=d_kind, dt_softplus=dt_softplus, conv_bc=conv_bc, combine=combine,
-                time_chunks=time_chunks)
+                time_chunks=time_chunks, state_split=state_split)
 
 
 def m2_cfg(batch, seqlen, d_inner, headdim=64, d_state=128, io="bf16", **kw):

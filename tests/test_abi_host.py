@@ -64,7 +64,7 @@ def test_null_and_shape_errors_are_decided_on_the_host():
     ("struct_size", 8, -2), ("batch", -1, -2), ("seqlen", -5, -2), ("d_inner", 0, -2), ("n_heads", 3, -2),
     ("n_groups", 5, -2), ("d_state", 12, -3), ("d_conv", 5, -3), ("d_conv", 0, -2), ("io_dtype", 7, -3),
     ("a_kind", 2, -3), ("d_kind", 9, -3), ("combine", 2, -3), ("dt_softplus", 2, -3), ("conv_bc", -1, -3),
-    ("time_chunks", -1, -2), ("reserved", 1, -2),
+    ("time_chunks", -1, -2), ("state_split", -1, -2), ("state_split", 3, -3), ("state_split", 8, -3),
 ])
 def test_descriptor_validation(field, value, code):
     cfg, desc, p, inp, out = good()
@@ -82,9 +82,9 @@ def test_group_tiling_rule():
 
 def test_workspace_and_chunk_planning():
     d1 = bd.make_desc(synth.CONFIGS["headline"])
-    assert bd.bimamba_time_chunks(d1) == 1                       # 1024 chains-of-64 already fill the chip
+    assert bd.bimamba_time_chunks(d1) == 1                       # chains x 2 lanes per chain already fill the chip
     d2 = bd.make_desc(synth.CONFIGS["cfg2"])
-    assert bd.bimamba_time_chunks(d2) == 8                       # batch 1: the sequence is cut to fill it
+    assert bd.bimamba_time_chunks(d2) == 4                       # batch 1: 4 lanes per chain, then the sequence is cut
     assert bd.bimamba_time_chunks(bd.make_desc(synth.CONFIGS["cfg3_block"])) == 1
     assert bd.bimamba_time_chunks(bd.make_desc(synth.mixer_cfg(1, 100, 64, time_chunks=7))) == 7
     assert bd.bimamba_time_chunks(bd.make_desc(synth.mixer_cfg(1, 5, 64, time_chunks=7))) == 5

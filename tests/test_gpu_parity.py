@@ -101,6 +101,18 @@ def test_time_chunking_matches_oracle(gpu, oracle, chunks):
     check_fwd(gpu, oracle, m2, 601)
 
 
+@pytest.mark.parametrize("N,split", [(16, 1), (16, 2), (16, 4), (32, 1), (32, 2), (32, 4), (64, 1), (64, 4), (128, 1), (128, 4)])
+def test_lanes_per_chain(gpu, oracle, N, split):
+    """Every supported way of spreading a chain's states over lanes, on ragged shapes, chunked and not."""
+    for io, chunks, L in (("f32", 1, 77), ("bf16", 3, 131), ("f32", 2, 16)):
+        cfg = synth.mixer_cfg(2, L, 100, d_state=N, io=io, time_chunks=chunks, state_split=split)
+        check_fwd(gpu, oracle, cfg, 900 + N + split, random_a=True)
+    m2 = synth.m2_cfg(2, 70, 128, headdim=32, d_state=N, io="f32", state_split=split, time_chunks=2)
+    check_fwd(gpu, oracle, m2, 950 + N + split, untied=True)
+    sep = synth.mixer_cfg(1, 45, 40, d_state=N, io="f32", combine=1, state_split=split)
+    check_fwd(gpu, oracle, sep, 970 + N + split, random_a=True, untied=True)
+
+
 def test_strided_views_of_one_projection(gpu, oracle):
     """x, z, dt, B, C as column slices of one [Bt, L, D_in] buffer (channel stride 1, token stride D_in)."""
     from paper_2511_15927_amd import binding as bd
