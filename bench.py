@@ -28,6 +28,8 @@ def parse():
     ap.add_argument("--general-a", action="store_true", help="draw A with no structure across states")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=2, help="batch elements the oracle is timed on")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run three 1 GiB device-to-device copies (a known-size reference for HBM counters)")
     return ap.parse_args()
 
 
@@ -56,6 +58,16 @@ def main():
     from paper_2511_15927_amd import shapes, synth
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read, 1 GiB written per copy
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "3 x copy of 1 GiB", "bytes_read_per_copy": src.numel() * 4,
+                          "bytes_written_per_copy": src.numel() * 4}))
+        return
     bd.lib()  # fail loudly if the HIP library is not built
     cfg = dict(synth.CONFIGS[args.workload])
     seed = synth.config_seed(9)

@@ -341,6 +341,18 @@ __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, 
     }
 }
 
+// Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own L2.  With S lanes per chain
+// a wave's row accesses cover only 1/S of a 128-byte line (bf16), so the S channel tiles that share a line are
+// given to workgroups 8 apart: same XCD, dispatched together, and the line is fetched from HBM once.  Within each
+// group of 8*S workgroups this is a permutation of the tiles; a ragged last group keeps the identity.
+template <int S>
+__device__ __forceinline__ unsigned xcd_aware_tile(unsigned g, unsigned n)
+{
+    constexpr unsigned kGroup = 8 * S;
+    if (S == 1 || g >= n / kGroup * kGroup) return g;
+    return g / kGroup * kGroup + (g % 8) * S + (g / 8) % S;
+}
+
 // grid (ceil(Dn / (64/S)), nseg, batch), block 128: wave 0 walks left-to-right, wave 1 right-to-left.
 template <int N, int S, int AKIND, typename IO, int KIND>
 __global__ __launch_bounds__(128) void sweep_kernel(const SweepArgs a)
@@ -356,10 +368,11 @@ __global__ __launch_bounds__(128) void sweep_kernel(const SweepArgs a)
     const int b = blockIdx.z, seg = blockIdx.y;
     // Lanes past the last channel shadow channel Dn-1: they load the same inputs, compute the same values and
     // store them to the same addresses, so no lane needs masking anywhere below.
-    const int ch = min((int)(blockIdx.x * kCpw + lane / S), a.Dn - 1);
+    const int tile = xcd_aware_tile<S>(blockIdx.x, gridDim.x);
+    const int ch = min((int)(tile * kCpw + lane / S), a.Dn - 1);
     const int sub = lane % S;
     const int head = ch / a.P;
-    const int grp = (int)((blockIdx.x * kCpw) / a.P) / a.HG;  // uniform: a tile never straddles two B/C groups
+    const int grp = (int)((tile * kCpw) / a.P) / a.HG;  // uniform: a tile never straddles two B/C groups
     const int t0 = seg * a.seg_len;
     const int t1 = min(a.L, t0 + a.seg_len);
     const int len = t1 - t0;
