@@ -29,6 +29,16 @@ def sources():
     return [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC))] + [os.path.join(ROOT, "include", "bimamba.h")]
 
 
+def newest_dep(src, newest_all):
+    """Modification time an object must beat: its source and the headers that source includes."""
+    text = open(src).read()
+    deps = [src, os.path.join(ROOT, "include", "bimamba.h")]
+    for h in ("kernels.h", "launch.h", "ssd_kernels.h"):
+        if h in text or (h == "kernels.h"):
+            deps.append(os.path.join(CSRC, h))
+    return max(os.path.getmtime(p) for p in deps)
+
+
 def build(force: bool = True, jobs: int = 8):
     if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= max(os.path.getmtime(p) for p in sources()):
         return LIB
@@ -37,7 +47,10 @@ def build(force: bool = True, jobs: int = 8):
     for n, s in VARIANTS:
         units.append((os.path.join(CSRC, "scan_inst.hip"), os.path.join(OBJ, "scan_n%d_s%d.o" % (n, s)),
                       ["-DBM_N=%d" % n, "-DBM_S=%d" % s]))
-    cmds = [["hipcc"] + FLAGS + extra + ["-c", src, "-o", obj] for src, obj, extra in units]
+    units.append((os.path.join(CSRC, "ssd_inst.hip"), os.path.join(OBJ, "ssd_inst.o"), []))
+    newest = max(os.path.getmtime(p) for p in sources())
+    todo = [u for u in units if force or not os.path.exists(u[1]) or os.path.getmtime(u[1]) < newest_dep(u[0], newest)]
+    cmds = [["hipcc"] + FLAGS + extra + ["-c", src, "-o", obj] for src, obj, extra in todo]
     with ThreadPoolExecutor(max_workers=max(1, min(jobs, len(cmds)))) as ex:
         logs = list(ex.map(_run, cmds))
     logs.append(_run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + [u[1] for u in units]))
@@ -48,4 +61,5 @@ def build(force: bool = True, jobs: int = 8):
 
 
 if __name__ == "__main__":
-    print(build())
+    import sys
+    print(build(force="--incremental" not in sys.argv))

@@ -2,6 +2,7 @@
 #include "bimamba.h"
 #include "kernels.h"
 #include "launch.h"
+#include "ssd_kernels.h"
 
 #include <hip/hip_runtime.h>
 
@@ -98,14 +99,25 @@ int pick_chunks(const bimamba_desc* d, int split)
 struct Plan {
     int split, nseg, seg_len;
     bool two_bc;  // the two directions consume different prepared B|C buffers
-    size_t off_bc[2], off_partial, off_carry, off_sumdt, total;
+    bool ssd;     // Mamba-2 parameterisation on the chunked matrix-core kernels
+    int ssd_chunks;
+    size_t off_bc[2], off_partial, off_carry, off_sumdt, off_crows[2], off_bt[2], off_score[2], total;
 };
+
+// The chunked matrix-core path covers bf16 I/O with one decay rate per head, d_state 64 or 128 and heads of 32 or
+// 64 channels; forcing time_chunks or state_split selects the lane-per-chain kernels instead.
+bool use_ssd(const bimamba_desc* d)
+{
+    return d->a_kind == BIMAMBA_A_SCALAR_PER_HEAD && d->io_dtype == BIMAMBA_BF16 && d->time_chunks == 0 &&
+           d->state_split == 0 && ssd_supported(d->d_state, d->d_inner / d->n_heads);
+}
 
 Plan make_plan(const bimamba_desc* d, bool inputs_shared)
 {
     Plan p{};
-    p.split = pick_split(d);
-    p.nseg = pick_chunks(d, p.split);
+    p.ssd = use_ssd(d);
+    p.split = p.ssd ? 1 : pick_split(d);
+    p.nseg = p.ssd ? 1 : pick_chunks(d, p.split);
     p.seg_len = d->seqlen > 0 ? (d->seqlen + p.nseg - 1) / p.nseg : 1;
     p.nseg = d->seqlen > 0 ? (d->seqlen + p.seg_len - 1) / p.seg_len : 1;
     p.two_bc = d->conv_bc || !inputs_shared;
@@ -121,6 +133,16 @@ Plan make_plan(const bimamba_desc* d, bool inputs_shared)
         off += align_up((size_t)2 * d->batch * p.nseg * d->d_inner * d->d_state * sizeof(float), 256);
         p.off_sumdt = off;
         off += align_up((size_t)2 * d->batch * p.nseg * d->d_inner * sizeof(float), 256);
+    }
+    p.ssd_chunks = (d->seqlen + kQ - 1) / kQ;
+    if (p.ssd) {
+        const size_t rows = align_up((size_t)d->batch * p.ssd_chunks * kQ * d->n_groups * d->d_state * sizeof(__bf16), 256);
+        const size_t score = align_up((size_t)d->batch * p.ssd_chunks * d->n_groups * kQ * kQ * sizeof(float), 256);
+        for (int s = 0; s < 2; s++) {
+            p.off_crows[s] = off; off += rows;
+            p.off_bt[s] = off; off += rows;
+            p.off_score[s] = off; off += score;
+        }
     }
     p.total = off;
     return p;
@@ -237,6 +259,46 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
             if (d->io_dtype == BIMAMBA_BF16) hipLaunchKernelGGL(prep_bc_kernel<IoBF16>, grid, dim3(256), 0, st, pa);
             else hipLaunchKernelGGL(prep_bc_kernel<IoF32>, grid, dim3(256), 0, st, pa);
         }
+        if (plan.ssd) {
+            // 2'. chunked matrix-core path: per-direction operand tiles, then the reverse scan parks its result and the
+            // forward scan adds, gates and stores (or each writes its own half)
+            const bool separate = d->combine == BIMAMBA_COMBINE_SEPARATE;
+            const bool raw = !separate && same_tensor(in_f->z, in_b->z);
+            for (int s = 0; s < 2; s++) {
+                SsdPrepArgs pa{};
+                pa.bc = reinterpret_cast<const float*>(ws + plan.off_bc[s]);
+                pa.c_rows = reinterpret_cast<__bf16*>(ws + plan.off_crows[s]);
+                pa.b_t = reinterpret_cast<__bf16*>(ws + plan.off_bt[s]);
+                pa.score_t = reinterpret_cast<float*>(ws + plan.off_score[s]);
+                pa.L = d->seqlen; pa.G = d->n_groups; pa.dir = s == 0 ? 1 : -1;
+                launch_ssd_prep(d->d_state, pa, plan.ssd_chunks, d->batch, st);
+            }
+            if (probe_start) (void)hipEventRecord(probe_start, st);
+            for (int s = 1; s >= 0; s--) {
+                const bimamba_inputs* in = s == 0 ? in_f : in_b;
+                const bimamba_params* p = s == 0 ? pf : pb;
+                SsdArgs sa{};
+                sa.x = targ(in->x); sa.z = targ(in->z); sa.dt = targ(in->dt);
+                sa.conv_w = p->conv_w; sa.conv_b = p->conv_b; sa.A = p->A; sa.D = p->D; sa.dt_bias = p->dt_bias;
+                sa.c_rows = reinterpret_cast<const __bf16*>(ws + plan.off_crows[s]);
+                sa.b_t = reinterpret_cast<const __bf16*>(ws + plan.off_bt[s]);
+                sa.score_t = reinterpret_cast<const float*>(ws + plan.off_score[s]);
+                sa.out = out->ptr; sa.out_sb = out->stride_batch; sa.out_st = out->stride_token;
+                sa.partial = reinterpret_cast<float*>(ws + plan.off_partial);
+                sa.h_in = (s == 0 && block_variant) ? h_in : nullptr;
+                sa.h_out = (s == 0 && block_variant) ? h_out : nullptr;
+                sa.tail_in = (s == 0 && block_variant) ? tail_in : nullptr;
+                sa.L = d->seqlen; sa.Dn = d->d_inner; sa.H = d->n_heads; sa.HG = d->n_heads / d->n_groups;
+                sa.G = d->n_groups; sa.K = d->d_conv; sa.tail_ch = tail_ch; sa.nchunk = plan.ssd_chunks;
+                sa.dir = s == 0 ? 1 : -1;
+                sa.mode = separate ? kSsdFinalOnly
+                                   : s == 1 ? (raw ? kSsdPartialRaw : kSsdPartial) : (raw ? kSsdFinalAddRaw : kSsdFinalAdd);
+                sa.out_ch_off = separate ? s * d->d_inner : 0;
+                sa.dt_softplus = d->dt_softplus; sa.d_per_head = d->d_kind == BIMAMBA_D_PER_HEAD;
+                launch_ssd_scan(d->d_state, d->d_inner / d->n_heads, sa, d->batch, st);
+            }
+            if (probe_stop) (void)hipEventRecord(probe_stop, st);
+        } else {
         // 2. scan (summary + carry when the sequence is cut into segments) and combine
         SweepArgs sa{};
         for (int s = 0; s < 2; s++) {
@@ -264,6 +326,7 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
         ca.h_in = sa.h_in; ca.h_out = sa.h_out;
         ca.batch = d->batch; ca.nseg = plan.nseg; ca.Dn = d->d_inner; ca.P = sa.P;
         launch_scan(d, plan.split, sa, ca, st, probe_start, probe_stop);
+        }
     } else if (block_variant && d->batch > 0 && h_out && h_out != h_in) {
         // empty block: the state passes through unchanged
         const size_t bytes = (size_t)d->batch * d->d_inner * d->d_state * sizeof(float);

@@ -1,0 +1,49 @@
+// Instantiations and launchers of the chunked Mamba-2 kernels (d_state in {64, 128}, head width in {32, 64}).
+#include "ssd_kernels.h"
+#include "launch.h"
+
+namespace bm {
+
+template <int N>
+static void prep_one(const SsdPrepArgs& pa, int nchunk, int batch, hipStream_t st)
+{
+    static bool configured = false;  // raising the dynamic-LDS limit is idempotent; done once per process and size
+    if (!configured) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ssd_prep_kernel<N>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)(ssd_prep_lds_bytes<N>()));
+        configured = true;
+    }
+    const size_t lds = ssd_prep_lds_bytes<N>();
+    hipLaunchKernelGGL((ssd_prep_kernel<N>), dim3((unsigned)nchunk, (unsigned)pa.G, (unsigned)batch), dim3(256), lds, st, pa);
+}
+
+template <int N, int P>
+static void scan_one(const SsdArgs& sa, int batch, hipStream_t st)
+{
+    static bool configured = false;
+    if (!configured) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ssd_kernel<N, P>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)ssd_lds_bytes<N, P>());
+        configured = true;
+    }
+    const size_t lds = ssd_lds_bytes<N, P>();
+    hipLaunchKernelGGL((ssd_kernel<N, P>), dim3((unsigned)sa.H, 1, (unsigned)batch), dim3(4 * P), lds, st, sa);
+}
+
+bool ssd_supported(int d_state, int headdim) { return (d_state == 64 || d_state == 128) && (headdim == 32 || headdim == 64); }
+
+void launch_ssd_prep(int d_state, const SsdPrepArgs& pa, int nchunk, int batch, hipStream_t st)
+{
+    if (d_state == 128) prep_one<128>(pa, nchunk, batch, st);
+    else prep_one<64>(pa, nchunk, batch, st);
+}
+
+void launch_ssd_scan(int d_state, int headdim, const SsdArgs& sa, int batch, hipStream_t st)
+{
+    if (d_state == 128 && headdim == 64) scan_one<128, 64>(sa, batch, st);
+    else if (d_state == 128 && headdim == 32) scan_one<128, 32>(sa, batch, st);
+    else if (d_state == 64 && headdim == 64) scan_one<64, 64>(sa, batch, st);
+    else if (d_state == 64 && headdim == 32) scan_one<64, 32>(sa, batch, st);
+}
+
+}  // namespace bm
