@@ -186,12 +186,10 @@ __global__ __launch_bounds__(4 * P) void ssd_kernel(const SsdArgs a)
         // ---- A1: Delta, cumulative log-decay (base 2) and end-of-chunk weights, by wave 0
         if (wave == 0) {
             const int tau = c * kQ + lane;
-            float dl = 0.0f;
-            if (tau < a.L) {
-                const int t = a.dir > 0 ? tau : a.L - 1 - tau;
-                dl = IoBF16::ld(dtb_p + (long long)t * a.dt.st);
-                if (a.dt_softplus) dl = softplus(dl + dtb);
-            }
+            const int tc = min(tau, a.L - 1);
+            float dl = IoBF16::ld(dtb_p + (long long)(a.dir > 0 ? tc : a.L - 1 - tc) * a.dt.st);
+            if (a.dt_softplus) dl = softplus(dl + dtb);
+            if (tau >= a.L) dl = 0.0f;
             float l2 = dl * a2;
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
@@ -203,19 +201,24 @@ __global__ __launch_bounds__(4 * P) void ssd_kernel(const SsdArgs a)
             sDl[lane] = dl;
             sW[lane] = fast_exp2(l2q - l2) * dl;
         }
-        // x of this thread's 16 tokens plus the 3 before them in scan order
+        // x of this thread's 16 tokens plus the 3 before them in scan order: every load is issued unconditionally from
+        // a clamped position (so the 19 requests overlap) and zeroed by a select when the position is outside [0, L)
         float xr[19];
 #pragma unroll
         for (int q = 0; q < 19; q++) {
             const int tau = c * kQ + 16 * tg + q - 3;
-            float v = 0.0f;
-            if (tau >= 0 && tau < a.L) {
-                const int t = a.dir > 0 ? tau : a.L - 1 - tau;
-                v = IoBF16::ld(xb + (long long)t * a.x.st + pc);
-            } else if (tau < 0 && a.dir > 0 && a.tail_in && tau + (a.K - 1) >= 0) {
-                v = IoBF16::ld((const T*)a.tail_in + ((size_t)b * (a.K - 1) + (a.K - 1 + tau)) * a.tail_ch + ch0 + pc);
+            const int tc = min(max(tau, 0), a.L - 1);
+            const int t = a.dir > 0 ? tc : a.L - 1 - tc;
+            const float v = IoBF16::ld(xb + (long long)t * a.x.st + pc);
+            xr[q] = (tau >= 0 && tau < a.L) ? v : 0.0f;
+        }
+        if (c == 0 && tg == 0 && a.dir > 0 && a.tail_in) {
+#pragma unroll
+            for (int q = 0; q < 3; q++) {
+                const int tau = q - 3;
+                if (tau + (a.K - 1) >= 0)
+                    xr[q] = IoBF16::ld((const T*)a.tail_in + ((size_t)b * (a.K - 1) + (a.K - 1 + tau)) * a.tail_ch + ch0 + pc);
             }
-            xr[q] = v;
         }
         // C rows and transposed B tile of this chunk into LDS, 16 bytes at a time
         {
@@ -318,24 +321,37 @@ __global__ __launch_bounds__(4 * P) void ssd_kernel(const SsdArgs a)
                 }
             }
         }
-        // ---- epilogue: inter-chunk term, skip term, gate, combine, store
+        // ---- epilogue: inter-chunk term, skip term, gate, combine, store.  Gate and partial values of the 16 outputs are
+        // requested together from clamped positions before any of them is used.
+        {
+            const bool need_z = a.mode != kSsdPartialRaw;
+            const bool need_p = a.mode == kSsdFinalAdd || a.mode == kSsdFinalAddRaw;
+            T zraw[16];
+            float part[16];
 #pragma unroll
-        for (int r = 0; r < 16; r++) {
-            const int i = iblk * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-            const int tau = c * kQ + i;
-            if (tau < a.L) {
+            for (int r = 0; r < 16; r++) {
+                const int tau = min(c * kQ + iblk * 32 + 8 * (r / 4) + 4 * half + (r % 4), a.L - 1);
                 const int t = a.dir > 0 ? tau : a.L - 1 - tau;
-                float y = y1[r] + fast_exp2(sL2[i]) * y2[r] + dval * (float)sXc[po * kRowT + i];
-                float* pp = a.partial + ((size_t)b * a.L + t) * a.Dn + ch0 + po;
-                T* op = (T*)a.out + (size_t)b * a.out_sb + (long long)t * a.out_st + a.out_ch_off + ch0 + po;
-                if (a.mode == kSsdPartialRaw) {
-                    *pp = y;
-                } else {
-                    const float zg = silu(IoBF16::ld(zb + (long long)t * a.z.st + po));
-                    if (a.mode == kSsdPartial) *pp = y * zg;
-                    else if (a.mode == kSsdFinalAddRaw) IoBF16::st(op, (y + *pp) * zg);
-                    else if (a.mode == kSsdFinalAdd) IoBF16::st(op, y * zg + *pp);
-                    else IoBF16::st(op, y * zg);
+                zraw[r] = need_z ? zb[(long long)t * a.z.st + po] : (T)0;
+                part[r] = need_p ? a.partial[((size_t)b * a.L + t) * a.Dn + ch0 + po] : 0.0f;
+            }
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                const int i = iblk * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+                const int tau = c * kQ + i;
+                const int t = a.dir > 0 ? tau : a.L - 1 - tau;
+                const float y = y1[r] + fast_exp2(sL2[i]) * y2[r] + dval * (float)sXc[po * kRowT + i];
+                float res;
+                if (a.mode == kSsdPartialRaw) res = y;
+                else {
+                    const float zg = silu(IoBF16::cvt(zraw[r]));
+                    res = a.mode == kSsdFinalAddRaw ? (y + part[r]) * zg : y * zg + part[r];
+                }
+                if (tau < a.L) {
+                    if (a.mode == kSsdPartialRaw || a.mode == kSsdPartial)
+                        a.partial[((size_t)b * a.L + t) * a.Dn + ch0 + po] = res;
+                    else
+                        IoBF16::st((T*)a.out + (size_t)b * a.out_sb + (long long)t * a.out_st + a.out_ch_off + ch0 + po, res);
                 }
             }
         }
