@@ -54,6 +54,7 @@ struct SweepArgs {
     int L, Dn, P, HG, G, K, nseg, seg_len, tail_ch;
     int dt_softplus, d_per_head, separate;
     int raw_partial;      // both directions gate with the same z: park y ungated and gate once at the final store
+    const int* a_progression;  // [2] per direction: A[h, n] == A[h, 0] + n (A[h, 1] - A[h, 0]) for every h, n; or null
 };
 
 struct IoF32 {
@@ -102,6 +103,9 @@ __device__ __forceinline__ float sum_over_chain_lanes(float v)
 }
 
 enum { kSweep = 0, kSummary = 1 };
+// How the decay exp(Delta A[h, n]) is formed: one exponential per state; one per token for a scalar A per head; or, when
+// A is an arithmetic progression in n (detected on the device), two exponentials per token, a_n = a_first r^n.
+enum { kAPerState = 0, kAScalar = 1, kAProgression = 2 };
 // What a range of the walk does with its result:
 //   Partial      park g = y * SiLU(z)           PartialRaw   park y (gate later)
 //   FinalAdd     store g + partial              FinalAddRaw  store (y + partial) * SiLU(z)
@@ -119,7 +123,8 @@ struct Chain {
     using T = typename IO::T;
     static constexpr int NS = N / S;
     float h[NS];
-    float a2[AKIND == 0 ? NS : 1];  // A * log2(e)
+    float a2[AKIND == kAPerState ? NS : 1];  // A * log2(e) (kAProgression: of the slice's first state)
+    float d2;                       // kAProgression: (A[h,1] - A[h,0]) * log2(e)
     float w4[4];                    // conv taps, w4[3] on the current token
     float cb, dval, dtb, sum_dt;
     float xh[3];                    // previous raw x, xh[0] most recent
@@ -212,12 +217,21 @@ __device__ __forceinline__ void token_step(Chain<N, S, AKIND, IO>& c, typename I
     uniform_ro_ptr bcmem = (uniform_ro_ptr)c.bcrow;  // only for S = 1 rows too long to prefetch
     constexpr bool kFromMem = (S == 1 && N > 16);
     auto bc = [&](int n) -> float { return kFromMem ? bcmem[n < NS ? n : n - NS + N] : row.v[n]; };
-    if (AKIND == 0) {
+    if (AKIND == kAPerState) {
 #pragma unroll
         for (int n = 0; n < NS; n++) {
             const float a = fast_exp2(delta * c.a2[n]);
             c.h[n] = fmaf(a, c.h[n], u * bc(n));
             if (MODE != kModeNoOutput) y = fmaf(bc(NS + n), c.h[n], y);
+        }
+    } else if (AKIND == kAProgression) {
+        float an = fast_exp2(delta * c.a2[0]);
+        const float ratio = fast_exp2(delta * c.d2);
+#pragma unroll
+        for (int n = 0; n < NS; n++) {
+            c.h[n] = fmaf(an, c.h[n], u * bc(n));
+            if (MODE != kModeNoOutput) y = fmaf(bc(NS + n), c.h[n], y);
+            an *= ratio;
         }
     } else {
         const float a = fast_exp2(delta * c.a2[0]);
@@ -355,14 +369,12 @@ __device__ __forceinline__ unsigned xcd_aware_tile(unsigned g, unsigned n)
 
 // grid (ceil(Dn / (64/S)), nseg, batch), block 128: wave 0 walks left-to-right, wave 1 right-to-left.
 template <int N, int S, int AKIND, typename IO, int KIND>
-__global__ __launch_bounds__(128) void sweep_kernel(const SweepArgs a)
+__device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, const int s)
 {
     using T = typename IO::T;
     constexpr int NS = N / S;
     constexpr int kCpw = 64 / S;  // channels per wave
-    __shared__ __attribute__((aligned(16))) float lds_all[S > 1 ? 2 * 2 * kTile * 2 * N : 4];
     const int lane = threadIdx.x & 63;
-    const int s = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     float* lds = lds_all + (S > 1 ? s * (2 * kTile * 2 * N) : 0);
     const DirArgs& da = a.dir[s];
     const int b = blockIdx.z, seg = blockIdx.y;
@@ -392,9 +404,13 @@ __global__ __launch_bounds__(128) void sweep_kernel(const SweepArgs a)
         c.cb = da.conv_b ? da.conv_b[ch] : 0.0f;
         c.dval = da.D[a.d_per_head ? head : ch];
         c.dtb = (a.dt_softplus && da.dt_bias) ? da.dt_bias[head] : 0.0f;
-        if (AKIND == 0) {
+        c.d2 = 0.0f;
+        if (AKIND == kAPerState) {
 #pragma unroll
             for (int n = 0; n < NS; n++) c.a2[n] = da.A[(size_t)head * N + sub * NS + n] * kLog2e;
+        } else if (AKIND == kAProgression) {
+            c.a2[0] = da.A[(size_t)head * N + sub * NS] * kLog2e;
+            c.d2 = (da.A[(size_t)head * N + 1] - da.A[(size_t)head * N]) * kLog2e;
         } else {
             c.a2[0] = da.A[head] * kLog2e;
         }
@@ -465,6 +481,40 @@ __global__ __launch_bounds__(128) void sweep_kernel(const SweepArgs a)
 #pragma unroll
         for (int n = 0; n < NS; n++) dst[n] = c.h[n];
     }
+}
+
+// The progression form of the decay is used for bf16 I/O and up to 32 states (its rounding error grows with the state
+// index, which bf16 output hides and an fp32 comparison would not).
+template <int N, typename IO>
+constexpr bool kProgressionEligible = (N >= 2 && N <= 32 && sizeof(typename IO::T) == 2);
+
+template <int N, int S, int AKIND, typename IO, int KIND>
+__global__ __launch_bounds__(128) void sweep_kernel(const SweepArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float lds_all[S > 1 ? 2 * 2 * kTile * 2 * N : 4];
+    const int s = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    if constexpr (AKIND == kAPerState && kProgressionEligible<N, IO>) {
+        if (a.a_progression && a.a_progression[s]) {
+            sweep_body<N, S, kAProgression, IO, KIND>(a, lds_all, s);
+            return;
+        }
+    }
+    sweep_body<N, S, AKIND, IO, KIND>(a, lds_all, s);
+}
+
+// One block per direction: flag[s] = 1 iff A_s[h, n] == fma(n, A_s[h, 1] - A_s[h, 0], A_s[h, 0]) for every head and state.
+template <int kUnused = 0>
+__global__ __launch_bounds__(1024) void detect_progression_kernel(const float* A_f, const float* A_b, int H, int N, int* flag)
+{
+    const float* A = blockIdx.x == 0 ? A_f : A_b;
+    int ok = 1;
+    for (long long idx = threadIdx.x; idx < (long long)H * N; idx += blockDim.x) {
+        const int n = (int)(idx % N);
+        const float* row = A + (idx - n);
+        ok &= A[idx] == fmaf((float)n, row[1] - row[0], row[0]);
+    }
+    ok = __syncthreads_and(ok);
+    if (threadIdx.x == 0) flag[blockIdx.x] = ok;
 }
 
 // Stitch time segments: carry[s][b][seg] holds each segment's end state from a zero start (summary pass); replace it

@@ -23,11 +23,11 @@ static void scan_one(const SsdArgs& sa, int batch, hipStream_t st)
     static bool configured = false;
     if (!configured) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ssd_kernel<N, P>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)ssd_lds_bytes<N, P>());
+                                  (int)(SsdLds<N, P>::bytes()));
         configured = true;
     }
-    const size_t lds = ssd_lds_bytes<N, P>();
-    hipLaunchKernelGGL((ssd_kernel<N, P>), dim3((unsigned)sa.H, 1, (unsigned)batch), dim3(4 * P), lds, st, sa);
+    const size_t lds = SsdLds<N, P>::bytes();
+    hipLaunchKernelGGL((ssd_kernel<N, P>), dim3((unsigned)sa.H, 1, (unsigned)batch), dim3(8 * P), lds, st, sa);
 }
 
 bool ssd_supported(int d_state, int headdim) { return (d_state == 64 || d_state == 128) && (headdim == 32 || headdim == 64); }

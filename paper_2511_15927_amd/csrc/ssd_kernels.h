@@ -102,141 +102,166 @@ struct SsdArgs {
     int dir, mode, out_ch_off, dt_softplus, d_per_head;
 };
 
+// LDS of ssd_kernel: two buffers of per-chunk tiles (filled by the producer waves one chunk ahead of the consumer
+// waves) and two copies of the state in MFMA operand form.
 template <int N, int P>
-constexpr size_t ssd_lds_bytes()
-{
-    return ((size_t)kQ * (N + kPadK) + (size_t)N * (kQ + kPadK) + 2 * (size_t)P * (kQ + kPadK) + (size_t)(N / 32) * (P / 32) * 2 * 64 * 8) *
-               sizeof(__bf16) + 3 * kQ * sizeof(float);
-}
+struct SsdLds {
+    static constexpr int kRowC = N + kPadK, kRowT = kQ + kPadK;
+    static constexpr int kC = kQ * kRowC;    // C rows of the chunk               [kQ][kRowC] bf16
+    static constexpr int kBT = N * kRowT;    // B transposed                      [N][kRowT]  bf16
+    static constexpr int kX = P * kRowT;     // conv + SiLU output, transposed    [P][kRowT]  bf16 (two of them)
+    static constexpr int kM = 2 * 2 * 2 * 64 * 8;   // masked, decayed score tile as MFMA operands [iblk][jblk][kb][lane][8]
+    static constexpr int kTileElems = kC + kBT + 2 * kX + kM;
+    static constexpr int kHT = (N / 32) * (P / 32) * 2 * 64 * 8;   // state operand copy, bf16
+    static constexpr size_t bytes() { return (size_t)(2 * kTileElems + 2 * kHT) * sizeof(__bf16) + 2 * kQ * sizeof(float); }
+};
 
-// grid (H, 1, batch), block 4*P, dynamic LDS ssd_lds_bytes<N, P>(): wave w owns output rows iblk*32.. and channels pblk*32.. of every chunk,
-// and N/64 of the 32x32 blocks of H.
+// LDS-only barrier: waits for this wave's LDS traffic, not for global loads that were issued ahead on purpose.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// grid (H, 1, batch), block 8*P, dynamic LDS SsdLds<N, P>::bytes().
+// The first P/16 waves are consumers: wave w owns output rows iblk*32.. and channels pblk*32.. of every chunk and N/64
+// of the 32x32 blocks of H; they build the masked score operand, run the MFMAs and store.  The last P/16 waves are
+// producers: one chunk ahead they compute Delta and the cumulative decay, run conv + SiLU, and stage the C / B^T
+// tiles, with the global loads of the chunk after that already in flight.  One LDS barrier per chunk.
 template <int N, int P>
-__global__ __launch_bounds__(4 * P) void ssd_kernel(const SsdArgs a)
+__global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
 {
+    using Lds = SsdLds<N, P>;
     constexpr int kPB = P / 32;       // channel blocks
     constexpr int kNB = N / 32;       // state blocks
-    constexpr int kHB = kNB / 2;      // state blocks owned per wave
-    constexpr int kThreads = 4 * P;
-    constexpr int kRowC = N + kPadK, kRowT = kQ + kPadK;
+    constexpr int kHB = kNB / 2;      // state blocks owned per consumer wave
+    constexpr int kRoleThreads = 4 * P;
+    constexpr int kRowC = Lds::kRowC, kRowT = Lds::kRowT;
+    constexpr int kCopy = kQ * N / 8 / kRoleThreads;   // 16-byte pieces of each tile per producer thread
+    constexpr int kSlots = 3 * 2 * 64;                 // operand slots (8 values) of the lower-triangular score blocks
+    constexpr int kMS = (kSlots + kRoleThreads - 1) / kRoleThreads;
     using T = unsigned short;
     extern __shared__ __attribute__((aligned(16))) unsigned char ssd_lds[];
-    __bf16* sC = reinterpret_cast<__bf16*>(ssd_lds);   // [kQ][kRowC]   C rows of the chunk
-    __bf16* sBT = sC + kQ * kRowC;                      // [N][kRowT]    B transposed
-    __bf16* sXc = sBT + N * kRowT;                      // [P][kRowT]    conv + SiLU output, transposed
-    __bf16* sXw = sXc + P * kRowT;                      // [P][kRowT]    same, scaled by exp(l_Q - l_j) Delta_j
-    __bf16* sHT = sXw + P * kRowT;                      // [kNB][kPB][2][64][8]  state as an MFMA operand
-    float* sL2 = reinterpret_cast<float*>(sHT + kNB * kPB * 2 * 64 * 8);
-    float* sDl = sL2 + kQ;
-    float* sW = sDl + kQ;
+    __bf16* const tiles = reinterpret_cast<__bf16*>(ssd_lds);
+    __bf16* const sHT = tiles + 2 * Lds::kTileElems;
+    float* const scal = reinterpret_cast<float*>(sHT + 2 * Lds::kHT);   // [2][kQ]: exp(l_i), decay from the chunk start
+    auto sC = [&](int buf) { return tiles + buf * Lds::kTileElems; };
+    auto sBT = [&](int buf) { return tiles + buf * Lds::kTileElems + Lds::kC; };
+    auto sXc = [&](int buf) { return tiles + buf * Lds::kTileElems + Lds::kC + Lds::kBT; };
+    auto sXw = [&](int buf) { return tiles + buf * Lds::kTileElems + Lds::kC + Lds::kBT + Lds::kX; };
+    auto sM = [&](int buf) { return tiles + buf * Lds::kTileElems + Lds::kC + Lds::kBT + 2 * Lds::kX; };
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int iblk = wave / kPB, pblk = wave % kPB;
-    const int cl = lane & 31, half = lane >> 5;
+    const bool producer = wave >= kRoleThreads / 64;
     const int head = blockIdx.x, b = blockIdx.z;
     const int grp = head / a.HG;
     const int ch0 = head * P;
-    const float a2 = a.A[head] * kLog2e;
-    const float dtb = (a.dt_softplus && a.dt_bias) ? a.dt_bias[head] : 0.0f;
-
-    // conv role: channel pc, tokens 16*tg .. 16*tg+15 of each chunk
-    const int pc = tid % P, tg = tid / P;
-    float w4[4];
-#pragma unroll
-    for (int i = 0; i < 4; i++) w4[3 - i] = i < a.K ? a.conv_w[(size_t)(ch0 + pc) * a.K + (a.K - 1 - i)] : 0.0f;
-    const float cbias = a.conv_b ? a.conv_b[ch0 + pc] : 0.0f;
-    // output role: channel po
-    const int po = pblk * 32 + cl;
-    const float dval = a.D[a.d_per_head ? head : ch0 + po];
-
-    // state blocks in accumulator layout
-    f32x16 hacc[kHB];
-#pragma unroll
-    for (int hb = 0; hb < kHB; hb++) {
-        const int nblk = iblk * kHB + hb;
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-            const int n = nblk * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-            hacc[hb][r] = a.h_in ? a.h_in[((size_t)b * a.Dn + ch0 + po) * N + n] : 0.0f;
-        }
-    }
-    auto publish_state = [&]() {
-#pragma unroll
-        for (int hb = 0; hb < kHB; hb++) {
-            const int nblk = iblk * kHB + hb;
-#pragma unroll
-            for (int kb = 0; kb < 2; kb++) {
-                bf16x8 v;
-#pragma unroll
-                for (int e = 0; e < 8; e++) v[e] = (__bf16)hacc[hb][8 * kb + e];
-                *reinterpret_cast<bf16x8*>(&sHT[(((nblk * kPB + pblk) * 2 + kb) * 64 + lane) * 8]) = v;
-            }
-        }
-    };
-    publish_state();
-    bool state_nonzero = a.h_in != nullptr;
-
-    const T* xb = (const T*)a.x.p + (size_t)b * a.x.sb + ch0;
-    const T* zb = (const T*)a.z.p + (size_t)b * a.z.sb + ch0;
-    const T* dtb_p = (const T*)a.dt.p + (size_t)b * a.dt.sb + head;
     const size_t Lpad = (size_t)a.nchunk * kQ;
+    const int last = a.L - 1;
+    auto token_of = [&](int tau) { return a.dir > 0 ? tau : last - tau; };   // scan position -> token index
 
-    for (int c = 0; c < a.nchunk; c++) {
-        // ---- A1: Delta, cumulative log-decay (base 2) and end-of-chunk weights, by wave 0
-        if (wave == 0) {
-            const int tau = c * kQ + lane;
-            const int tc = min(tau, a.L - 1);
-            float dl = IoBF16::ld(dtb_p + (long long)(a.dir > 0 ? tc : a.L - 1 - tc) * a.dt.st);
+    if (producer) {
+        // ------------------------------------------------------------------ producers
+        const int ptid = tid - kRoleThreads;
+        const int pc = ptid % P, tg = ptid / P;    // conv role: channel pc, positions 16*tg .. 16*tg+15 of each chunk
+        const float a2 = a.A[head] * kLog2e;
+        const float dtb = (a.dt_softplus && a.dt_bias) ? a.dt_bias[head] : 0.0f;
+        float w4[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++) w4[3 - i] = i < a.K ? a.conv_w[(size_t)(ch0 + pc) * a.K + (a.K - 1 - i)] : 0.0f;
+        const float cbias = a.conv_b ? a.conv_b[ch0 + pc] : 0.0f;
+        const T* xb = (const T*)a.x.p + (size_t)b * a.x.sb + ch0 + pc;
+        const T* dtp = (const T*)a.dt.p + (size_t)b * a.dt.sb + head;
+
+        T xraw[19];
+        T dtraw;
+        bf16x8 ctile[kCopy], btile[kCopy];
+        float gt[kMS][8];
+        // Score operand slot s: block pair (iblk, jblk) = (0,0), (1,0), (1,1) for s / 128, k-block (s / 64) % 2, operand
+        // lane s % 64.  Its 8 values are column i = iblk*32 + lane%32 of rows j = jblk*32 + 8*(r/4) + 4*(lane/32) + r%4,
+        // r = 8*kb .. 8*kb+7 (the accumulator-register order, see the header comment).
+        auto slot_of = [&](int m, int& iblk, int& jblk, int& kb, int& sl) {
+            const int sidx = m * kRoleThreads + ptid;
+            const int bp = sidx / 128;
+            iblk = bp > 0;
+            jblk = bp > 1;
+            kb = (sidx / 64) % 2;
+            sl = sidx % 64;
+            return sidx < kSlots;
+        };
+        // request everything chunk c needs from global memory (clamped positions: every address is valid)
+        auto issue = [&](int c) {
+            const float* sc = a.score_t + (((size_t)b * a.nchunk + c) * a.G + grp) * (kQ * kQ);
+#pragma unroll
+            for (int m = 0; m < kMS; m++) {
+                int iblk, jblk, kb, sl;
+                if (slot_of(m, iblk, jblk, kb, sl)) {
+#pragma unroll
+                    for (int e = 0; e < 8; e++) {
+                        const int r = 8 * kb + e;
+                        gt[m][e] = sc[(jblk * 32 + 8 * (r / 4) + 4 * (sl / 32) + (r % 4)) * kQ + iblk * 32 + sl % 32];
+                    }
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 19; q++) {
+                const int tau = min(max(c * kQ + 16 * tg + q - 3, 0), last);
+                xraw[q] = xb[(long long)token_of(tau) * a.x.st];
+            }
+            dtraw = dtp[(long long)token_of(min(c * kQ + lane, last)) * a.dt.st];
+            const __bf16* csrc = a.c_rows + (((size_t)b * Lpad + (size_t)c * kQ) * a.G + grp) * N;
+            const __bf16* bsrc = a.b_t + ((((size_t)b * a.nchunk + c) * a.G + grp) * N) * kQ;
+#pragma unroll
+            for (int i = 0; i < kCopy; i++) {
+                const int idx = i * kRoleThreads + ptid;
+                ctile[i] = *reinterpret_cast<const bf16x8*>(csrc + (size_t)(idx / (N / 8)) * a.G * N + (idx % (N / 8)) * 8);
+                btile[i] = *reinterpret_cast<const bf16x8*>(bsrc + (idx / (kQ / 8)) * kQ + (idx % (kQ / 8)) * 8);
+            }
+        };
+        // turn the requested data into chunk c's tiles in buffer buf
+        auto finish = [&](int c, int buf) {
+            // Delta, inclusive cumulative log2-decay and end-of-chunk weight of position `lane` (every producer wave
+            // computes them for itself; the first one publishes them for the consumers)
+            float dl = IoBF16::cvt(dtraw);
             if (a.dt_softplus) dl = softplus(dl + dtb);
-            if (tau >= a.L) dl = 0.0f;
+            if (c * kQ + lane > last) dl = 0.0f;
             float l2 = dl * a2;
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
                 const float up = __shfl_up(l2, off, 64);
                 if (lane >= off) l2 += up;
             }
-            const float l2q = __shfl(l2, 63, 64);
-            sL2[lane] = l2;
-            sDl[lane] = dl;
-            sW[lane] = fast_exp2(l2q - l2) * dl;
-        }
-        // x of this thread's 16 tokens plus the 3 before them in scan order: every load is issued unconditionally from
-        // a clamped position (so the 19 requests overlap) and zeroed by a select when the position is outside [0, L)
-        float xr[19];
+            const float wgt = fast_exp2(__shfl(l2, 63, 64) - l2) * dl;
+            if (ptid < 64) scal[buf * kQ + lane] = fast_exp2(l2);
+            // masked score operand: (B_j . C_i) exp(l_i - l_j) Delta_j for j <= i, else 0
 #pragma unroll
-        for (int q = 0; q < 19; q++) {
-            const int tau = c * kQ + 16 * tg + q - 3;
-            const int tc = min(max(tau, 0), a.L - 1);
-            const int t = a.dir > 0 ? tc : a.L - 1 - tc;
-            const float v = IoBF16::ld(xb + (long long)t * a.x.st + pc);
-            xr[q] = (tau >= 0 && tau < a.L) ? v : 0.0f;
-        }
-        if (c == 0 && tg == 0 && a.dir > 0 && a.tail_in) {
+            for (int m = 0; m < kMS; m++) {
+                int iblk, jblk, kb, sl;
+                if (slot_of(m, iblk, jblk, kb, sl)) {
+                    const int i = iblk * 32 + sl % 32;
+                    const float l2i = __shfl(l2, i, 64);
+                    bf16x8 v;
 #pragma unroll
-            for (int q = 0; q < 3; q++) {
-                const int tau = q - 3;
-                if (tau + (a.K - 1) >= 0)
-                    xr[q] = IoBF16::ld((const T*)a.tail_in + ((size_t)b * (a.K - 1) + (a.K - 1 + tau)) * a.tail_ch + ch0 + pc);
+                    for (int e = 0; e < 8; e++) {
+                        const int r = 8 * kb + e;
+                        const int j = jblk * 32 + 8 * (r / 4) + 4 * (sl / 32) + (r % 4);
+                        const float val = gt[m][e] * fast_exp2(l2i - __shfl(l2, j, 64)) * __shfl(dl, j, 64);
+                        v[e] = (__bf16)(j > i ? 0.0f : val);
+                    }
+                    *reinterpret_cast<bf16x8*>(&sM(buf)[(((iblk * 2 + jblk) * 2 + kb) * 64 + sl) * 8]) = v;
+                }
             }
-        }
-        // C rows and transposed B tile of this chunk into LDS, 16 bytes at a time
-        {
-            const __bf16* csrc = a.c_rows + (((size_t)b * Lpad + (size_t)c * kQ) * a.G + grp) * N;
-            for (int idx = tid; idx < kQ * N / 8; idx += kThreads) {
-                const int j = idx / (N / 8), col = (idx % (N / 8)) * 8;
-                *reinterpret_cast<bf16x8*>(&sC[j * kRowC + col]) =
-                    *reinterpret_cast<const bf16x8*>(csrc + (size_t)j * a.G * N + col);
+            float xr[19];
+#pragma unroll
+            for (int q = 0; q < 19; q++) {
+                const int tau = c * kQ + 16 * tg + q - 3;
+                xr[q] = (tau >= 0 && tau <= last) ? IoBF16::cvt(xraw[q]) : 0.0f;
             }
-            const __bf16* bsrc = a.b_t + ((((size_t)b * a.nchunk + c) * a.G + grp) * N) * kQ;
-            for (int idx = tid; idx < N * kQ / 8; idx += kThreads) {
-                const int n = idx / (kQ / 8), col = (idx % (kQ / 8)) * 8;
-                *reinterpret_cast<bf16x8*>(&sBT[n * kRowT + col]) = *reinterpret_cast<const bf16x8*>(bsrc + n * kQ + col);
+            if (c == 0 && a.dir > 0 && a.tail_in) {
+#pragma unroll
+                for (int q = 0; q < 3; q++) {
+                    const int back = 3 - q;                       // how many tokens before the block
+                    if (tg == 0 && back <= a.K - 1)
+                        xr[q] = IoBF16::ld((const T*)a.tail_in + ((size_t)b * (a.K - 1) + (a.K - 1 - back)) * a.tail_ch + ch0 + pc);
+                }
             }
-        }
-        __syncthreads();
-        // ---- A2: conv + SiLU, two bf16 copies transposed to [channel][position]
-        {
             bf16x8 vx[2], vw[2];
 #pragma unroll
             for (int q = 0; q < 16; q++) {
@@ -247,48 +272,111 @@ __global__ __launch_bounds__(4 * P) void ssd_kernel(const SsdArgs a)
                 pre = fmaf(w4[3], xr[q + 3], pre);
                 const float xc = silu(pre);
                 vx[q / 8][q % 8] = (__bf16)xc;
-                vw[q / 8][q % 8] = (__bf16)(xc * sW[16 * tg + q]);
+                vw[q / 8][q % 8] = (__bf16)(xc * __shfl(wgt, 16 * tg + q, 64));
             }
 #pragma unroll
             for (int q = 0; q < 2; q++) {
-                *reinterpret_cast<bf16x8*>(&sXc[pc * kRowT + 16 * tg + 8 * q]) = vx[q];
-                *reinterpret_cast<bf16x8*>(&sXw[pc * kRowT + 16 * tg + 8 * q]) = vw[q];
+                *reinterpret_cast<bf16x8*>(&sXc(buf)[pc * kRowT + 16 * tg + 8 * q]) = vx[q];
+                *reinterpret_cast<bf16x8*>(&sXw(buf)[pc * kRowT + 16 * tg + 8 * q]) = vw[q];
             }
-        }
-        __syncthreads();
-        // ---- B: outputs of this chunk
-        f32x16 y1 = {0}, y2 = {0};
-        const int icol = iblk * 32 + cl;  // this lane's output row as the score tile's column
-        const float l2i = sL2[icol];
-        for (int jblk = 0; jblk <= iblk; jblk++) {
-            const float* sc = a.score_t + (((size_t)b * a.nchunk + c) * a.G + grp) * (kQ * kQ);
-            float gt[16];
 #pragma unroll
-            for (int r = 0; r < 16; r++) {
-                const int j = jblk * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-                gt[r] = sc[j * kQ + icol];
+            for (int i = 0; i < kCopy; i++) {
+                const int idx = i * kRoleThreads + ptid;
+                *reinterpret_cast<bf16x8*>(&sC(buf)[(idx / (N / 8)) * kRowC + (idx % (N / 8)) * 8]) = ctile[i];
+                *reinterpret_cast<bf16x8*>(&sBT(buf)[(idx / (kQ / 8)) * kRowT + (idx % (kQ / 8)) * 8]) = btile[i];
             }
+        };
+        issue(0);
+        finish(0, 0);
+        if (a.nchunk > 1) issue(1);
+        lds_barrier();
+        for (int c = 0; c < a.nchunk; c++) {
+            if (c + 1 < a.nchunk) {
+                finish(c + 1, (c + 1) & 1);
+                if (c + 2 < a.nchunk) issue(c + 2);
+            }
+            lds_barrier();
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------------- consumers
+    const int iblk = wave / kPB, pblk = wave % kPB;
+    const int cl = lane & 31, half = lane >> 5;
+    const int po = pblk * 32 + cl;             // this lane's channel within the head
+    const int icol = iblk * 32 + cl;           // this lane's output row, as the score tile's column
+    const float dval = a.D[a.d_per_head ? head : ch0 + po];
+    const T* zb = (const T*)a.z.p + (size_t)b * a.z.sb + ch0 + po;
+    float* const pbase = a.partial + (size_t)b * a.L * a.Dn + ch0 + po;
+    T* const obase = (T*)a.out + (size_t)b * a.out_sb + a.out_ch_off + ch0 + po;
+    const bool need_z = a.mode != kSsdPartialRaw;
+    const bool need_p = a.mode == kSsdFinalAdd || a.mode == kSsdFinalAddRaw;
+
+    f32x16 hacc[kHB];
+#pragma unroll
+    for (int hb = 0; hb < kHB; hb++) {
+        const int nblk = iblk * kHB + hb;
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+            const int n = nblk * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+            hacc[hb][r] = a.h_in ? a.h_in[((size_t)b * a.Dn + ch0 + po) * N + n] : 0.0f;
+        }
+    }
+    auto publish_state = [&](int which) {
+#pragma unroll
+        for (int hb = 0; hb < kHB; hb++) {
+            const int nblk = iblk * kHB + hb;
 #pragma unroll
             for (int kb = 0; kb < 2; kb++) {
-                bf16x8 am, bx;
+                bf16x8 v;
 #pragma unroll
-                for (int e = 0; e < 8; e++) {
-                    const int r = 8 * kb + e;
-                    const int j = jblk * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-                    float m = gt[r] * fast_exp2(l2i - sL2[j]) * sDl[j];
-                    if (j > icol) m = 0.0f;
-                    am[e] = (__bf16)m;
-                }
+                for (int e = 0; e < 8; e++) v[e] = (__bf16)hacc[hb][8 * kb + e];
+                *reinterpret_cast<bf16x8*>(&sHT[which * Lds::kHT + (((nblk * kPB + pblk) * 2 + kb) * 64 + lane) * 8]) = v;
+            }
+        }
+    };
+    // global data of one chunk, requested well before it is used
+    T zraw[16];
+    float part[16];
+    auto issue_gate = [&](int c) {
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+            const int t = token_of(min(c * kQ + iblk * 32 + 8 * (r / 4) + 4 * half + (r % 4), last));
+            if (need_z) zraw[r] = zb[(long long)t * a.z.st];
+            if (need_p) part[r] = pbase[(size_t)t * a.Dn];
+        }
+    };
+    publish_state(0);
+    bool state_nonzero = a.h_in != nullptr;
+    issue_gate(0);
+    lds_barrier();
+
+    for (int c = 0; c < a.nchunk; c++) {
+        const int buf = c & 1;
+        const float* el = scal + buf * kQ;
+        const __bf16* xc_t = sXc(buf);
+        // ---- intra-chunk product with the masked, decayed score operand the producers prepared
+        f32x16 y1 = {0}, y2 = {0};
+#pragma unroll
+        for (int jblk = 0; jblk < 2; jblk++) {
+            if (jblk > iblk) break;
+#pragma unroll
+            for (int kb = 0; kb < 2; kb++) {
+                const bf16x8 am = *reinterpret_cast<const bf16x8*>(&sM(buf)[(((iblk * 2 + jblk) * 2 + kb) * 64 + lane) * 8]);
+                bf16x8 bx;
 #pragma unroll
                 for (int jj = 0; jj < 2; jj++) {
-                    const bf16x4 v = *reinterpret_cast<const bf16x4*>(&sXc[po * kRowT + jblk * 32 + 16 * kb + 8 * jj + 4 * half]);
+                    const bf16x4 v = *reinterpret_cast<const bf16x4*>(&xc_t[po * kRowT + jblk * 32 + 16 * kb + 8 * jj + 4 * half]);
 #pragma unroll
                     for (int e = 0; e < 4; e++) bx[4 * jj + e] = v[e];
                 }
                 y1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bx, y1, 0, 0, 0);
             }
         }
+        // ---- inter-chunk product with the state entering the chunk
         if (state_nonzero) {
+            const __bf16* c_t = sC(buf);
+            const __bf16* h_t = sHT + buf * Lds::kHT;
 #pragma unroll
             for (int nblk = 0; nblk < kNB; nblk++) {
 #pragma unroll
@@ -296,18 +384,20 @@ __global__ __launch_bounds__(4 * P) void ssd_kernel(const SsdArgs a)
                     bf16x8 ac;
 #pragma unroll
                     for (int jj = 0; jj < 2; jj++) {
-                        const bf16x4 v = *reinterpret_cast<const bf16x4*>(&sC[icol * kRowC + nblk * 32 + 16 * kb + 8 * jj + 4 * half]);
+                        const bf16x4 v = *reinterpret_cast<const bf16x4*>(&c_t[icol * kRowC + nblk * 32 + 16 * kb + 8 * jj + 4 * half]);
 #pragma unroll
                         for (int e = 0; e < 4; e++) ac[4 * jj + e] = v[e];
                     }
-                    const bf16x8 bh = *reinterpret_cast<const bf16x8*>(&sHT[(((nblk * kPB + pblk) * 2 + kb) * 64 + lane) * 8]);
+                    const bf16x8 bh = *reinterpret_cast<const bf16x8*>(&h_t[(((nblk * kPB + pblk) * 2 + kb) * 64 + lane) * 8]);
                     y2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ac, bh, y2, 0, 0, 0);
                 }
             }
         }
-        // ---- C: state update of the blocks this wave owns
+        // ---- state update of the blocks this wave owns
         {
-            const float decay_q = fast_exp2(sL2[kQ - 1]);
+            const __bf16* b_t = sBT(buf);
+            const __bf16* xw_t = sXw(buf);
+            const float decay_q = el[kQ - 1];
 #pragma unroll
             for (int hb = 0; hb < kHB; hb++) {
                 const int nblk = iblk * kHB + hb;
@@ -315,49 +405,34 @@ __global__ __launch_bounds__(4 * P) void ssd_kernel(const SsdArgs a)
                 for (int r = 0; r < 16; r++) hacc[hb][r] *= decay_q;
 #pragma unroll
                 for (int kb = 0; kb < 4; kb++) {
-                    const bf16x8 ab = *reinterpret_cast<const bf16x8*>(&sBT[(nblk * 32 + cl) * kRowT + 16 * kb + 8 * half]);
-                    const bf16x8 bw = *reinterpret_cast<const bf16x8*>(&sXw[po * kRowT + 16 * kb + 8 * half]);
+                    const bf16x8 ab = *reinterpret_cast<const bf16x8*>(&b_t[(nblk * 32 + cl) * kRowT + 16 * kb + 8 * half]);
+                    const bf16x8 bw = *reinterpret_cast<const bf16x8*>(&xw_t[po * kRowT + 16 * kb + 8 * half]);
                     hacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ab, bw, hacc[hb], 0, 0, 0);
                 }
             }
         }
-        // ---- epilogue: inter-chunk term, skip term, gate, combine, store.  Gate and partial values of the 16 outputs are
-        // requested together from clamped positions before any of them is used.
-        {
-            const bool need_z = a.mode != kSsdPartialRaw;
-            const bool need_p = a.mode == kSsdFinalAdd || a.mode == kSsdFinalAddRaw;
-            T zraw[16];
-            float part[16];
+        // ---- epilogue: inter-chunk term, skip term, gate, combine, store
 #pragma unroll
-            for (int r = 0; r < 16; r++) {
-                const int tau = min(c * kQ + iblk * 32 + 8 * (r / 4) + 4 * half + (r % 4), a.L - 1);
-                const int t = a.dir > 0 ? tau : a.L - 1 - tau;
-                zraw[r] = need_z ? zb[(long long)t * a.z.st + po] : (T)0;
-                part[r] = need_p ? a.partial[((size_t)b * a.L + t) * a.Dn + ch0 + po] : 0.0f;
+        for (int r = 0; r < 16; r++) {
+            const int i = iblk * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+            const int tau = c * kQ + i;
+            const int t = token_of(min(tau, last));
+            const float y = y1[r] + el[i] * y2[r] + dval * (float)xc_t[po * kRowT + i];
+            float res;
+            if (!need_z) res = y;
+            else {
+                const float zg = silu(IoBF16::cvt(zraw[r]));
+                res = a.mode == kSsdFinalAddRaw ? (y + part[r]) * zg : need_p ? y * zg + part[r] : y * zg;
             }
-#pragma unroll
-            for (int r = 0; r < 16; r++) {
-                const int i = iblk * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-                const int tau = c * kQ + i;
-                const int t = a.dir > 0 ? tau : a.L - 1 - tau;
-                const float y = y1[r] + fast_exp2(sL2[i]) * y2[r] + dval * (float)sXc[po * kRowT + i];
-                float res;
-                if (a.mode == kSsdPartialRaw) res = y;
-                else {
-                    const float zg = silu(IoBF16::cvt(zraw[r]));
-                    res = a.mode == kSsdFinalAddRaw ? (y + part[r]) * zg : y * zg + part[r];
-                }
-                if (tau < a.L) {
-                    if (a.mode == kSsdPartialRaw || a.mode == kSsdPartial)
-                        a.partial[((size_t)b * a.L + t) * a.Dn + ch0 + po] = res;
-                    else
-                        IoBF16::st((T*)a.out + (size_t)b * a.out_sb + (long long)t * a.out_st + a.out_ch_off + ch0 + po, res);
-                }
+            if (tau <= last) {
+                if (a.mode == kSsdPartialRaw || a.mode == kSsdPartial) pbase[(size_t)t * a.Dn] = res;
+                else IoBF16::st(obase + (long long)t * a.out_st, res);
             }
         }
-        __syncthreads();  // every wave is done with this chunk's tiles and with the published state
-        publish_state();
+        issue_gate(min(c + 1, a.nchunk - 1));
+        publish_state(buf ^ 1);
         state_nonzero = true;
+        lds_barrier();
     }
     if (a.h_out) {
 #pragma unroll

@@ -204,3 +204,25 @@ def test_cfg4_stack_teacher_forced_per_layer(gpu, oracle):
         got = out.float().cpu().numpy().astype(np.float64)[:, :, sel]
         assert rel_l2(got, ref) < gpu.TOL["bf16"], layer
         x_gpu = out
+
+
+@pytest.mark.parametrize("N,split", [(16, 1), (16, 2), (16, 4), (32, 2), (8, 1)])
+def test_decay_progression_detected_path(gpu, oracle, N, split):
+    """A[h, n] arithmetic in n with a different start and step per channel (the form the library detects on the device
+    and evaluates with two exponentials per token), and the same A with one entry nudged so that detection must fail:
+    both must match the oracle (bf16 I/O, long enough for detection to be attempted, chunked and not)."""
+    for chunks in (1, 3):
+        cfg = synth.mixer_cfg(2, 300, 136, d_state=N, io="bf16", state_split=split, time_chunks=chunks)
+        pf, pb, inp = case(cfg, 1500 + N)
+        hidx = torch.arange(cfg["n_heads"], dtype=torch.float32)
+        n = torch.arange(N, dtype=torch.float32)
+        for p, sign in ((pf, 1.0), (pb, 2.0)):
+            start = -(0.5 + 0.25 * (hidx % 7))                 # multiples of 1/4: every entry is exact in fp32
+            step = -(0.125 * sign) * (1 + hidx % 3)
+            p["A"] = (start[:, None] + n[None, :] * step[:, None]).contiguous()
+        ref = oracle.bimamba_fwd(cfg, to_np(pf), to_np(pb), to_np(inp))
+        assert rel_l2(gpu.gpu_fwd(cfg, pf, pb, inp), ref) < gpu.TOL["bf16"]
+        pf2 = dict(pf, A=pf["A"].clone())
+        pf2["A"][5, N - 1] *= 1.0 + 2.0 ** -20                  # no longer a progression: the general path must run
+        ref2 = oracle.bimamba_fwd(cfg, to_np(pf2), to_np(pb), to_np(inp))
+        assert rel_l2(gpu.gpu_fwd(cfg, pf2, pb, inp), ref2) < gpu.TOL["bf16"]
