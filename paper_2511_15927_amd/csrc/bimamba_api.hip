@@ -58,20 +58,17 @@ long long waves_of(const bimamba_desc* d, int split)
     return 2LL * d->batch * ((d->d_inner + cpw - 1) / cpw);
 }
 
-// Lanes per chain: spreading a chain's states over 2 or 4 lanes multiplies the number of waves without repeating the
-// decay exponentials (the per-token conv / gate work is repeated instead), so it is the first lever when the
-// (batch x channel x direction) chains alone leave SIMDs with fewer than two waves.
+// Lanes per chain: spreading a chain's states over 2 lanes doubles the number of waves without repeating the decay
+// exponentials (the per-token conv / gate work is repeated instead), so it is the first lever when the
+// (batch x channel x direction) chains alone leave SIMDs with fewer than two waves.  Four lanes per chain repeat too
+// much of that work to pay off below 64 states (measured), so beyond two lanes the sequence is cut instead.
 int pick_split(const bimamba_desc* d)
 {
     if (d->state_split > 0) return d->state_split;
-    int split = 1;
-    while (waves_of(d, split) < kTargetWaves && split < 4) {
-        int next = split * 2;
-        if (!split_supported(d->d_state, next)) next = split * 4;
-        if (next > 4 || !split_supported(d->d_state, next)) break;
-        split = next;
-    }
-    return split;
+    if (waves_of(d, 1) >= kTargetWaves) return 1;
+    if (split_supported(d->d_state, 2)) return 2;
+    if (d->d_state >= 64 && split_supported(d->d_state, 4)) return 4;
+    return 1;
 }
 
 int pick_chunks(const bimamba_desc* d, int split)
@@ -205,8 +202,10 @@ void launch_scan(const bimamba_desc* d, int split, const SweepArgs& sa, const Ca
                  hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     const int scalar_a = d->a_kind == BIMAMBA_A_SCALAR_PER_HEAD, bf16 = d->io_dtype == BIMAMBA_BF16;
+    // four or more waves per SIMD are available: trade prefetch depth for registers (occupancy)
+    const int shallow = split == 1 && waves_of(d, 1) * sa.nseg >= 2 * kTargetWaves;
 #define BM_CASE(n, s) \
-    case (n) * 8 + (s): launch_scan_n##n##_s##s(scalar_a, bf16, sa, ca, d->batch, st, ev_start, ev_stop); break;
+    case (n) * 8 + (s): launch_scan_n##n##_s##s(scalar_a, bf16, sa, ca, d->batch, shallow, st, ev_start, ev_stop); break;
     switch (d->d_state * 8 + split) {
         BM_CASE(4, 1) BM_CASE(8, 1) BM_CASE(16, 1) BM_CASE(16, 2) BM_CASE(16, 4) BM_CASE(32, 1) BM_CASE(32, 2)
         BM_CASE(32, 4) BM_CASE(64, 1) BM_CASE(64, 4) BM_CASE(128, 1) BM_CASE(128, 4)

@@ -114,7 +114,9 @@ enum { kModePartial = 0, kModeFinalAdd = 1, kModeFinalOnly = 2, kModeNoOutput = 
 __host__ __device__ constexpr bool mode_reads_z(int m) { return m != kModeNoOutput && m != kModePartialRaw; }
 __host__ __device__ constexpr bool mode_reads_partial(int m) { return m == kModeFinalAdd || m == kModeFinalAddRaw; }
 
-constexpr int kTile = 8;  // tokens whose loads are in flight while the previous tile is being computed
+// TILE (template parameter below): tokens whose loads are in flight while the previous tile is being computed.  8 when
+// a SIMD holds one or two waves (the prefetch depth hides HBM latency); 4 when it can hold four or more (fewer
+// registers per wave, and the other waves hide the latency).
 
 // Per-lane constants and running state of one chain slice.  Row pointers are wave-uniform and advance by signed
 // per-token steps; ch / head are the lane's constant offsets into a row.
@@ -136,17 +138,17 @@ struct Chain {
     unsigned ch, head, sub;         // channel, head, slice index (lane % S)
 };
 
-template <typename IO>
+template <typename IO, int TILE>
 struct RawTile {
-    typename IO::T x[kTile], z[kTile], dt[kTile];
-    float part[kTile];
+    typename IO::T x[TILE], z[TILE], dt[TILE];
+    float part[TILE];
 };
 
-template <int N, int S, int AKIND, typename IO, int MODE>
-__device__ __forceinline__ void load_tile(const Chain<N, S, AKIND, IO>& c, long long ahead, RawTile<IO>& r)
+template <int N, int S, int AKIND, typename IO, int MODE, int TILE>
+__device__ __forceinline__ void load_tile(const Chain<N, S, AKIND, IO>& c, long long ahead, RawTile<IO, TILE>& r)
 {
 #pragma unroll
-    for (int i = 0; i < kTile; i++) {
+    for (int i = 0; i < TILE; i++) {
         r.x[i] = (c.xrow + (ahead + i) * c.xs)[c.ch];
         r.dt[i] = (c.dtrow + (ahead + i) * c.dts)[c.head];
         if (mode_reads_z(MODE)) r.z[i] = (c.zrow + (ahead + i) * c.zs)[c.ch];
@@ -187,7 +189,7 @@ __device__ __forceinline__ void load_bc_direct(const float* row, unsigned sub, B
     }
 }
 
-// Lane-private slice of token i of a staged tile in LDS ([kTile][2N] floats).
+// Lane-private slice of token i of a staged tile in LDS ([TILE][2N] floats).
 template <int N, int S>
 __device__ __forceinline__ void load_bc_lds(const float* tile, int i, unsigned sub, BcRow<N / S>& r)
 {
@@ -266,19 +268,19 @@ __device__ __forceinline__ void token_step(Chain<N, S, AKIND, IO>& c, typename I
 
 // Tokens [0, count) of the chain's walk from its current position, tile by tile with the next tile's loads in flight
 // and the next token's B|C slice requested before the current token is computed.  lds: this wave's private staging
-// area of 2 * kTile * 2N floats (S > 1 only).
-template <int N, int S, int AKIND, typename IO, int MODE>
+// area of 2 * TILE * 2N floats (S > 1 only).
+template <int N, int S, int AKIND, typename IO, int MODE, int TILE>
 __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, bool softplus_dt, float* lds, int lane)
 {
     constexpr int NS = N / S;
     constexpr int kRowF4 = 2 * N / 4;              // float4s per B|C row
-    constexpr int kStage = (kTile * kRowF4 + 63) / 64;  // float4s each lane moves per staged tile
-    using Tile = RawTile<IO>;
+    constexpr int kStage = (TILE * kRowF4 + 63) / 64;  // float4s each lane moves per staged tile
+    using Tile = RawTile<IO, TILE>;
     if (count <= 0) return;
     int done = 0;
-    if (count >= kTile) {
+    if (count >= TILE) {
         Tile cur;
-        load_tile<N, S, AKIND, IO, MODE>(c, 0, cur);
+        load_tile<N, S, AKIND, IO, MODE, TILE>(c, 0, cur);
         BcRow<NS> row;
         float4 stage[kStage];
         int buf = 0;
@@ -287,7 +289,7 @@ __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, 
 #pragma unroll
             for (int j = 0; j < kStage; j++) {
                 const int idx = j * 64 + lane;
-                if (kTile * kRowF4 % 64 == 0 || idx < kTile * kRowF4)
+                if (TILE * kRowF4 % 64 == 0 || idx < TILE * kRowF4)
                     stage[j] = *reinterpret_cast<const float4*>(c.bcrow + (ahead + idx / kRowF4) * c.bcs + (idx % kRowF4) * 4);
             }
         };
@@ -295,8 +297,8 @@ __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, 
 #pragma unroll
             for (int j = 0; j < kStage; j++) {
                 const int idx = j * 64 + lane;
-                if (kTile * kRowF4 % 64 == 0 || idx < kTile * kRowF4)
-                    *reinterpret_cast<float4*>(lds + which * (kTile * 2 * N) + idx * 4) = stage[j];
+                if (TILE * kRowF4 % 64 == 0 || idx < TILE * kRowF4)
+                    *reinterpret_cast<float4*>(lds + which * (TILE * 2 * N) + idx * 4) = stage[j];
             }
             __builtin_amdgcn_wave_barrier();  // other lanes of this wave read these rows next; LDS keeps wave order
         };
@@ -308,18 +310,18 @@ __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, 
             load_bc_scalar<N>(c.bcrow, row);
         }
         while (true) {
-            const bool more = done + 2 * kTile <= count;
+            const bool more = done + 2 * TILE <= count;
             Tile nxt;
             if (more) {
-                load_tile<N, S, AKIND, IO, MODE>(c, kTile, nxt);
-                if constexpr (S > 1) stage_load(kTile);
+                load_tile<N, S, AKIND, IO, MODE, TILE>(c, TILE, nxt);
+                if constexpr (S > 1) stage_load(TILE);
             }
-            const float* tile_bc = lds + buf * (kTile * 2 * N);
+            const float* tile_bc = lds + buf * (TILE * 2 * N);
 #pragma unroll
-            for (int i = 0; i < kTile; i++) {
+            for (int i = 0; i < TILE; i++) {
                 BcRow<NS> row_next;
                 if constexpr (S > 1) {
-                    if (i + 1 < kTile) load_bc_lds<N, S>(tile_bc, i + 1, c.sub, row_next);
+                    if (i + 1 < TILE) load_bc_lds<N, S>(tile_bc, i + 1, c.sub, row_next);
                 } else if constexpr (kBcScalarAhead<N, S>) {
                     // never read past the walk's last token: the row after it may lie outside the buffer
                     load_bc_scalar<N>(done + i + 1 < count ? c.bcrow + c.bcs : c.bcrow, row_next);
@@ -327,19 +329,19 @@ __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, 
                 }
                 token_step<N, S, AKIND, IO, MODE>(c, cur.x[i], cur.dt[i], cur.z[i], cur.part[i], softplus_dt, row);
                 if constexpr (S > 1) {
-                    if (i + 1 < kTile) row = row_next;
+                    if (i + 1 < TILE) row = row_next;
                 } else if constexpr (kBcScalarAhead<N, S>) {
                     __builtin_amdgcn_sched_barrier(0);
                     row = row_next;
                 }
             }
-            done += kTile;
+            done += TILE;
             if (!more) break;
             cur = nxt;
             if constexpr (S > 1) {
                 buf ^= 1;
                 stage_store(buf);
-                load_bc_lds<N, S>(lds + buf * (kTile * 2 * N), 0, c.sub, row);
+                load_bc_lds<N, S>(lds + buf * (TILE * 2 * N), 0, c.sub, row);
             }
         }
     }
@@ -368,14 +370,14 @@ __device__ __forceinline__ unsigned xcd_aware_tile(unsigned g, unsigned n)
 }
 
 // grid (ceil(Dn / (64/S)), nseg, batch), block 128: wave 0 walks left-to-right, wave 1 right-to-left.
-template <int N, int S, int AKIND, typename IO, int KIND>
+template <int N, int S, int AKIND, typename IO, int KIND, int TILE>
 __device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, const int s)
 {
     using T = typename IO::T;
     constexpr int NS = N / S;
     constexpr int kCpw = 64 / S;  // channels per wave
     const int lane = threadIdx.x & 63;
-    float* lds = lds_all + (S > 1 ? s * (2 * kTile * 2 * N) : 0);
+    float* lds = lds_all + (S > 1 ? s * (2 * TILE * 2 * N) : 0);
     const DirArgs& da = a.dir[s];
     const int b = blockIdx.z, seg = blockIdx.y;
     // Lanes past the last channel shadow channel Dn-1: they load the same inputs, compute the same values and
@@ -457,7 +459,7 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, c
     const bool sp = a.dt_softplus != 0;
 
     if (KIND == kSummary) {
-        run_range<N, S, AKIND, IO, kModeNoOutput>(c, len, sp, lds, lane);
+        run_range<N, S, AKIND, IO, kModeNoOutput, TILE>(c, len, sp, lds, lane);
         float* dst = a.carry + ((((size_t)s * gridDim.z + b) * a.nseg + seg) * a.Dn + ch) * N + sub * NS;
 #pragma unroll
         for (int n = 0; n < NS; n++) dst[n] = c.h[n];
@@ -466,15 +468,15 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, c
     }
 
     if (a.separate) {
-        run_range<N, S, AKIND, IO, kModeFinalOnly>(c, len, sp, lds, lane);
+        run_range<N, S, AKIND, IO, kModeFinalOnly, TILE>(c, len, sp, lds, lane);
     } else {
         // forward parks [t0, m), reverse parks [m, t1); then each finishes the other's half
         const int n_first = s == 0 ? (len + 1) / 2 : len / 2;
-        if (a.raw_partial) run_range<N, S, AKIND, IO, kModePartialRaw>(c, n_first, sp, lds, lane);
-        else run_range<N, S, AKIND, IO, kModePartial>(c, n_first, sp, lds, lane);
+        if (a.raw_partial) run_range<N, S, AKIND, IO, kModePartialRaw, TILE>(c, n_first, sp, lds, lane);
+        else run_range<N, S, AKIND, IO, kModePartial, TILE>(c, n_first, sp, lds, lane);
         __syncthreads();  // workgroup-scope release/acquire: the other wave's partials are visible from here on
-        if (a.raw_partial) run_range<N, S, AKIND, IO, kModeFinalAddRaw>(c, len - n_first, sp, lds, lane);
-        else run_range<N, S, AKIND, IO, kModeFinalAdd>(c, len - n_first, sp, lds, lane);
+        if (a.raw_partial) run_range<N, S, AKIND, IO, kModeFinalAddRaw, TILE>(c, len - n_first, sp, lds, lane);
+        else run_range<N, S, AKIND, IO, kModeFinalAdd, TILE>(c, len - n_first, sp, lds, lane);
     }
     if (s == 0 && a.nseg == 1 && a.h_out) {
         float* dst = a.h_out + ((size_t)b * a.Dn + ch) * N + sub * NS;
@@ -488,18 +490,18 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, c
 template <int N, typename IO>
 constexpr bool kProgressionEligible = (N >= 2 && N <= 32 && sizeof(typename IO::T) == 2);
 
-template <int N, int S, int AKIND, typename IO, int KIND>
+template <int N, int S, int AKIND, typename IO, int KIND, int TILE>
 __global__ __launch_bounds__(128) void sweep_kernel(const SweepArgs a)
 {
-    __shared__ __attribute__((aligned(16))) float lds_all[S > 1 ? 2 * 2 * kTile * 2 * N : 4];
+    __shared__ __attribute__((aligned(16))) float lds_all[S > 1 ? 2 * 2 * TILE * 2 * N : 4];
     const int s = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     if constexpr (AKIND == kAPerState && kProgressionEligible<N, IO>) {
         if (a.a_progression && a.a_progression[s]) {
-            sweep_body<N, S, kAProgression, IO, KIND>(a, lds_all, s);
+            sweep_body<N, S, kAProgression, IO, KIND, TILE>(a, lds_all, s);
             return;
         }
     }
-    sweep_body<N, S, AKIND, IO, KIND>(a, lds_all, s);
+    sweep_body<N, S, AKIND, IO, KIND, TILE>(a, lds_all, s);
 }
 
 // One block per direction: flag[s] = 1 iff A_s[h, n] == fma(n, A_s[h, 1] - A_s[h, 0], A_s[h, 0]) for every head and state.

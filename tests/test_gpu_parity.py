@@ -226,3 +226,10 @@ def test_decay_progression_detected_path(gpu, oracle, N, split):
         pf2["A"][5, N - 1] *= 1.0 + 2.0 ** -20                  # no longer a progression: the general path must run
         ref2 = oracle.bimamba_fwd(cfg, to_np(pf2), to_np(pb), to_np(inp))
         assert rel_l2(gpu.gpu_fwd(cfg, pf2, pb, inp), ref2) < gpu.TOL["bf16"]
+
+
+def test_large_batch_shallow_tile(gpu, oracle):
+    """Enough chains for four waves per SIMD: the library switches to the shallow-tile instantiation."""
+    for L, ra in ((100, True), (37, False)):
+        cfg = synth.mixer_cfg(32, L, 4096)
+        check_fwd(gpu, oracle, cfg, 1600 + L, random_a=ra, sel=sampled(16, 4096, 9))
