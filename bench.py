@@ -17,6 +17,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBPS = 8000.0          # MI355X HBM3E
 PEAK_FP32_VECTOR_TFLOPS = 157.3  # MI355X fp32 vector (256 CUs x 2.4 GHz x 256 flop/clk)
+PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16 matrix
 
 
 def parse():
@@ -131,20 +132,30 @@ def main():
     ach_tflops = flops / (kernel_ms * 1e-3) / 1e12
     ach_gbps = nbytes / (kernel_ms * 1e-3) / 1e9
     scalar_a = cfg["a_kind"] == 1
+    ssd = scalar_a and cfg["io"] == "bf16" and cfg["d_state"] in (64, 128) and cfg["d_inner"] // cfg["n_heads"] in (32, 64)
     kernel = "sweep_kernel<N=%d,%s,%s>" % (cfg["d_state"], "scalarA" if scalar_a else "perStateA", cfg["io"])
+    roofline = {"bound": "alu", "achieved": ach_tflops, "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach_tflops / PEAK_FP32_VECTOR_TFLOPS, "algorithmic_flops": flops}
+    if ssd:
+        # the chunked matrix-core kernels: one launch per direction, both inside the probed interval
+        kernel = "ssd_kernel<N=%d,P=%d> (two launches, one per direction)" % (cfg["d_state"], cfg["d_inner"] // cfg["n_heads"])
+        mflops = shapes.ssd_matrix_flops(cfg)
+        ach = mflops / (kernel_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / PEAK_BF16_MFMA_TFLOPS, "algorithmic_flops": mflops}
+    roofline.update({"traffic": read_traffic("sweep_" + args.workload), "kernel": kernel, "kernel_ms": kernel_ms})
     result = {
         "metric": "bidirectional-scan tokens/s/GPU at d_inner=4096,L=8K; HBM GB/s vs peak",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "batch": cfg["batch"], "seq_len": cfg["seqlen"], "d_inner": cfg["d_inner"],
-                   "d_state": cfg["d_state"], "io_dtype": cfg["io"], "state_dtype": "f32",
-                   "A": "general" if args.general_a else "-(1..N) per state (arithmetic in n: detected on the device)",
+                   "d_state": cfg["d_state"], "n_heads": cfg["n_heads"], "io_dtype": cfg["io"], "state_dtype": "f32",
+                   "A": "general" if args.general_a else ("scalar per head" if scalar_a else
+                                                           "-(1..N) per state (arithmetic in n: detected on the device)"),
                    "inputs": "shared by both directions",
                    "combine": "add", "time_chunks": bd.bimamba_time_chunks(desc)},
-        "roofline": {"bound": "alu", "achieved": ach_tflops, "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
-                     "frac": ach_tflops / PEAK_FP32_VECTOR_TFLOPS, "traffic": read_traffic("sweep_" + args.workload),
-                     "kernel": kernel, "kernel_ms": kernel_ms, "algorithmic_flops": flops},
+        "roofline": roofline,
         "hbm": {"achieved": ach_gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach_gbps / PEAK_HBM_GBPS,
                 "algorithmic_bytes": nbytes},
         "general_A": general,

@@ -98,8 +98,7 @@ struct Plan {
     bool two_bc;  // the two directions consume different prepared B|C buffers
     bool ssd;     // Mamba-2 parameterisation on the chunked matrix-core kernels
     int ssd_chunks;
-    bool detect_progression;  // look for A[h, n] arithmetic in n on the device before the scan
-    size_t off_bc[2], off_partial, off_carry, off_sumdt, off_crows[2], off_bt[2], off_score[2], off_flags, total;
+    size_t off_bc[2], off_partial, off_carry, off_sumdt, off_crows[2], off_bt[2], off_score[2], total;
 };
 
 // The chunked matrix-core path covers bf16 I/O with one decay rate per head, d_state 64 or 128 and heads of 32 or
@@ -132,12 +131,6 @@ Plan make_plan(const bimamba_desc* d, bool inputs_shared)
         p.off_sumdt = off;
         off += align_up((size_t)2 * d->batch * p.nseg * d->d_inner * sizeof(float), 256);
     }
-    // The progression form of the decay saves most exponentials; finding out costs one small launch, which only long
-    // calls repay.
-    p.detect_progression = !p.ssd && d->a_kind == BIMAMBA_A_PER_HEAD_STATE && d->io_dtype == BIMAMBA_BF16 &&
-                           d->d_state >= 2 && d->d_state <= 32 && d->seqlen >= 256;
-    p.off_flags = off;
-    if (p.detect_progression) off += 256;
     p.ssd_chunks = (d->seqlen + kQ - 1) / kQ;
     if (p.ssd) {
         const size_t rows = align_up((size_t)d->batch * p.ssd_chunks * kQ * d->n_groups * d->d_state * sizeof(__bf16), 256);
@@ -327,12 +320,7 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
         sa.dt_softplus = d->dt_softplus; sa.d_per_head = d->d_kind == BIMAMBA_D_PER_HEAD;
         sa.separate = d->combine == BIMAMBA_COMBINE_SEPARATE;
         sa.raw_partial = !sa.separate && same_tensor(in_f->z, in_b->z);
-        sa.a_progression = nullptr;
-        if (plan.detect_progression) {
-            int* flags = reinterpret_cast<int*>(ws + plan.off_flags);
-            hipLaunchKernelGGL(detect_progression_kernel<0>, dim3(2), dim3(1024), 0, st, pf->A, pb->A, d->n_heads, d->d_state, flags);
-            sa.a_progression = flags;
-        }
+        sa.try_progression = 1;
         CarryArgs ca{};
         ca.carry = sa.carry; ca.sumdt = sa.sumdt; ca.A[0] = pf->A; ca.A[1] = pb->A;
         ca.h_in = sa.h_in; ca.h_out = sa.h_out;

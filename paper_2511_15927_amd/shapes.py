@@ -43,3 +43,16 @@ def algorithmic_flops(cfg):
     per_state = 7 if cfg["a_kind"] == 0 else 5
     per_tc = 22 + per_state * N + (0 if cfg["a_kind"] == 0 else 2)
     return 2 * Bt * L * Dn * per_tc + (Bt * L * Dn if not cfg["combine"] else 0)
+
+
+SSD_CHUNK = 64
+
+
+def ssd_matrix_flops(cfg, chunk=SSD_CHUNK):
+    """Matrix-core flops of the chunked form of the scalar-decay (Mamba-2) recurrence, both directions: per token and
+    head 2*Q*P (masked scores times inputs) + 2*N*P (C times the carried state) + 2*N*P (state update), plus the score
+    tile 2*Q*N per token and group."""
+    Bt, L, Dn, N, H, G = cfg["batch"], cfg["seqlen"], cfg["d_inner"], cfg["d_state"], cfg["n_heads"], cfg["n_groups"]
+    P = Dn // H
+    per_token = H * (2 * chunk * P + 4 * N * P) + G * 2 * chunk * N
+    return 2 * Bt * L * per_token

@@ -51,6 +51,7 @@ CONFIGS = {
     "cfg3_block": mixer_cfg(16, 32, 4096),
     "headline": mixer_cfg(8, 8192, 4096),
     "headline_b1": mixer_cfg(1, 8192, 4096),
+    "headline_m2": m2_cfg(8, 8192, 4096),
     "paper_1p3b": m2_cfg(1, 1024, 3840, headdim=32, d_state=128),
 }
 CFG4_BATCHES = (1, 8, 32, 64)
