@@ -17,6 +17,7 @@
 // k-slots of k-block kb, i.e. k = 16*kb + 8*jj + 4*(l/32) + e for slot 4*jj + e.
 #pragma once
 #include "kernels.h"
+#include <type_traits>
 
 namespace bm {
 
@@ -301,149 +302,204 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
     }
 
     // ---------------------------------------------------------------------- consumers
-    const int iblk = wave / kPB, pblk = wave % kPB;
-    const int cl = lane & 31, half = lane >> 5;
-    const int po = pblk * 32 + cl;             // this lane's channel within the head
-    const int icol = iblk * 32 + cl;           // this lane's output row, as the score tile's column
-    const float dval = a.D[a.d_per_head ? head : ch0 + po];
-    const T* zb = (const T*)a.z.p + (size_t)b * a.z.sb + ch0 + po;
-    float* const pbase = a.partial + (size_t)b * a.L * a.Dn + ch0 + po;
-    T* const obase = (T*)a.out + (size_t)b * a.out_sb + a.out_ch_off + ch0 + po;
-    const bool need_z = a.mode != kSsdPartialRaw;
-    const bool need_p = a.mode == kSsdFinalAdd || a.mode == kSsdFinalAddRaw;
+    // The output mode is fixed per launch; the walk is compiled once per mode so that the per-chunk code has no
+    // mode branches (gfx9 counts loads and stores on one counter: a load awaited while a store is in flight costs
+    // the store's full round trip, so every chunk first consumes its prefetched gate data, then stores).
+    auto walk = [&](auto mode_c) {
+        constexpr int kMode = decltype(mode_c)::value;
+        constexpr bool need_z = kMode != kSsdPartialRaw;
+        constexpr bool need_p = kMode == kSsdFinalAdd || kMode == kSsdFinalAddRaw;
+        constexpr bool park = kMode == kSsdPartialRaw || kMode == kSsdPartial;
+        const int iblk = wave / kPB, pblk = wave % kPB;
+        const int cl = lane & 31, half = lane >> 5;
+        const int po = pblk * 32 + cl;             // this lane's channel within the head
+        const int icol = iblk * 32 + cl;           // this lane's output row, as the score tile's column
+        const int i0 = iblk * 32 + 4 * half;       // output row of accumulator register 0; register r: i0 + row_k(r)
+        auto row_k = [](int r) { return 8 * (r / 4) + (r % 4); };
+        const float dval = a.D[a.d_per_head ? head : ch0 + po];
+        const T* zb = (const T*)a.z.p + (size_t)b * a.z.sb + ch0 + po;
+        float* const pbase = a.partial + (size_t)b * a.L * a.Dn + ch0 + po;
+        T* const obase = (T*)a.out + (size_t)b * a.out_sb + a.out_ch_off + ch0 + po;
+        // signed element steps from one scan position to the next
+        const long long zstep = a.dir * a.z.st, pstep = (long long)a.dir * a.Dn, ostep = a.dir * a.out_st;
 
-    f32x16 hacc[kHB];
-#pragma unroll
-    for (int hb = 0; hb < kHB; hb++) {
-        const int nblk = iblk * kHB + hb;
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-            const int n = nblk * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-            hacc[hb][r] = a.h_in ? a.h_in[((size_t)b * a.Dn + ch0 + po) * N + n] : 0.0f;
-        }
-    }
-    auto publish_state = [&](int which) {
-#pragma unroll
-        for (int hb = 0; hb < kHB; hb++) {
-            const int nblk = iblk * kHB + hb;
-#pragma unroll
-            for (int kb = 0; kb < 2; kb++) {
-                bf16x8 v;
-#pragma unroll
-                for (int e = 0; e < 8; e++) v[e] = (__bf16)hacc[hb][8 * kb + e];
-                *reinterpret_cast<bf16x8*>(&sHT[which * Lds::kHT + (((nblk * kPB + pblk) * 2 + kb) * 64 + lane) * 8]) = v;
-            }
-        }
-    };
-    // global data of one chunk, requested well before it is used
-    T zraw[16];
-    float part[16];
-    auto issue_gate = [&](int c) {
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-            const int t = token_of(min(c * kQ + iblk * 32 + 8 * (r / 4) + 4 * half + (r % 4), last));
-            if (need_z) zraw[r] = zb[(long long)t * a.z.st];
-            if (need_p) part[r] = pbase[(size_t)t * a.Dn];
-        }
-    };
-    publish_state(0);
-    bool state_nonzero = a.h_in != nullptr;
-    issue_gate(0);
-    lds_barrier();
-
-    for (int c = 0; c < a.nchunk; c++) {
-        const int buf = c & 1;
-        const float* el = scal + buf * kQ;
-        const __bf16* xc_t = sXc(buf);
-        // ---- intra-chunk product with the masked, decayed score operand the producers prepared
-        f32x16 y1 = {0}, y2 = {0};
-#pragma unroll
-        for (int jblk = 0; jblk < 2; jblk++) {
-            if (jblk > iblk) break;
-#pragma unroll
-            for (int kb = 0; kb < 2; kb++) {
-                const bf16x8 am = *reinterpret_cast<const bf16x8*>(&sM(buf)[(((iblk * 2 + jblk) * 2 + kb) * 64 + lane) * 8]);
-                bf16x8 bx;
-#pragma unroll
-                for (int jj = 0; jj < 2; jj++) {
-                    const bf16x4 v = *reinterpret_cast<const bf16x4*>(&xc_t[po * kRowT + jblk * 32 + 16 * kb + 8 * jj + 4 * half]);
-#pragma unroll
-                    for (int e = 0; e < 4; e++) bx[4 * jj + e] = v[e];
-                }
-                y1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bx, y1, 0, 0, 0);
-            }
-        }
-        // ---- inter-chunk product with the state entering the chunk
-        if (state_nonzero) {
-            const __bf16* c_t = sC(buf);
-            const __bf16* h_t = sHT + buf * Lds::kHT;
-#pragma unroll
-            for (int nblk = 0; nblk < kNB; nblk++) {
-#pragma unroll
-                for (int kb = 0; kb < 2; kb++) {
-                    bf16x8 ac;
-#pragma unroll
-                    for (int jj = 0; jj < 2; jj++) {
-                        const bf16x4 v = *reinterpret_cast<const bf16x4*>(&c_t[icol * kRowC + nblk * 32 + 16 * kb + 8 * jj + 4 * half]);
-#pragma unroll
-                        for (int e = 0; e < 4; e++) ac[4 * jj + e] = v[e];
-                    }
-                    const bf16x8 bh = *reinterpret_cast<const bf16x8*>(&h_t[(((nblk * kPB + pblk) * 2 + kb) * 64 + lane) * 8]);
-                    y2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ac, bh, y2, 0, 0, 0);
-                }
-            }
-        }
-        // ---- state update of the blocks this wave owns
-        {
-            const __bf16* b_t = sBT(buf);
-            const __bf16* xw_t = sXw(buf);
-            const float decay_q = el[kQ - 1];
-#pragma unroll
-            for (int hb = 0; hb < kHB; hb++) {
-                const int nblk = iblk * kHB + hb;
-#pragma unroll
-                for (int r = 0; r < 16; r++) hacc[hb][r] *= decay_q;
-#pragma unroll
-                for (int kb = 0; kb < 4; kb++) {
-                    const bf16x8 ab = *reinterpret_cast<const bf16x8*>(&b_t[(nblk * 32 + cl) * kRowT + 16 * kb + 8 * half]);
-                    const bf16x8 bw = *reinterpret_cast<const bf16x8*>(&xw_t[po * kRowT + 16 * kb + 8 * half]);
-                    hacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ab, bw, hacc[hb], 0, 0, 0);
-                }
-            }
-        }
-        // ---- epilogue: inter-chunk term, skip term, gate, combine, store
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-            const int i = iblk * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-            const int tau = c * kQ + i;
-            const int t = token_of(min(tau, last));
-            const float y = y1[r] + el[i] * y2[r] + dval * (float)xc_t[po * kRowT + i];
-            float res;
-            if (!need_z) res = y;
-            else {
-                const float zg = silu(IoBF16::cvt(zraw[r]));
-                res = a.mode == kSsdFinalAddRaw ? (y + part[r]) * zg : need_p ? y * zg + part[r] : y * zg;
-            }
-            if (tau <= last) {
-                if (a.mode == kSsdPartialRaw || a.mode == kSsdPartial) pbase[(size_t)t * a.Dn] = res;
-                else IoBF16::st(obase + (long long)t * a.out_st, res);
-            }
-        }
-        issue_gate(min(c + 1, a.nchunk - 1));
-        publish_state(buf ^ 1);
-        state_nonzero = true;
-        lds_barrier();
-    }
-    if (a.h_out) {
+        f32x16 hacc[kHB];
 #pragma unroll
         for (int hb = 0; hb < kHB; hb++) {
             const int nblk = iblk * kHB + hb;
 #pragma unroll
             for (int r = 0; r < 16; r++) {
-                const int n = nblk * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-                a.h_out[((size_t)b * a.Dn + ch0 + po) * N + n] = hacc[hb][r];
+                const int n = nblk * 32 + 4 * half + row_k(r);
+                hacc[hb][r] = a.h_in ? a.h_in[((size_t)b * a.Dn + ch0 + po) * N + n] : 0.0f;
             }
         }
+        auto publish_state = [&](int which) {
+#pragma unroll
+            for (int hb = 0; hb < kHB; hb++) {
+                const int nblk = iblk * kHB + hb;
+#pragma unroll
+                for (int kb = 0; kb < 2; kb++) {
+                    bf16x8 v;
+#pragma unroll
+                    for (int e = 0; e < 8; e++) v[e] = (__bf16)hacc[hb][8 * kb + e];
+                    *reinterpret_cast<bf16x8*>(&sHT[which * Lds::kHT + (((nblk * kPB + pblk) * 2 + kb) * 64 + lane) * 8]) = v;
+                }
+            }
+        };
+        // gate and parked partial of one chunk, requested a whole chunk before they are used.  A chunk that ends
+        // inside the sequence addresses its rows as one base plus constant multiples of the step; the ragged last
+        // chunk clamps every position instead.
+        T zraw[16];
+        float part[16];
+        auto issue_gate = [&](int c) {
+            const int tau0 = c * kQ + i0;
+            if (c * kQ + kQ - 1 <= last) {
+                const long long t0 = token_of(tau0);
+                const T* zp = zb + t0 * a.z.st;
+                const float* pp = pbase + t0 * a.Dn;
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    if constexpr (need_z) zraw[r] = zp[row_k(r) * zstep];
+                    if constexpr (need_p) part[r] = pp[row_k(r) * pstep];
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const long long t = token_of(min(tau0 + row_k(r), last));
+                    if constexpr (need_z) zraw[r] = zb[t * a.z.st];
+                    if constexpr (need_p) part[r] = pbase[t * a.Dn];
+                }
+            }
+        };
+        publish_state(0);
+        bool state_nonzero = a.h_in != nullptr;
+        issue_gate(0);
+        lds_barrier();
+
+        for (int c = 0; c < a.nchunk; c++) {
+            const int buf = c & 1;
+            const float* el = scal + buf * kQ;
+            const __bf16* xc_t = sXc(buf);
+            // ---- intra-chunk product with the masked, decayed score operand the producers prepared
+            f32x16 y1 = {0}, y2 = {0};
+#pragma unroll
+            for (int jblk = 0; jblk < 2; jblk++) {
+                if (jblk > iblk) break;
+#pragma unroll
+                for (int kb = 0; kb < 2; kb++) {
+                    const bf16x8 am = *reinterpret_cast<const bf16x8*>(&sM(buf)[(((iblk * 2 + jblk) * 2 + kb) * 64 + lane) * 8]);
+                    bf16x8 bx;
+#pragma unroll
+                    for (int jj = 0; jj < 2; jj++) {
+                        const bf16x4 v = *reinterpret_cast<const bf16x4*>(&xc_t[po * kRowT + jblk * 32 + 16 * kb + 8 * jj + 4 * half]);
+#pragma unroll
+                        for (int e = 0; e < 4; e++) bx[4 * jj + e] = v[e];
+                    }
+                    y1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bx, y1, 0, 0, 0);
+                }
+            }
+            // ---- inter-chunk product with the state entering the chunk
+            if (state_nonzero) {
+                const __bf16* c_t = sC(buf);
+                const __bf16* h_t = sHT + buf * Lds::kHT;
+#pragma unroll
+                for (int nblk = 0; nblk < kNB; nblk++) {
+#pragma unroll
+                    for (int kb = 0; kb < 2; kb++) {
+                        bf16x8 ac;
+#pragma unroll
+                        for (int jj = 0; jj < 2; jj++) {
+                            const bf16x4 v = *reinterpret_cast<const bf16x4*>(&c_t[icol * kRowC + nblk * 32 + 16 * kb + 8 * jj + 4 * half]);
+#pragma unroll
+                            for (int e = 0; e < 4; e++) ac[4 * jj + e] = v[e];
+                        }
+                        const bf16x8 bh = *reinterpret_cast<const bf16x8*>(&h_t[(((nblk * kPB + pblk) * 2 + kb) * 64 + lane) * 8]);
+                        y2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ac, bh, y2, 0, 0, 0);
+                    }
+                }
+            }
+            // ---- state update of the blocks this wave owns
+            {
+                const __bf16* b_t = sBT(buf);
+                const __bf16* xw_t = sXw(buf);
+                const float decay_q = el[kQ - 1];
+#pragma unroll
+                for (int hb = 0; hb < kHB; hb++) {
+                    const int nblk = iblk * kHB + hb;
+#pragma unroll
+                    for (int r = 0; r < 16; r++) hacc[hb][r] *= decay_q;
+#pragma unroll
+                    for (int kb = 0; kb < 4; kb++) {
+                        const bf16x8 ab = *reinterpret_cast<const bf16x8*>(&b_t[(nblk * 32 + cl) * kRowT + 16 * kb + 8 * half]);
+                        const bf16x8 bw = *reinterpret_cast<const bf16x8*>(&xw_t[po * kRowT + 16 * kb + 8 * half]);
+                        hacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ab, bw, hacc[hb], 0, 0, 0);
+                    }
+                }
+            }
+            // ---- epilogue: inter-chunk term, skip term, gate, combine; all 16 results first, then the stores
+            float res[16];
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                const float4 e4 = *reinterpret_cast<const float4*>(&el[i0 + 8 * q]);
+                const bf16x4 x4 = *reinterpret_cast<const bf16x4*>(&xc_t[po * kRowT + i0 + 8 * q]);
+                const float ev[4] = {e4.x, e4.y, e4.z, e4.w};
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    const int r = 4 * q + e;
+                    const float y = y1[r] + ev[e] * y2[r] + dval * (float)x4[e];
+                    if constexpr (!need_z) res[r] = y;
+                    else {
+                        const float zg = silu(IoBF16::cvt(zraw[r]));
+                        res[r] = kMode == kSsdFinalAddRaw ? (y + part[r]) * zg : need_p ? y * zg + part[r] : y * zg;
+                    }
+                }
+            }
+            {
+                const int tau0 = c * kQ + i0;
+                if (c * kQ + kQ - 1 <= last) {
+                    const long long t0 = token_of(tau0);
+                    float* pp = pbase + t0 * a.Dn;
+                    T* op = obase + t0 * a.out_st;
+#pragma unroll
+                    for (int r = 0; r < 16; r++) {
+                        if constexpr (park) pp[row_k(r) * pstep] = res[r];
+                        else IoBF16::st(op + row_k(r) * ostep, res[r]);
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; r++) {
+                        const int tau = tau0 + row_k(r);
+                        if (tau <= last) {
+                            const long long t = token_of(tau);
+                            if constexpr (park) pbase[t * a.Dn] = res[r];
+                            else IoBF16::st(obase + t * a.out_st, res[r]);
+                        }
+                    }
+                }
+            }
+            issue_gate(min(c + 1, a.nchunk - 1));
+            publish_state(buf ^ 1);
+            state_nonzero = true;
+            lds_barrier();
+        }
+        if (a.h_out) {
+#pragma unroll
+            for (int hb = 0; hb < kHB; hb++) {
+                const int nblk = iblk * kHB + hb;
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const int n = nblk * 32 + 4 * half + row_k(r);
+                    a.h_out[((size_t)b * a.Dn + ch0 + po) * N + n] = hacc[hb][r];
+                }
+            }
+        }
+    };
+    switch (a.mode) {
+        case kSsdFinalOnly: walk(std::integral_constant<int, kSsdFinalOnly>{}); break;
+        case kSsdPartial: walk(std::integral_constant<int, kSsdPartial>{}); break;
+        case kSsdPartialRaw: walk(std::integral_constant<int, kSsdPartialRaw>{}); break;
+        case kSsdFinalAdd: walk(std::integral_constant<int, kSsdFinalAdd>{}); break;
+        default: walk(std::integral_constant<int, kSsdFinalAddRaw>{}); break;
     }
 }
 
