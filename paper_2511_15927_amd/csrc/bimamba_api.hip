@@ -112,9 +112,11 @@ bool use_ssd(const bimamba_desc* d)
 Plan make_plan(const bimamba_desc* d, bool inputs_shared)
 {
     Plan p{};
+    // The lane-per-chain geometry is always planned (and its workspace reserved): a call whose x tensors do not meet
+    // the matrix-core kernels' alignment needs falls back to it.
     p.ssd = use_ssd(d);
-    p.split = p.ssd ? 1 : pick_split(d);
-    p.nseg = p.ssd ? 1 : pick_chunks(d, p.split);
+    p.split = pick_split(d);
+    p.nseg = pick_chunks(d, p.split);
     p.seg_len = d->seqlen > 0 ? (d->seqlen + p.nseg - 1) / p.nseg : 1;
     p.nseg = d->seqlen > 0 ? (d->seqlen + p.seg_len - 1) / p.seg_len : 1;
     p.two_bc = d->conv_bc || !inputs_shared;
@@ -134,7 +136,7 @@ Plan make_plan(const bimamba_desc* d, bool inputs_shared)
     p.ssd_chunks = (d->seqlen + kQ - 1) / kQ;
     if (p.ssd) {
         const size_t rows = align_up((size_t)d->batch * p.ssd_chunks * kQ * d->n_groups * d->d_state * sizeof(__bf16), 256);
-        const size_t score = align_up((size_t)d->batch * p.ssd_chunks * d->n_groups * kQ * kQ * sizeof(float), 256);
+        const size_t score = align_up((size_t)d->batch * p.ssd_chunks * d->n_groups * kScoreOp * sizeof(float), 256);
         for (int s = 0; s < 2; s++) {
             p.off_crows[s] = off; off += rows;
             p.off_bt[s] = off; off += rows;
@@ -189,6 +191,11 @@ bool same_inputs(const bimamba_inputs* a, const bimamba_inputs* b)
                       same_tensor(a->B, b->B) && same_tensor(a->C, b->C));
 }
 
+bool pairs_readable(const bimamba_tensor& t)
+{
+    return is_aligned(t.ptr, 4) && t.stride_batch % 2 == 0 && t.stride_token % 2 == 0;
+}
+
 TensorArg targ(const bimamba_tensor& t) { return TensorArg{t.ptr, (long long)t.stride_batch, (long long)t.stride_token}; }
 
 void launch_scan(const bimamba_desc* d, int split, const SweepArgs& sa, const CarryArgs& ca, hipStream_t st,
@@ -227,7 +234,9 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
     if (!is_aligned(h_in, 4) || !is_aligned(h_out, 4) || !is_aligned(tail_in, elem) || !is_aligned(tail_out, elem))
         return BIMAMBA_ERR_MISALIGNED;
     const bool shared = same_inputs(in_f, in_b);
-    const Plan plan = make_plan(d, shared);
+    Plan plan = make_plan(d, shared);
+    // the chunked kernels read x two channels at a time
+    if (plan.ssd && !(pairs_readable(in_f->x) && pairs_readable(in_b->x))) plan.ssd = false;
     if (plan.total > 0) {
         if (!workspace) return BIMAMBA_ERR_NULL_POINTER;
         if (!is_aligned(workspace, 16)) return BIMAMBA_ERR_MISALIGNED;
@@ -268,7 +277,7 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
                 pa.bc = reinterpret_cast<const float*>(ws + plan.off_bc[s]);
                 pa.c_rows = reinterpret_cast<__bf16*>(ws + plan.off_crows[s]);
                 pa.b_t = reinterpret_cast<__bf16*>(ws + plan.off_bt[s]);
-                pa.score_t = reinterpret_cast<float*>(ws + plan.off_score[s]);
+                pa.score_op = reinterpret_cast<float*>(ws + plan.off_score[s]);
                 pa.L = d->seqlen; pa.G = d->n_groups; pa.dir = s == 0 ? 1 : -1;
                 launch_ssd_prep(d->d_state, pa, plan.ssd_chunks, d->batch, st);
             }
@@ -281,7 +290,7 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
                 sa.conv_w = p->conv_w; sa.conv_b = p->conv_b; sa.A = p->A; sa.D = p->D; sa.dt_bias = p->dt_bias;
                 sa.c_rows = reinterpret_cast<const __bf16*>(ws + plan.off_crows[s]);
                 sa.b_t = reinterpret_cast<const __bf16*>(ws + plan.off_bt[s]);
-                sa.score_t = reinterpret_cast<const float*>(ws + plan.off_score[s]);
+                sa.score_op = reinterpret_cast<const float*>(ws + plan.off_score[s]);
                 sa.out = out->ptr; sa.out_sb = out->stride_batch; sa.out_st = out->stride_token;
                 sa.partial = reinterpret_cast<float*>(ws + plan.off_partial);
                 sa.h_in = (s == 0 && block_variant) ? h_in : nullptr;
@@ -379,7 +388,8 @@ size_t bimamba_workspace_bytes(const bimamba_desc* desc, int block_variant)
 int bimamba_time_chunks(const bimamba_desc* desc)
 {
     if (check_desc(desc)) return 0;
-    return make_plan(desc, true).nseg;
+    const Plan p = make_plan(desc, true);
+    return p.ssd ? 1 : p.nseg;
 }
 
 void bimamba_profile_next_call(void* ev_start, void* ev_stop)

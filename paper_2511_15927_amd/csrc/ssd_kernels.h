@@ -27,12 +27,13 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int kQ = 64;     // chunk length
 constexpr int kPadK = 8;   // bf16 elements of row padding in LDS tiles (keeps 16-byte alignment, spreads banks)
+constexpr int kScoreOp = 3 * 2 * 64 * 8;   // floats of one chunk's score tile: 3 lower-triangular 32x32 blocks
 
 struct SsdPrepArgs {
     const float* bc;   // fp32 B|C rows [batch][L][G][2N] in token order (from prep_bc_kernel)
     __bf16* c_rows;    // [batch][Lpad][G][N], scan order
     __bf16* b_t;       // [batch][nchunk][G][N][64], scan order inside the chunk
-    float* score_t;    // [batch][nchunk][G][64 j][64 i] = B_j . C_i
+    float* score_op;   // [batch][nchunk][G][kScoreOp]: B_j . C_i for j, i in the chunk, MFMA operand order (see the kernel)
     int L, G, dir;     // dir +1: scan position tau is token tau; -1: token L-1-tau
 };
 
@@ -79,10 +80,20 @@ __global__ __launch_bounds__(256) void ssd_prep_kernel(const SsdPrepArgs a)
 #pragma unroll
             for (int r = 0; r < 4; r++) acc[q][r] = fmaf(bv[q], cv[r], acc[q][r]);
     }
-    float* dst = a.score_t + (((size_t)b * nchunk + c) * a.G + g) * (kQ * kQ);
+    // Rows j = 4tj.., columns i = 4ti.. of the tile.  Only blocks on or below the diagonal are kept, in the order the
+    // scan kernel feeds them to the MFMA as operand A: [block pair (0,0), (1,0), (1,1)][k-block][lane][8], where lane
+    // 32h + i%32 holds rows j%32 = 16kb + 8q + 4h + e of column i in slots 4q + e.
+    const int jblk = tj / 8, iblk = ti / 8;
+    if (jblk <= iblk) {
+        float* dst = a.score_op + (((size_t)b * nchunk + c) * a.G + g) * kScoreOp;
+        const int jj = (4 * tj) % 32, kb = jj / 16, q = (jj % 16) / 8, h = (jj % 8) / 4;
 #pragma unroll
-    for (int q = 0; q < 4; q++)
-        *reinterpret_cast<float4*>(dst + (4 * tj + q) * kQ + 4 * ti) = make_float4(acc[q][0], acc[q][1], acc[q][2], acc[q][3]);
+        for (int r = 0; r < 4; r++) {
+            const int sl = 32 * h + (4 * ti + r) % 32;
+            *reinterpret_cast<float4*>(dst + ((((iblk + jblk) * 2 + kb) * 64 + sl) * 8 + 4 * q)) =
+                make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
+        }
+    }
 }
 
 enum { kSsdFinalOnly = 0, kSsdPartial = 1, kSsdPartialRaw = 2, kSsdFinalAdd = 3, kSsdFinalAddRaw = 4 };
@@ -92,7 +103,7 @@ struct SsdArgs {
     const float *conv_w, *conv_b, *A, *D, *dt_bias;
     const __bf16* c_rows;
     const __bf16* b_t;
-    const float* score_t;
+    const float* score_op;
     void* out;
     long long out_sb, out_st;
     float* partial;       // [batch][L][Dn] fp32
@@ -114,13 +125,31 @@ struct SsdLds {
     static constexpr int kM = 2 * 2 * 2 * 64 * 8;   // masked, decayed score tile as MFMA operands [iblk][jblk][kb][lane][8]
     static constexpr int kTileElems = kC + kBT + 2 * kX + kM;
     static constexpr int kHT = (N / 32) * (P / 32) * 2 * 64 * 8;   // state operand copy, bf16
-    static constexpr size_t bytes() { return (size_t)(2 * kTileElems + 2 * kHT) * sizeof(__bf16) + 2 * kQ * sizeof(float); }
+    static constexpr int kProducerWaves = 4 * P / 64;
+    // + exp(l_i) per buffer, + per producer wave: cumulative log2 decay, Delta, end-of-chunk weight of each position
+    static constexpr size_t bytes() { return (size_t)(2 * kTileElems + 2 * kHT) * sizeof(__bf16) + (2 + 3 * kProducerWaves) * kQ * sizeof(float); }
 };
 
 // LDS-only barrier: waits for this wave's LDS traffic, not for global loads that were issued ahead on purpose.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-// grid (H, 1, batch), block 8*P, dynamic LDS SsdLds<N, P>::bytes().
+// Inclusive prefix sum over the 64 lanes with DPP moves: shifts inside each row of 16 lanes, then the last lane of
+// row 0 / 2 is added to row 1 / 3 and the last lane of row 1 to rows 2 and 3.
+__device__ __forceinline__ float wave_inclusive_sum(float v)
+{
+#define BM_DPP_ADD(ctrl, rows) v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), ctrl, rows, 0xF, false))
+    BM_DPP_ADD(0x111, 0xF);  // row_shr:1
+    BM_DPP_ADD(0x112, 0xF);  // row_shr:2
+    BM_DPP_ADD(0x114, 0xF);  // row_shr:4
+    BM_DPP_ADD(0x118, 0xF);  // row_shr:8
+    BM_DPP_ADD(0x142, 0xA);  // row_bcast:15 into rows 1 and 3
+    BM_DPP_ADD(0x143, 0xC);  // row_bcast:31 into rows 2 and 3
+#undef BM_DPP_ADD
+    return v;
+}
+
+// grid (H, 1, batch), block 8*P, dynamic LDS SsdLds<N, P>::bytes().  x is read as pairs of channels: its pointer must be
+// 4-byte aligned and its strides even (the host checks).
 // The first P/16 waves are consumers: wave w owns output rows iblk*32.. and channels pblk*32.. of every chunk and N/64
 // of the 32x32 blocks of H; they build the masked score operand, run the MFMAs and store.  The last P/16 waves are
 // producers: one chunk ahead they compute Delta and the cumulative decay, run conv + SiLU, and stage the C / B^T
@@ -160,24 +189,44 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
 
     if (producer) {
         // ------------------------------------------------------------------ producers
+        constexpr int kCP = P / 2;                 // channel pairs of the head
         const int ptid = tid - kRoleThreads;
-        const int pc = ptid % P, tg = ptid / P;    // conv role: channel pc, positions 16*tg .. 16*tg+15 of each chunk
+        const int pwave = wave - kRoleThreads / 64;
+        const int cp = ptid % kCP, tg = ptid / kCP;   // conv role: channels 2cp, 2cp+1; positions 8*tg .. 8*tg+7 of each chunk
+        float* const pw_l2 = scal + 2 * kQ + pwave * 3 * kQ;   // wave-private, written and read by this wave only
+        float* const pw_dl = pw_l2 + kQ;
+        float* const pw_wgt = pw_dl + kQ;
         const float a2 = a.A[head] * kLog2e;
         const float dtb = (a.dt_softplus && a.dt_bias) ? a.dt_bias[head] : 0.0f;
-        float w4[4];
+        float w4[2][4], cbias[2];
 #pragma unroll
-        for (int i = 0; i < 4; i++) w4[3 - i] = i < a.K ? a.conv_w[(size_t)(ch0 + pc) * a.K + (a.K - 1 - i)] : 0.0f;
-        const float cbias = a.conv_b ? a.conv_b[ch0 + pc] : 0.0f;
-        const T* xb = (const T*)a.x.p + (size_t)b * a.x.sb + ch0 + pc;
+        for (int h2 = 0; h2 < 2; h2++) {
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                w4[h2][3 - i] = i < a.K ? a.conv_w[(size_t)(ch0 + 2 * cp + h2) * a.K + (a.K - 1 - i)] : 0.0f;
+            cbias[h2] = a.conv_b ? a.conv_b[ch0 + 2 * cp + h2] : 0.0f;
+        }
+        const T* xb = (const T*)a.x.p + (size_t)b * a.x.sb + ch0 + 2 * cp;
         const T* dtp = (const T*)a.dt.p + (size_t)b * a.dt.sb + head;
+        const long long xstep = a.dir * a.x.st;
+        // this thread's 16-byte pieces of the C and B^T tiles: offsets inside a chunk (global) and inside the LDS tiles
+        unsigned c_src[kCopy], b_src[kCopy], c_dst[kCopy], b_dst[kCopy];
+#pragma unroll
+        for (int i = 0; i < kCopy; i++) {
+            const int idx = i * kRoleThreads + ptid;
+            c_src[i] = (unsigned)(idx / (N / 8)) * a.G * N + (idx % (N / 8)) * 8;
+            b_src[i] = (idx / (kQ / 8)) * kQ + (idx % (kQ / 8)) * 8;
+            c_dst[i] = (idx / (N / 8)) * kRowC + (idx % (N / 8)) * 8;
+            b_dst[i] = (idx / (kQ / 8)) * kRowT + (idx % (kQ / 8)) * 8;
+        }
 
-        T xraw[19];
+        unsigned xraw[11];   // channel pair at positions 8*tg - 3 .. 8*tg + 7
         T dtraw;
         bf16x8 ctile[kCopy], btile[kCopy];
-        float gt[kMS][8];
-        // Score operand slot s: block pair (iblk, jblk) = (0,0), (1,0), (1,1) for s / 128, k-block (s / 64) % 2, operand
-        // lane s % 64.  Its 8 values are column i = iblk*32 + lane%32 of rows j = jblk*32 + 8*(r/4) + 4*(lane/32) + r%4,
-        // r = 8*kb .. 8*kb+7 (the accumulator-register order, see the header comment).
+        float4 gt[kMS][2];
+        // Score operand slot s = m*kRoleThreads + ptid: block pair (iblk, jblk) = (0,0), (1,0), (1,1) for s / 128,
+        // k-block (s / 64) % 2, operand lane s % 64.  Its 8 values are column i = iblk*32 + lane%32 of rows
+        // j = jblk*32 + 16*kb + 4*(lane/32) + {0..3, 8..11} (the accumulator-register order, see the header comment).
         auto slot_of = [&](int m, int& iblk, int& jblk, int& kb, int& sl) {
             const int sidx = m * kRoleThreads + ptid;
             const int bp = sidx / 128;
@@ -187,105 +236,124 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
             sl = sidx % 64;
             return sidx < kSlots;
         };
+        auto edge_chunk = [&](int c) { return c == 0 || c * kQ + kQ - 1 > last; };
         // request everything chunk c needs from global memory (clamped positions: every address is valid)
         auto issue = [&](int c) {
-            const float* sc = a.score_t + (((size_t)b * a.nchunk + c) * a.G + grp) * (kQ * kQ);
+            const float4* sc = reinterpret_cast<const float4*>(a.score_op + (((size_t)b * a.nchunk + c) * a.G + grp) * kScoreOp);
 #pragma unroll
             for (int m = 0; m < kMS; m++) {
-                int iblk, jblk, kb, sl;
-                if (slot_of(m, iblk, jblk, kb, sl)) {
-#pragma unroll
-                    for (int e = 0; e < 8; e++) {
-                        const int r = 8 * kb + e;
-                        gt[m][e] = sc[(jblk * 32 + 8 * (r / 4) + 4 * (sl / 32) + (r % 4)) * kQ + iblk * 32 + sl % 32];
-                    }
+                const int sidx = m * kRoleThreads + ptid;
+                if (sidx < kSlots) {
+                    gt[m][0] = sc[2 * sidx];
+                    gt[m][1] = sc[2 * sidx + 1];
                 }
             }
+            const int tau0 = c * kQ + 8 * tg - 3;
+            if (!edge_chunk(c)) {
+                const T* xp = xb + (long long)token_of(tau0) * a.x.st;
 #pragma unroll
-            for (int q = 0; q < 19; q++) {
-                const int tau = min(max(c * kQ + 16 * tg + q - 3, 0), last);
-                xraw[q] = xb[(long long)token_of(tau) * a.x.st];
+                for (int q = 0; q < 11; q++) xraw[q] = *reinterpret_cast<const unsigned*>(xp + q * xstep);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 11; q++)
+                    xraw[q] = *reinterpret_cast<const unsigned*>(xb + (long long)token_of(min(max(tau0 + q, 0), last)) * a.x.st);
             }
             dtraw = dtp[(long long)token_of(min(c * kQ + lane, last)) * a.dt.st];
             const __bf16* csrc = a.c_rows + (((size_t)b * Lpad + (size_t)c * kQ) * a.G + grp) * N;
             const __bf16* bsrc = a.b_t + ((((size_t)b * a.nchunk + c) * a.G + grp) * N) * kQ;
 #pragma unroll
             for (int i = 0; i < kCopy; i++) {
-                const int idx = i * kRoleThreads + ptid;
-                ctile[i] = *reinterpret_cast<const bf16x8*>(csrc + (size_t)(idx / (N / 8)) * a.G * N + (idx % (N / 8)) * 8);
-                btile[i] = *reinterpret_cast<const bf16x8*>(bsrc + (idx / (kQ / 8)) * kQ + (idx % (kQ / 8)) * 8);
+                ctile[i] = *reinterpret_cast<const bf16x8*>(csrc + c_src[i]);
+                btile[i] = *reinterpret_cast<const bf16x8*>(bsrc + b_src[i]);
             }
         };
         // turn the requested data into chunk c's tiles in buffer buf
         auto finish = [&](int c, int buf) {
             // Delta, inclusive cumulative log2-decay and end-of-chunk weight of position `lane` (every producer wave
-            // computes them for itself; the first one publishes them for the consumers)
+            // computes them for itself; the first one publishes exp(l) for the consumers)
             float dl = IoBF16::cvt(dtraw);
             if (a.dt_softplus) dl = softplus(dl + dtb);
             if (c * kQ + lane > last) dl = 0.0f;
-            float l2 = dl * a2;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const float up = __shfl_up(l2, off, 64);
-                if (lane >= off) l2 += up;
-            }
-            const float wgt = fast_exp2(__shfl(l2, 63, 64) - l2) * dl;
-            if (ptid < 64) scal[buf * kQ + lane] = fast_exp2(l2);
+            const float l2 = wave_inclusive_sum(dl * a2);
+            const float l2_end = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(l2), 63));
+            pw_l2[lane] = l2;
+            pw_dl[lane] = dl;
+            pw_wgt[lane] = fast_exp2(l2_end - l2) * dl;
+            if (pwave == 0) scal[buf * kQ + lane] = fast_exp2(l2);
+            __builtin_amdgcn_wave_barrier();
             // masked score operand: (B_j . C_i) exp(l_i - l_j) Delta_j for j <= i, else 0
 #pragma unroll
             for (int m = 0; m < kMS; m++) {
                 int iblk, jblk, kb, sl;
                 if (slot_of(m, iblk, jblk, kb, sl)) {
                     const int i = iblk * 32 + sl % 32;
-                    const float l2i = __shfl(l2, i, 64);
+                    const int jb = jblk * 32 + 16 * kb + 4 * (sl / 32);
+                    const float l2i = pw_l2[i];
+                    const float4 la = *reinterpret_cast<const float4*>(&pw_l2[jb]), lb = *reinterpret_cast<const float4*>(&pw_l2[jb + 8]);
+                    const float4 da = *reinterpret_cast<const float4*>(&pw_dl[jb]), db = *reinterpret_cast<const float4*>(&pw_dl[jb + 8]);
+                    const float lj[8] = {la.x, la.y, la.z, la.w, lb.x, lb.y, lb.z, lb.w};
+                    const float dj[8] = {da.x, da.y, da.z, da.w, db.x, db.y, db.z, db.w};
+                    const float sv[8] = {gt[m][0].x, gt[m][0].y, gt[m][0].z, gt[m][0].w, gt[m][1].x, gt[m][1].y, gt[m][1].z, gt[m][1].w};
                     bf16x8 v;
 #pragma unroll
                     for (int e = 0; e < 8; e++) {
-                        const int r = 8 * kb + e;
-                        const int j = jblk * 32 + 8 * (r / 4) + 4 * (sl / 32) + (r % 4);
-                        const float val = gt[m][e] * fast_exp2(l2i - __shfl(l2, j, 64)) * __shfl(dl, j, 64);
+                        const int j = jb + (e < 4 ? e : e + 4);
+                        const float val = sv[e] * fast_exp2(l2i - lj[e]) * dj[e];
                         v[e] = (__bf16)(j > i ? 0.0f : val);
                     }
                     *reinterpret_cast<bf16x8*>(&sM(buf)[(((iblk * 2 + jblk) * 2 + kb) * 64 + sl) * 8]) = v;
                 }
             }
-            float xr[19];
+            // conv + SiLU of two channels at 8 positions
+            float xr[2][11];
 #pragma unroll
-            for (int q = 0; q < 19; q++) {
-                const int tau = c * kQ + 16 * tg + q - 3;
-                xr[q] = (tau >= 0 && tau <= last) ? IoBF16::cvt(xraw[q]) : 0.0f;
+            for (int q = 0; q < 11; q++) {
+                xr[0][q] = __uint_as_float(xraw[q] << 16);
+                xr[1][q] = __uint_as_float(xraw[q] & 0xffff0000u);
             }
-            if (c == 0 && a.dir > 0 && a.tail_in) {
+            if (edge_chunk(c)) {
 #pragma unroll
-                for (int q = 0; q < 3; q++) {
-                    const int back = 3 - q;                       // how many tokens before the block
-                    if (tg == 0 && back <= a.K - 1)
-                        xr[q] = IoBF16::ld((const T*)a.tail_in + ((size_t)b * (a.K - 1) + (a.K - 1 - back)) * a.tail_ch + ch0 + pc);
+                for (int q = 0; q < 11; q++) {
+                    const int tau = c * kQ + 8 * tg + q - 3;
+                    if (tau < 0 || tau > last) xr[0][q] = xr[1][q] = 0.0f;
+                }
+                if (c == 0 && a.dir > 0 && a.tail_in && tg == 0) {
+#pragma unroll
+                    for (int q = 0; q < 3; q++) {
+                        const int back = 3 - q;                       // how many tokens before the block
+                        if (back <= a.K - 1) {
+                            const T* tp = (const T*)a.tail_in + ((size_t)b * (a.K - 1) + (a.K - 1 - back)) * a.tail_ch + ch0 + 2 * cp;
+                            xr[0][q] = IoBF16::ld(tp);
+                            xr[1][q] = IoBF16::ld(tp + 1);
+                        }
+                    }
                 }
             }
-            bf16x8 vx[2], vw[2];
+            const float4 wa = *reinterpret_cast<const float4*>(&pw_wgt[8 * tg]), wb = *reinterpret_cast<const float4*>(&pw_wgt[8 * tg + 4]);
+            const float wq[8] = {wa.x, wa.y, wa.z, wa.w, wb.x, wb.y, wb.z, wb.w};
 #pragma unroll
-            for (int q = 0; q < 16; q++) {
-                float pre = cbias;
-                pre = fmaf(w4[0], xr[q], pre);
-                pre = fmaf(w4[1], xr[q + 1], pre);
-                pre = fmaf(w4[2], xr[q + 2], pre);
-                pre = fmaf(w4[3], xr[q + 3], pre);
-                const float xc = silu(pre);
-                vx[q / 8][q % 8] = (__bf16)xc;
-                vw[q / 8][q % 8] = (__bf16)(xc * __shfl(wgt, 16 * tg + q, 64));
-            }
+            for (int h2 = 0; h2 < 2; h2++) {
+                bf16x8 vx, vw;
 #pragma unroll
-            for (int q = 0; q < 2; q++) {
-                *reinterpret_cast<bf16x8*>(&sXc(buf)[pc * kRowT + 16 * tg + 8 * q]) = vx[q];
-                *reinterpret_cast<bf16x8*>(&sXw(buf)[pc * kRowT + 16 * tg + 8 * q]) = vw[q];
+                for (int q = 0; q < 8; q++) {
+                    float pre = cbias[h2];
+                    pre = fmaf(w4[h2][0], xr[h2][q], pre);
+                    pre = fmaf(w4[h2][1], xr[h2][q + 1], pre);
+                    pre = fmaf(w4[h2][2], xr[h2][q + 2], pre);
+                    pre = fmaf(w4[h2][3], xr[h2][q + 3], pre);
+                    const float xc = silu(pre);
+                    vx[q] = (__bf16)xc;
+                    vw[q] = (__bf16)(xc * wq[q]);
+                }
+                *reinterpret_cast<bf16x8*>(&sXc(buf)[(2 * cp + h2) * kRowT + 8 * tg]) = vx;
+                *reinterpret_cast<bf16x8*>(&sXw(buf)[(2 * cp + h2) * kRowT + 8 * tg]) = vw;
             }
 #pragma unroll
             for (int i = 0; i < kCopy; i++) {
-                const int idx = i * kRoleThreads + ptid;
-                *reinterpret_cast<bf16x8*>(&sC(buf)[(idx / (N / 8)) * kRowC + (idx % (N / 8)) * 8]) = ctile[i];
-                *reinterpret_cast<bf16x8*>(&sBT(buf)[(idx / (kQ / 8)) * kRowT + (idx % (kQ / 8)) * 8]) = btile[i];
+                *reinterpret_cast<bf16x8*>(&sC(buf)[c_dst[i]]) = ctile[i];
+                *reinterpret_cast<bf16x8*>(&sBT(buf)[b_dst[i]]) = btile[i];
             }
+            __builtin_amdgcn_wave_barrier();   // the next chunk's scan results overwrite pw_* only after these reads
         };
         issue(0);
         finish(0, 0);
