@@ -164,8 +164,7 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
     constexpr int kRoleThreads = 4 * P;
     constexpr int kRowC = Lds::kRowC, kRowT = Lds::kRowT;
     constexpr int kCopy = kQ * N / 8 / kRoleThreads;   // 16-byte pieces of each tile per producer thread
-    constexpr int kSlots = 3 * 2 * 64;                 // operand slots (8 values) of the lower-triangular score blocks
-    constexpr int kMS = (kSlots + kRoleThreads - 1) / kRoleThreads;
+    constexpr int kHS = 2 * 3 * 2 * 64 / kRoleThreads;   // half operand slots (4 values) of the lower-triangular score blocks per producer thread
     using T = unsigned short;
     extern __shared__ __attribute__((aligned(16))) unsigned char ssd_lds[];
     __bf16* const tiles = reinterpret_cast<__bf16*>(ssd_lds);
@@ -223,31 +222,20 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
         unsigned xraw[11];   // channel pair at positions 8*tg - 3 .. 8*tg + 7
         T dtraw;
         bf16x8 ctile[kCopy], btile[kCopy];
-        float4 gt[kMS][2];
-        // Score operand slot s = m*kRoleThreads + ptid: block pair (iblk, jblk) = (0,0), (1,0), (1,1) for s / 128,
-        // k-block (s / 64) % 2, operand lane s % 64.  Its 8 values are column i = iblk*32 + lane%32 of rows
-        // j = jblk*32 + 16*kb + 4*(lane/32) + {0..3, 8..11} (the accumulator-register order, see the header comment).
-        auto slot_of = [&](int m, int& iblk, int& jblk, int& kb, int& sl) {
-            const int sidx = m * kRoleThreads + ptid;
-            const int bp = sidx / 128;
-            iblk = bp > 0;
-            jblk = bp > 1;
-            kb = (sidx / 64) % 2;
-            sl = sidx % 64;
-            return sidx < kSlots;
-        };
+        float4 gt[kHS];
+        // Score operand half-slot hs = m*kRoleThreads + ptid: slot hs/2 is block pair (iblk, jblk) = (0,0), (1,0), (1,1)
+        // for hs / 256, k-block (hs / 128) % 2, operand lane (hs / 2) % 64; the half hs % 2 holds column
+        // i = iblk*32 + lane%32 of rows j = jblk*32 + 16*kb + 8*(hs%2) + 4*(lane/32) + 0..3 (the accumulator-register
+        // order, see the header comment).
         auto edge_chunk = [&](int c) { return c == 0 || c * kQ + kQ - 1 > last; };
-        // request everything chunk c needs from global memory (clamped positions: every address is valid)
-        auto issue = [&](int c) {
+        // The global loads of a chunk, one group per stage of `finish` (clamped positions: every address is valid).
+        auto issue_dt = [&](int c) { dtraw = dtp[(long long)token_of(min(c * kQ + lane, last)) * a.dt.st]; };
+        auto issue_score = [&](int c) {
             const float4* sc = reinterpret_cast<const float4*>(a.score_op + (((size_t)b * a.nchunk + c) * a.G + grp) * kScoreOp);
 #pragma unroll
-            for (int m = 0; m < kMS; m++) {
-                const int sidx = m * kRoleThreads + ptid;
-                if (sidx < kSlots) {
-                    gt[m][0] = sc[2 * sidx];
-                    gt[m][1] = sc[2 * sidx + 1];
-                }
-            }
+            for (int m = 0; m < kHS; m++) gt[m] = sc[m * kRoleThreads + ptid];
+        };
+        auto issue_x = [&](int c) {
             const int tau0 = c * kQ + 8 * tg - 3;
             if (!edge_chunk(c)) {
                 const T* xp = xb + (long long)token_of(tau0) * a.x.st;
@@ -258,7 +246,8 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
                 for (int q = 0; q < 11; q++)
                     xraw[q] = *reinterpret_cast<const unsigned*>(xb + (long long)token_of(min(max(tau0 + q, 0), last)) * a.x.st);
             }
-            dtraw = dtp[(long long)token_of(min(c * kQ + lane, last)) * a.dt.st];
+        };
+        auto issue_tiles = [&](int c) {
             const __bf16* csrc = a.c_rows + (((size_t)b * Lpad + (size_t)c * kQ) * a.G + grp) * N;
             const __bf16* bsrc = a.b_t + ((((size_t)b * a.nchunk + c) * a.G + grp) * N) * kQ;
 #pragma unroll
@@ -267,11 +256,14 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
                 btile[i] = *reinterpret_cast<const bf16x8*>(bsrc + b_src[i]);
             }
         };
-        // turn the requested data into chunk c's tiles in buffer buf
-        auto finish = [&](int c, int buf) {
+        // Turn the data requested for chunk c into its tiles in buffer buf.  Each stage, once it has taken its inputs
+        // out of the load registers, requests the same data of chunk cn (the chunk this wave handles next), so every
+        // load has a whole chunk period to arrive.
+        auto finish = [&](int c, int buf, int cn) {
             // Delta, inclusive cumulative log2-decay and end-of-chunk weight of position `lane` (every producer wave
             // computes them for itself; the first one publishes exp(l) for the consumers)
             float dl = IoBF16::cvt(dtraw);
+            issue_dt(cn);
             if (a.dt_softplus) dl = softplus(dl + dtb);
             if (c * kQ + lane > last) dl = 0.0f;
             const float l2 = wave_inclusive_sum(dl * a2);
@@ -282,27 +274,30 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
             if (pwave == 0) scal[buf * kQ + lane] = fast_exp2(l2);
             __builtin_amdgcn_wave_barrier();
             // masked score operand: (B_j . C_i) exp(l_i - l_j) Delta_j for j <= i, else 0
+            float sv[kHS][4];
 #pragma unroll
-            for (int m = 0; m < kMS; m++) {
-                int iblk, jblk, kb, sl;
-                if (slot_of(m, iblk, jblk, kb, sl)) {
-                    const int i = iblk * 32 + sl % 32;
-                    const int jb = jblk * 32 + 16 * kb + 4 * (sl / 32);
-                    const float l2i = pw_l2[i];
-                    const float4 la = *reinterpret_cast<const float4*>(&pw_l2[jb]), lb = *reinterpret_cast<const float4*>(&pw_l2[jb + 8]);
-                    const float4 da = *reinterpret_cast<const float4*>(&pw_dl[jb]), db = *reinterpret_cast<const float4*>(&pw_dl[jb + 8]);
-                    const float lj[8] = {la.x, la.y, la.z, la.w, lb.x, lb.y, lb.z, lb.w};
-                    const float dj[8] = {da.x, da.y, da.z, da.w, db.x, db.y, db.z, db.w};
-                    const float sv[8] = {gt[m][0].x, gt[m][0].y, gt[m][0].z, gt[m][0].w, gt[m][1].x, gt[m][1].y, gt[m][1].z, gt[m][1].w};
-                    bf16x8 v;
+            for (int m = 0; m < kHS; m++) { sv[m][0] = gt[m].x; sv[m][1] = gt[m].y; sv[m][2] = gt[m].z; sv[m][3] = gt[m].w; }
+            asm volatile("" ::: "memory");   // the re-issue below must not move above the reads of gt
+            issue_score(cn);
 #pragma unroll
-                    for (int e = 0; e < 8; e++) {
-                        const int j = jb + (e < 4 ? e : e + 4);
-                        const float val = sv[e] * fast_exp2(l2i - lj[e]) * dj[e];
-                        v[e] = (__bf16)(j > i ? 0.0f : val);
-                    }
-                    *reinterpret_cast<bf16x8*>(&sM(buf)[(((iblk * 2 + jblk) * 2 + kb) * 64 + sl) * 8]) = v;
+            for (int m = 0; m < kHS; m++) {
+                const int hs = m * kRoleThreads + ptid;
+                const int bp = hs / 256, kb = (hs / 128) % 2, sl = (hs / 2) % 64, hi = hs % 2;
+                const int iblk = bp > 0, jblk = bp > 1;
+                const int i = iblk * 32 + sl % 32;
+                const int jb = jblk * 32 + 16 * kb + 8 * hi + 4 * (sl / 32);
+                const float l2i = pw_l2[i];
+                const float4 la = *reinterpret_cast<const float4*>(&pw_l2[jb]);
+                const float4 da = *reinterpret_cast<const float4*>(&pw_dl[jb]);
+                const float lj[4] = {la.x, la.y, la.z, la.w};
+                const float dj[4] = {da.x, da.y, da.z, da.w};
+                bf16x4 v;
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    const float val = sv[m][e] * fast_exp2(l2i - lj[e]) * dj[e];
+                    v[e] = (__bf16)(jb + e > i ? 0.0f : val);
                 }
+                *reinterpret_cast<bf16x4*>(&sM(buf)[(((iblk * 2 + jblk) * 2 + kb) * 64 + sl) * 8 + 4 * hi]) = v;
             }
             // conv + SiLU of two channels at 8 positions
             float xr[2][11];
@@ -311,6 +306,8 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
                 xr[0][q] = __uint_as_float(xraw[q] << 16);
                 xr[1][q] = __uint_as_float(xraw[q] & 0xffff0000u);
             }
+            asm volatile("" ::: "memory");
+            issue_x(cn);
             if (edge_chunk(c)) {
 #pragma unroll
                 for (int q = 0; q < 11; q++) {
@@ -353,17 +350,18 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
                 *reinterpret_cast<bf16x8*>(&sC(buf)[c_dst[i]]) = ctile[i];
                 *reinterpret_cast<bf16x8*>(&sBT(buf)[b_dst[i]]) = btile[i];
             }
+            asm volatile("" ::: "memory");
+            issue_tiles(cn);
             __builtin_amdgcn_wave_barrier();   // the next chunk's scan results overwrite pw_* only after these reads
         };
-        issue(0);
-        finish(0, 0);
-        if (a.nchunk > 1) issue(1);
+        issue_dt(0);
+        issue_score(0);
+        issue_x(0);
+        issue_tiles(0);
+        finish(0, 0, min(1, a.nchunk - 1));
         lds_barrier();
         for (int c = 0; c < a.nchunk; c++) {
-            if (c + 1 < a.nchunk) {
-                finish(c + 1, (c + 1) & 1);
-                if (c + 2 < a.nchunk) issue(c + 2);
-            }
+            if (c + 1 < a.nchunk) finish(c + 1, (c + 1) & 1, min(c + 2, a.nchunk - 1));
             lds_barrier();
         }
         return;
