@@ -248,8 +248,8 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
     char* ws = static_cast<char*>(workspace);
 
     if (d->batch > 0 && d->seqlen > 0) {
-        // 1. fp32 B|C rows per direction
-        const int nbuf = plan.two_bc ? 2 : 1;
+        // 1. fp32 B|C rows per direction (the chunked path prepares its own operand tiles from the raw rows)
+        const int nbuf = plan.ssd ? 0 : plan.two_bc ? 2 : 1;
         for (int s = 0; s < nbuf; s++) {
             const bimamba_inputs* in = s == 0 ? in_f : in_b;
             const bimamba_params* p = s == 0 ? pf : pb;
@@ -274,7 +274,12 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
             const bool raw = !separate && same_tensor(in_f->z, in_b->z);
             for (int s = 0; s < 2; s++) {
                 SsdPrepArgs pa{};
-                pa.bc = reinterpret_cast<const float*>(ws + plan.off_bc[s]);
+                const bimamba_inputs* in = s == 0 ? in_f : in_b;
+                const bimamba_params* p = s == 0 ? pf : pb;
+                pa.B = targ(in->B); pa.C = targ(in->C);
+                pa.conv_w = p->conv_w; pa.conv_b = p->conv_b;
+                pa.tail_in = (s == 0 && block_variant) ? tail_in : nullptr;
+                pa.K = d->d_conv; pa.Dn = d->d_inner; pa.tail_ch = tail_ch; pa.conv_bc = d->conv_bc;
                 pa.c_rows = reinterpret_cast<__bf16*>(ws + plan.off_crows[s]);
                 pa.b_t = reinterpret_cast<__bf16*>(ws + plan.off_bt[s]);
                 pa.score_op = reinterpret_cast<float*>(ws + plan.off_score[s]);

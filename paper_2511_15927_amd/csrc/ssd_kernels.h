@@ -30,35 +30,79 @@ constexpr int kPadK = 8;   // bf16 elements of row padding in LDS tiles (keeps 1
 constexpr int kScoreOp = 3 * 2 * 64 * 8;   // floats of one chunk's score tile: 3 lower-triangular 32x32 blocks
 
 struct SsdPrepArgs {
-    const float* bc;   // fp32 B|C rows [batch][L][G][2N] in token order (from prep_bc_kernel)
+    TensorArg B, C;       // bf16 [batch][L][G*N]
+    const float* conv_w;  // full [conv_ch][K] table of this direction (rows Dn.. are B|C) when conv_bc
+    const float* conv_b;  // or null
+    const void* tail_in;  // bf16 [batch][K-1][tail_ch] or null (causal direction of the block variant)
     __bf16* c_rows;    // [batch][Lpad][G][N], scan order
     __bf16* b_t;       // [batch][nchunk][G][N][64], scan order inside the chunk
     float* score_op;   // [batch][nchunk][G][kScoreOp]: B_j . C_i for j, i in the chunk, MFMA operand order (see the kernel)
-    int L, G, dir;     // dir +1: scan position tau is token tau; -1: token L-1-tau
+    int L, G, K, Dn, tail_ch, conv_bc;
+    int dir;           // +1: scan position tau is token tau; -1: token L-1-tau
 };
 
 template <int N>
 constexpr size_t ssd_prep_lds_bytes() { return 2 * (size_t)kQ * (N + 1) * sizeof(float); }
 
-// grid (nchunk, G, batch), block 256, dynamic LDS ssd_prep_lds_bytes<N>()
+// grid (nchunk, G, batch), block 256, dynamic LDS ssd_prep_lds_bytes<N>().  Reads the raw B and C rows of one chunk
+// (plus the conv halo), applies the short conv + SiLU along the scan direction when they pass through it, and
+// keeps the fp32 result in LDS for the three outputs.
 template <int N>
 __global__ __launch_bounds__(256) void ssd_prep_kernel(const SsdPrepArgs a)
 {
+    using T = unsigned short;
     extern __shared__ __attribute__((aligned(16))) unsigned char ssd_prep_lds[];
     float(*sB)[N + 1] = reinterpret_cast<float(*)[N + 1]>(ssd_prep_lds);
     float(*sC)[N + 1] = sB + kQ;
     const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     const int nchunk = gridDim.x;
-    for (int idx = tid; idx < kQ * 2 * N; idx += 256) {
-        const int j = idx / (2 * N), col = idx % (2 * N);
-        const int tau = c * kQ + j;
-        float v = 0.0f;
-        if (tau < a.L) {
-            const int t = a.dir > 0 ? tau : a.L - 1 - tau;
-            v = a.bc[(((size_t)b * a.L + t) * a.G + g) * (2 * N) + col];
+    {
+        constexpr int kCols = 2 * N, kParts = 256 / kCols, kLen = kQ / kParts;
+        const int col = tid % kCols, seg = tid / kCols;   // one column of B|C, positions seg*kLen .. of the chunk
+        const int which = col / N, n = col % N;
+        const TensorArg& src = which ? a.C : a.B;
+        const T* base = (const T*)src.p + (size_t)b * src.sb + g * N + n;
+        const int last = a.L - 1;
+        const int row = a.Dn + which * a.G * N + g * N + n;   // this column's conv channel
+        float w4[4] = {0.0f, 0.0f, 0.0f, 0.0f}, bias = 0.0f;   // w4[3] on the current position
+        if (a.conv_bc) {
+#pragma unroll
+            for (int i = 0; i < 4; i++) w4[3 - i] = i < a.K ? a.conv_w[(size_t)row * a.K + (a.K - 1 - i)] : 0.0f;
+            bias = a.conv_b ? a.conv_b[row] : 0.0f;
         }
-        if (col < N) sB[j][col] = v;
-        else sC[j][col - N] = v;
+        const int tau0 = c * kQ + seg * kLen - 3;
+        T raw[kLen + 3];
+#pragma unroll
+        for (int q = 0; q < kLen + 3; q++) {
+            const int tau = min(max(tau0 + q, 0), last);
+            raw[q] = base[(long long)(a.dir > 0 ? tau : last - tau) * src.st];
+        }
+        float xr[kLen + 3];
+#pragma unroll
+        for (int q = 0; q < kLen + 3; q++) xr[q] = (tau0 + q >= 0 && tau0 + q <= last) ? IoBF16::cvt(raw[q]) : 0.0f;
+        if (c == 0 && seg == 0 && a.dir > 0 && a.tail_in && a.conv_bc) {
+#pragma unroll
+            for (int q = 0; q < 3; q++) {
+                const int back = 3 - q;   // how many tokens before the block
+                if (back <= a.K - 1)
+                    xr[q] = IoBF16::ld((const T*)a.tail_in + ((size_t)b * (a.K - 1) + (a.K - 1 - back)) * a.tail_ch + row);
+            }
+        }
+        float(*dstm)[N + 1] = which ? sC : sB;
+#pragma unroll
+        for (int i = 0; i < kLen; i++) {
+            float v = xr[i + 3];
+            if (a.conv_bc) {
+                float pre = bias;
+                pre = fmaf(w4[0], xr[i], pre);
+                pre = fmaf(w4[1], xr[i + 1], pre);
+                pre = fmaf(w4[2], xr[i + 2], pre);
+                pre = fmaf(w4[3], xr[i + 3], pre);
+                v = silu(pre);
+            }
+            if (tau0 + 3 + i > last) v = 0.0f;
+            dstm[seg * kLen + i][n] = v;
+        }
     }
     __syncthreads();
     const size_t Lpad = (size_t)nchunk * kQ;
