@@ -22,7 +22,19 @@
  * allocates nothing, keeps no pointer after a call returns and has no global state (bimamba_profile_next_call
  * excepted).  Activations are
  * token-major with the channel dimension contiguous; batch and token strides are given in elements.
- * All math is fp32; bf16 I/O is widened on load and rounded to nearest-even once at the final store.
+ *
+ * Arithmetic: state, decay factors, gate and the sum of eq. 6 are fp32; bf16 I/O is widened on load and rounded
+ * to nearest-even once at the final store.  Two kernel families implement the same formulas:
+ *   - lane-per-chain kernels (every descriptor): one (direction, batch, channel) recurrence per lane group, all
+ *     products and sums in fp32.  When a head's A[h, 0..N-1] is an arithmetic progression in n (checked on the
+ *     device, bf16 I/O, d_state <= 32) the N decay factors of a token are formed as a_0 * r^n by repeated
+ *     multiplication from two exponentials instead of N exponentials.
+ *   - chunked matrix-core kernels (a_kind = SCALAR_PER_HEAD, bf16 I/O, d_state 64 or 128, 32 or 64 channels per
+ *     head, time_chunks = state_split = 0): the recurrence over 64-token chunks as dense products on the MFMA
+ *     units; their operands (conv output, B, C, the decayed score tile, a copy of the state) are rounded to bf16,
+ *     accumulation and the carried state stay fp32.  Setting time_chunks or state_split, or passing x / z / out
+ *     tensors that cannot be accessed as aligned runs of 2 (x) or 4 (z, out) channels, selects the lane-per-chain
+ *     kernels for the call; the workspace size covers both.
  *
  * Execution: calls validate their arguments on the host, enqueue kernels on the caller's HIP stream
  * and return without synchronising.  Calls on different streams are independent as long as their
@@ -78,11 +90,12 @@ typedef struct bimamba_desc {
     int32_t dt_softplus;    /* 0 or 1 */
     int32_t conv_bc;        /* 0 or 1 */
     int32_t combine;        /* bimamba_combine */
-    int32_t time_chunks;    /* 0 = let the library choose; n >= 1 forces n time segments per sequence
-                               (segments are scanned in parallel and stitched by a carry pass) */
-    int32_t state_split;    /* 0 = let the library choose; 1, 2 or 4 forces that many lanes per (direction, channel)
-                               chain, each holding d_state / state_split states (2 needs d_state 16 or 32, 4 needs
-                               d_state >= 16); results differ only by the summation order of C_t . h_t */
+    int32_t time_chunks;    /* 0 = let the library choose; n >= 1 forces the lane-per-chain kernels with n time segments
+                               per sequence (segments are scanned in parallel and stitched by a carry pass) */
+    int32_t state_split;    /* 0 = let the library choose; 1, 2 or 4 forces the lane-per-chain kernels with that many lanes
+                               per (direction, channel) chain, each holding d_state / state_split states (2 needs
+                               d_state 16 or 32, 4 needs d_state >= 16); results differ only by the summation order of
+                               C_t . h_t */
 } bimamba_desc;
 
 /* Per-direction parameters, device pointers, fp32, contiguous.
@@ -144,13 +157,14 @@ int bimamba_block_fwd(const bimamba_desc* desc, const bimamba_params* pf, const 
 /* Bytes of device scratch the two calls above need for this descriptor (0 on an invalid descriptor).  Pure host code. */
 size_t bimamba_workspace_bytes(const bimamba_desc* desc, int block_variant);
 
-/* Number of time segments the library would use for this descriptor (>= 1; 0 on an invalid descriptor).  Pure host code. */
+/* Number of time segments the library would use for this descriptor (>= 1; 1 on the chunked matrix-core path;
+ * 0 on an invalid descriptor).  Pure host code. */
 int bimamba_time_chunks(const bimamba_desc* desc);
 
 /* Benchmark diagnostics: arm a one-shot probe on the calling host thread.  The next bimamba_fwd or
  * bimamba_block_fwd made by this thread records ev_start immediately before and ev_stop immediately after its
- * scan-and-combine kernel (not the B|C preparation, segment summary or tail kernels) on that call's stream, then
- * disarms.  Both are hipEvent_t created by the caller with timing enabled; NULL, NULL disarms.  This thread-local
+ * scan-and-combine kernel (on the chunked matrix-core path: around its two launches, one per direction; never the
+ * B|C preparation, segment summary or tail kernels) on that call's stream, then disarms.  Both are hipEvent_t created by the caller with timing enabled; NULL, NULL disarms.  This thread-local
  * pair is the only state the library keeps between calls. */
 void bimamba_profile_next_call(void* ev_start, void* ev_stop);
 

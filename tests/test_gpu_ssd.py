@@ -85,3 +85,32 @@ def test_ssd_benchmark_shapes_sampled(gpu, oracle):
         ref = oracle.bimamba_fwd(cfg, to_np(pf), to_np(pb), to_np(inp), sel=sel)
         got = gpu.gpu_fwd(cfg, pf, pb, inp)[..., sel]
         assert rel_l2(got, ref) < gpu.TOL["bf16"], name
+
+
+@pytest.mark.parametrize("lead", [4, 3])
+def test_ssd_strided_views_and_unaligned_fallback(gpu, oracle, lead):
+    """Inputs as column slices of one projection buffer.  The chunked kernels read x as channel pairs: with an even
+    column offset and even row pitch they run; with an odd offset the call must still succeed (lane-per-chain
+    kernels take over inside the same workspace) and give the same answer."""
+    from paper_2511_15927_amd import binding as bd
+    cfg = synth.m2_cfg(2, 150, 128, headdim=64, d_state=64)
+    pf, pb, inp = case(cfg, 1500)
+    Bt, L, Dn, H, GN = 2, 150, 128, 2, 64
+    widths = dict(z=Dn, x=Dn, B=GN, C=GN, dt=H)
+    pitch = lead + sum(widths.values()) + 6
+    big = torch.zeros(Bt, L, pitch, dtype=torch.bfloat16, device="cuda")
+    views, off = {}, lead
+    for k in ("z", "x", "B", "C", "dt"):
+        views[k] = big[:, :, off:off + widths[k]]
+        views[k].copy_(inp[k].reshape(Bt, L, -1).to(torch.bfloat16))
+        off += widths[k]
+    assert (views["x"].data_ptr() % 4 == 0) == (lead % 2 == 0)
+    desc = bd.make_desc(cfg)
+    out_big = torch.zeros(Bt, L, Dn + 8, dtype=torch.bfloat16, device="cuda")
+    out = out_big[:, :, 4:4 + Dn]
+    dpf, dpb, ws = bd.to_device(pf), bd.to_device(pb), bd.alloc_workspace(desc)
+    bd.bimamba_fwd(desc, bd.make_params(dpf), bd.make_params(dpb), bd.make_inputs(views), None, bd.make_tensor(out), ws)
+    torch.cuda.synchronize()
+    ref = oracle.bimamba_fwd(cfg, to_np(pf), to_np(pb), to_np(inp))
+    assert rel_l2(out.float().cpu().numpy(), ref) < gpu.TOL["bf16"]
+    assert torch.all(out_big[:, :, :4] == 0) and torch.all(out_big[:, :, 4 + Dn:] == 0)
