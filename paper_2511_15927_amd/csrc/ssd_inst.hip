@@ -2,17 +2,26 @@
 #include "ssd_kernels.h"
 #include "launch.h"
 
+#include <atomic>
+
 namespace bm {
+
+// Raising a kernel's dynamic-LDS limit is idempotent; it is done once per (kernel, device).
+constexpr int kMaxDevices = 64;
+static bool first_use_on_current_device(std::atomic<bool>* seen)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return true;
+    return !seen[dev].exchange(true);
+}
 
 template <int N>
 static void prep_one(const SsdPrepArgs& pa, int nchunk, int batch, hipStream_t st)
 {
-    static bool configured = false;  // raising the dynamic-LDS limit is idempotent; done once per process and size
-    if (!configured) {
+    static std::atomic<bool> seen[kMaxDevices];
+    if (first_use_on_current_device(seen))
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ssd_prep_kernel<N>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)(ssd_prep_lds_bytes<N>()));
-        configured = true;
-    }
     const size_t lds = ssd_prep_lds_bytes<N>();
     hipLaunchKernelGGL((ssd_prep_kernel<N>), dim3((unsigned)nchunk, (unsigned)pa.G, (unsigned)batch), dim3(256), lds, st, pa);
 }
@@ -20,14 +29,12 @@ static void prep_one(const SsdPrepArgs& pa, int nchunk, int batch, hipStream_t s
 template <int N, int P>
 static void scan_one(const SsdArgs& sa, int batch, hipStream_t st)
 {
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> seen[kMaxDevices];
+    if (first_use_on_current_device(seen))
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ssd_kernel<N, P>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)(SsdLds<N, P>::bytes()));
-        configured = true;
-    }
     const size_t lds = SsdLds<N, P>::bytes();
-    hipLaunchKernelGGL((ssd_kernel<N, P>), dim3((unsigned)sa.H, 1, (unsigned)batch), dim3(8 * P), lds, st, sa);
+    hipLaunchKernelGGL((ssd_kernel<N, P>), dim3((unsigned)sa.H, 1, (unsigned)batch), dim3(4 * P + 256), lds, st, sa);
 }
 
 bool ssd_supported(int d_state, int headdim) { return (d_state == 64 || d_state == 128) && (headdim == 32 || headdim == 64); }

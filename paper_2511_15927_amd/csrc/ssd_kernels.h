@@ -169,7 +169,7 @@ struct SsdLds {
     static constexpr int kM = 2 * 2 * 2 * 64 * 8;   // masked, decayed score tile as MFMA operands [iblk][jblk][kb][lane][8]
     static constexpr int kTileElems = kC + kBT + 2 * kX + kM;
     static constexpr int kHT = (N / 32) * (P / 32) * 2 * 64 * 8;   // state operand copy, bf16
-    static constexpr int kProducerWaves = 4 * P / 64;
+    static constexpr int kProducerWaves = 4;
     // + exp(l_i) per buffer, + per producer wave: cumulative log2 decay, Delta, end-of-chunk weight of each position
     static constexpr size_t bytes() { return (size_t)(2 * kTileElems + 2 * kHT) * sizeof(__bf16) + (2 + 3 * kProducerWaves) * kQ * sizeof(float); }
 };
@@ -192,23 +192,25 @@ __device__ __forceinline__ float wave_inclusive_sum(float v)
     return v;
 }
 
-// grid (H, 1, batch), block 8*P, dynamic LDS SsdLds<N, P>::bytes().  x is read as pairs of channels: its pointer must be
-// 4-byte aligned and its strides even (the host checks).
+// grid (H, 1, batch), block 4*P + 256, dynamic LDS SsdLds<N, P>::bytes().  x is read as pairs of channels: its pointer
+// must be 4-byte aligned and its strides even (the host checks).
 // The first P/16 waves are consumers: wave w owns output rows iblk*32.. and channels pblk*32.. of every chunk and N/64
-// of the 32x32 blocks of H; they build the masked score operand, run the MFMAs and store.  The last P/16 waves are
-// producers: one chunk ahead they compute Delta and the cumulative decay, run conv + SiLU, and stage the C / B^T
-// tiles, with the global loads of the chunk after that already in flight.  One LDS barrier per chunk.
+// of the 32x32 blocks of H; they run the MFMAs, gate, combine and store.  The last four waves are producers: one
+// chunk ahead they compute Delta and the cumulative decay, build the masked decayed score operand, run conv + SiLU,
+// and stage the C / B^T tiles, with the global loads of the chunk after that already in flight.  One LDS barrier per
+// chunk.  (The producers' per-head work does not shrink with the head width, so their count does not either.)
 template <int N, int P>
-__global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
+__global__ __launch_bounds__(4 * P + 256) void ssd_kernel(const SsdArgs a)
 {
     using Lds = SsdLds<N, P>;
     constexpr int kPB = P / 32;       // channel blocks
     constexpr int kNB = N / 32;       // state blocks
     constexpr int kHB = kNB / 2;      // state blocks owned per consumer wave
-    constexpr int kRoleThreads = 4 * P;
+    constexpr int kConsThreads = 4 * P;   // one consumer wave per 32 x 32 block of a chunk's output
+    constexpr int kProdThreads = 256;
     constexpr int kRowC = Lds::kRowC, kRowT = Lds::kRowT;
-    constexpr int kCopy = kQ * N / 8 / kRoleThreads;   // 16-byte pieces of each tile per producer thread
-    constexpr int kHS = 2 * 3 * 2 * 64 / kRoleThreads;   // half operand slots (4 values) of the lower-triangular score blocks per producer thread
+    constexpr int kCopy = kQ * N / 8 / kProdThreads;   // 16-byte pieces of each tile per producer thread
+    constexpr int kHS = 2 * 3 * 2 * 64 / kProdThreads;   // half operand slots (4 values) of the lower-triangular score blocks per producer thread
     using T = unsigned short;
     extern __shared__ __attribute__((aligned(16))) unsigned char ssd_lds[];
     __bf16* const tiles = reinterpret_cast<__bf16*>(ssd_lds);
@@ -222,7 +224,7 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const bool producer = wave >= kRoleThreads / 64;
+    const bool producer = wave >= kConsThreads / 64;
     const int head = blockIdx.x, b = blockIdx.z;
     const int grp = head / a.HG;
     const int ch0 = head * P;
@@ -233,9 +235,10 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
     if (producer) {
         // ------------------------------------------------------------------ producers
         constexpr int kCP = P / 2;                 // channel pairs of the head
-        const int ptid = tid - kRoleThreads;
-        const int pwave = wave - kRoleThreads / 64;
-        const int cp = ptid % kCP, tg = ptid / kCP;   // conv role: channels 2cp, 2cp+1; positions 8*tg .. 8*tg+7 of each chunk
+        constexpr int kPos = kQ * kCP / kProdThreads;   // chunk positions per thread in the conv role (8 or 4)
+        const int ptid = tid - kConsThreads;
+        const int pwave = wave - kConsThreads / 64;
+        const int cp = ptid % kCP, tg = ptid / kCP;   // conv role: channels 2cp, 2cp+1; positions kPos*tg .. of each chunk
         float* const pw_l2 = scal + 2 * kQ + pwave * 3 * kQ;   // wave-private, written and read by this wave only
         float* const pw_dl = pw_l2 + kQ;
         float* const pw_wgt = pw_dl + kQ;
@@ -256,18 +259,18 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
         unsigned c_src[kCopy], b_src[kCopy], c_dst[kCopy], b_dst[kCopy];
 #pragma unroll
         for (int i = 0; i < kCopy; i++) {
-            const int idx = i * kRoleThreads + ptid;
+            const int idx = i * kProdThreads + ptid;
             c_src[i] = (unsigned)(idx / (N / 8)) * a.G * N + (idx % (N / 8)) * 8;
             b_src[i] = (idx / (kQ / 8)) * kQ + (idx % (kQ / 8)) * 8;
             c_dst[i] = (idx / (N / 8)) * kRowC + (idx % (N / 8)) * 8;
             b_dst[i] = (idx / (kQ / 8)) * kRowT + (idx % (kQ / 8)) * 8;
         }
 
-        unsigned xraw[11];   // channel pair at positions 8*tg - 3 .. 8*tg + 7
+        unsigned xraw[kPos + 3];   // channel pair at positions kPos*tg - 3 .. kPos*tg + kPos - 1
         T dtraw;
         bf16x8 ctile[kCopy], btile[kCopy];
         float4 gt[kHS];
-        // Score operand half-slot hs = m*kRoleThreads + ptid: slot hs/2 is block pair (iblk, jblk) = (0,0), (1,0), (1,1)
+        // Score operand half-slot hs = m*kProdThreads + ptid: slot hs/2 is block pair (iblk, jblk) = (0,0), (1,0), (1,1)
         // for hs / 256, k-block (hs / 128) % 2, operand lane (hs / 2) % 64; the half hs % 2 holds column
         // i = iblk*32 + lane%32 of rows j = jblk*32 + 16*kb + 8*(hs%2) + 4*(lane/32) + 0..3 (the accumulator-register
         // order, see the header comment).
@@ -277,17 +280,17 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
         auto issue_score = [&](int c) {
             const float4* sc = reinterpret_cast<const float4*>(a.score_op + (((size_t)b * a.nchunk + c) * a.G + grp) * kScoreOp);
 #pragma unroll
-            for (int m = 0; m < kHS; m++) gt[m] = sc[m * kRoleThreads + ptid];
+            for (int m = 0; m < kHS; m++) gt[m] = sc[m * kProdThreads + ptid];
         };
         auto issue_x = [&](int c) {
-            const int tau0 = c * kQ + 8 * tg - 3;
+            const int tau0 = c * kQ + kPos * tg - 3;
             if (!edge_chunk(c)) {
                 const T* xp = xb + (long long)token_of(tau0) * a.x.st;
 #pragma unroll
-                for (int q = 0; q < 11; q++) xraw[q] = *reinterpret_cast<const unsigned*>(xp + q * xstep);
+                for (int q = 0; q < kPos + 3; q++) xraw[q] = *reinterpret_cast<const unsigned*>(xp + q * xstep);
             } else {
 #pragma unroll
-                for (int q = 0; q < 11; q++)
+                for (int q = 0; q < kPos + 3; q++)
                     xraw[q] = *reinterpret_cast<const unsigned*>(xb + (long long)token_of(min(max(tau0 + q, 0), last)) * a.x.st);
             }
         };
@@ -325,7 +328,7 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
             issue_score(cn);
 #pragma unroll
             for (int m = 0; m < kHS; m++) {
-                const int hs = m * kRoleThreads + ptid;
+                const int hs = m * kProdThreads + ptid;
                 const int bp = hs / 256, kb = (hs / 128) % 2, sl = (hs / 2) % 64, hi = hs % 2;
                 const int iblk = bp > 0, jblk = bp > 1;
                 const int i = iblk * 32 + sl % 32;
@@ -343,10 +346,10 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
                 }
                 *reinterpret_cast<bf16x4*>(&sM(buf)[(((iblk * 2 + jblk) * 2 + kb) * 64 + sl) * 8 + 4 * hi]) = v;
             }
-            // conv + SiLU of two channels at 8 positions
-            float xr[2][11];
+            // conv + SiLU of two channels at kPos positions
+            float xr[2][kPos + 3];
 #pragma unroll
-            for (int q = 0; q < 11; q++) {
+            for (int q = 0; q < kPos + 3; q++) {
                 xr[0][q] = __uint_as_float(xraw[q] << 16);
                 xr[1][q] = __uint_as_float(xraw[q] & 0xffff0000u);
             }
@@ -354,8 +357,8 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
             issue_x(cn);
             if (edge_chunk(c)) {
 #pragma unroll
-                for (int q = 0; q < 11; q++) {
-                    const int tau = c * kQ + 8 * tg + q - 3;
+                for (int q = 0; q < kPos + 3; q++) {
+                    const int tau = c * kQ + kPos * tg + q - 3;
                     if (tau < 0 || tau > last) xr[0][q] = xr[1][q] = 0.0f;
                 }
                 if (c == 0 && a.dir > 0 && a.tail_in && tg == 0) {
@@ -370,13 +373,18 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
                     }
                 }
             }
-            const float4 wa = *reinterpret_cast<const float4*>(&pw_wgt[8 * tg]), wb = *reinterpret_cast<const float4*>(&pw_wgt[8 * tg + 4]);
-            const float wq[8] = {wa.x, wa.y, wa.z, wa.w, wb.x, wb.y, wb.z, wb.w};
+            float wq[kPos];
+#pragma unroll
+            for (int q = 0; q < kPos; q += 4) {
+                const float4 w = *reinterpret_cast<const float4*>(&pw_wgt[kPos * tg + q]);
+                wq[q] = w.x; wq[q + 1] = w.y; wq[q + 2] = w.z; wq[q + 3] = w.w;
+            }
 #pragma unroll
             for (int h2 = 0; h2 < 2; h2++) {
-                bf16x8 vx, vw;
+                typedef __attribute__((__vector_size__(kPos * sizeof(__bf16)))) __bf16 bf16run;
+                bf16run vx, vw;
 #pragma unroll
-                for (int q = 0; q < 8; q++) {
+                for (int q = 0; q < kPos; q++) {
                     float pre = cbias[h2];
                     pre = fmaf(w4[h2][0], xr[h2][q], pre);
                     pre = fmaf(w4[h2][1], xr[h2][q + 1], pre);
@@ -386,8 +394,8 @@ __global__ __launch_bounds__(8 * P) void ssd_kernel(const SsdArgs a)
                     vx[q] = (__bf16)xc;
                     vw[q] = (__bf16)(xc * wq[q]);
                 }
-                *reinterpret_cast<bf16x8*>(&sXc(buf)[(2 * cp + h2) * kRowT + 8 * tg]) = vx;
-                *reinterpret_cast<bf16x8*>(&sXw(buf)[(2 * cp + h2) * kRowT + 8 * tg]) = vw;
+                *reinterpret_cast<bf16run*>(&sXc(buf)[(2 * cp + h2) * kRowT + kPos * tg]) = vx;
+                *reinterpret_cast<bf16run*>(&sXw(buf)[(2 * cp + h2) * kRowT + kPos * tg]) = vw;
             }
 #pragma unroll
             for (int i = 0; i < kCopy; i++) {
