@@ -198,8 +198,8 @@ __device__ __forceinline__ void load_bc_lds(const float* tile, int i, unsigned s
 
 // One token of one chain slice: conv + SiLU, discretise, state updates, skip term, gate, output.
 template <int N, int S, int AKIND, typename IO, int MODE>
-__device__ __forceinline__ void token_step(Chain<N, S, AKIND, IO>& c, typename IO::T xraw, typename IO::T dtraw,
-                                           typename IO::T zraw, float part, bool softplus_dt, const BcRow<N / S>& row)
+__device__ __forceinline__ void token_step(Chain<N, S, AKIND, IO>& c, typename IO::T xraw, float delta,
+                                           typename IO::T zraw, float part, const BcRow<N / S>& row)
 {
     constexpr int NS = N / S;
     const float x0 = IO::cvt(xraw);
@@ -212,8 +212,6 @@ __device__ __forceinline__ void token_step(Chain<N, S, AKIND, IO>& c, typename I
     c.xh[1] = c.xh[0];
     c.xh[0] = x0;
     const float xc = silu(pre);
-    float delta = IO::cvt(dtraw);
-    if (softplus_dt) delta = softplus(delta + c.dtb);
     const float u = delta * xc;
     float y = 0.0f;
     uniform_ro_ptr bcmem = (uniform_ro_ptr)c.bcrow;  // only for S = 1 rows too long to prefetch
@@ -317,6 +315,14 @@ __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, 
                 if constexpr (S > 1) stage_load(TILE);
             }
             const float* tile_bc = lds + buf * (TILE * 2 * N);
+            // Delta of the whole tile up front: one uniform branch per tile instead of one per token
+            float delta[TILE];
+#pragma unroll
+            for (int i = 0; i < TILE; i++) delta[i] = IO::cvt(cur.dt[i]);
+            if (softplus_dt) {
+#pragma unroll
+                for (int i = 0; i < TILE; i++) delta[i] = softplus(delta[i] + c.dtb);
+            }
 #pragma unroll
             for (int i = 0; i < TILE; i++) {
                 BcRow<NS> row_next;
@@ -327,7 +333,7 @@ __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, 
                     load_bc_scalar<N>(done + i + 1 < count ? c.bcrow + c.bcs : c.bcrow, row_next);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                token_step<N, S, AKIND, IO, MODE>(c, cur.x[i], cur.dt[i], cur.z[i], cur.part[i], softplus_dt, row);
+                token_step<N, S, AKIND, IO, MODE>(c, cur.x[i], delta[i], cur.z[i], cur.part[i], row);
                 if constexpr (S > 1) {
                     if (i + 1 < TILE) row = row_next;
                 } else if constexpr (kBcScalarAhead<N, S>) {
@@ -353,7 +359,9 @@ __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, 
         BcRow<NS> row;
         if constexpr (S > 1) load_bc_direct<N, S>(c.bcrow, c.sub, row);
         else if constexpr (kBcScalarAhead<N, S>) load_bc_scalar<N>(c.bcrow, row);
-        token_step<N, S, AKIND, IO, MODE>(c, xr, dr, zr, part, softplus_dt, row);
+        float delta = IO::cvt(dr);
+        if (softplus_dt) delta = softplus(delta + c.dtb);
+        token_step<N, S, AKIND, IO, MODE>(c, xr, delta, zr, part, row);
     }
 }
 
