@@ -17,6 +17,12 @@ constexpr int kTargetWaves = 2048;  // two waves per SIMD on 256 CUs x 4 SIMDs
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline bool is_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+__global__ __launch_bounds__(256) void zero_fill_kernel(float* p, long long n)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0.0f;
+}
+
 bool split_supported(int d_state, int split)
 {
     switch (d_state * 8 + split) {
@@ -344,8 +350,13 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
     } else if (block_variant && d->batch > 0 && h_out && h_out != h_in) {
         // empty block: the state passes through unchanged
         const size_t bytes = (size_t)d->batch * d->d_inner * d->d_state * sizeof(float);
-        if (h_in) (void)hipMemcpyAsync(h_out, h_in, bytes, hipMemcpyDeviceToDevice, st);
-        else (void)hipMemsetAsync(h_out, 0, bytes, st);
+        if (h_in) {
+            (void)hipMemcpyAsync(h_out, h_in, bytes, hipMemcpyDeviceToDevice, st);
+        } else {
+            // a kernel rather than a memset node, so the call stays safe to capture into a HIP graph
+            const long long n = (long long)d->batch * d->d_inner * d->d_state;
+            hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, h_out, n);
+        }
     }
     // 3. conv tail for the next block
     if (block_variant && tail_out && d->batch > 0 && d->d_conv > 1) {

@@ -146,3 +146,35 @@ def test_cfg3_block_diffusion_shapes(gpu, oracle):
                 h_gpu, tail_gpu, h_ref, tail_ref = h_new, tail_new, h_ref_new, tail_ref_new
                 assert rel_l2(h_gpu[:, sel], h_ref[:, sel]) < 1e-5
                 assert np.array_equal(tail_gpu, tail_ref)
+
+
+@pytest.mark.parametrize("layout", ["selective", "mamba2"])
+def test_empty_sequence_and_empty_batch(gpu, oracle, layout):
+    """L = 0: nothing is computed, the cached state and conv tail pass through unchanged (zero state when there is
+    none); batch = 0: a no-op.  Both must return without touching memory they were not given."""
+    from paper_2511_15927_amd import binding as bd
+    if layout == "selective":
+        cfg = synth.mixer_cfg(2, 0, 128, io="bf16")
+    else:
+        cfg = synth.m2_cfg(2, 0, 128, headdim=64, d_state=64)
+    pf, pb = params(cfg, 21)
+    inp = synth.make_inputs(cfg, 21)
+    N, K = cfg["d_state"], cfg["d_conv"]
+    tail_ch = 128 + (2 * N if cfg["conv_bc"] else 0)
+    h0 = (0.1 * torch.randn(2, 128, N, generator=torch.Generator().manual_seed(7))).float()
+    tail0 = synth.round_io(torch.randn(2, K - 1, tail_ch, generator=torch.Generator().manual_seed(8)), "bf16")
+    ref, h_ref, t_ref = oracle.bimamba_block_fwd(cfg, to_np(pf), to_np(pb), to_np(inp), h_in=h0.numpy(), tail_in=tail0.numpy())
+    out, h, tail = gpu.gpu_block_fwd(cfg, pf, pb, inp, h_in=h0, tail_in=tail0)
+    assert out.shape == ref.shape == (2, 0, 128)
+    assert np.array_equal(h, h_ref) and np.array_equal(h, h0.numpy().astype(np.float64))
+    assert np.array_equal(tail, t_ref)
+    # no cached state: the committed state is zero
+    _, h_zero, _ = gpu.gpu_block_fwd(cfg, pf, pb, inp, h_in=None, tail_in=None)
+    assert np.array_equal(h_zero, np.zeros_like(h_zero))
+    # full-sequence entry point on an empty sequence and on an empty batch
+    assert gpu.gpu_fwd(cfg, pf, pb, inp).shape == (2, 0, 128)
+    cfg0 = dict(cfg, batch=0, seqlen=5)
+    inp0 = synth.make_inputs(cfg0, 22)
+    assert gpu.gpu_fwd(cfg0, pf, pb, inp0).shape == (0, 5, 128)
+    desc = bd.make_desc(cfg)
+    assert bd.bimamba_time_chunks(desc) >= 1
