@@ -178,3 +178,54 @@ def test_empty_sequence_and_empty_batch(gpu, oracle, layout):
     assert gpu.gpu_fwd(cfg0, pf, pb, inp0).shape == (0, 5, 128)
     desc = bd.make_desc(cfg)
     assert bd.bimamba_time_chunks(desc) >= 1
+
+
+@pytest.mark.parametrize("layout", ["selective", "mamba2"])
+def test_block_step_replayed_from_a_hip_graph(gpu, layout):
+    """One committing block call captured into a HIP graph: every replay (with eager work and synchronisation between
+    replays, and fresh contents in the static input buffers) must equal the eager call on the same contents bit for bit."""
+    from paper_2511_15927_amd import binding as bd
+    if layout == "selective":
+        cfg = synth.mixer_cfg(4, 32, 256, io="bf16")
+    else:
+        cfg = synth.m2_cfg(4, 32, 256, headdim=64, d_state=64)
+    N, K = cfg["d_state"], cfg["d_conv"]
+    tail_ch = 256 + (2 * N if cfg["conv_bc"] else 0)
+    pf, pb = params(cfg, 31, random_a=False)
+    dpf, dpb = bd.to_device(pf), bd.to_device(pb)
+    cpf, cpb = bd.make_params(dpf), bd.make_params(dpb)
+    desc = bd.make_desc(cfg)
+    static_in = bd.to_device(synth.make_inputs(cfg, 31), cfg)
+    c_in = bd.make_inputs(static_in)
+    h_in = torch.zeros(4, 256, N, dtype=torch.float32, device="cuda")
+    tail_in = torch.zeros(4, K - 1, tail_ch, dtype=torch.bfloat16, device="cuda")
+    h_out, tail_out = torch.empty_like(h_in), torch.empty_like(tail_in)
+    out, ws = bd.alloc_out(cfg), bd.alloc_workspace(desc, 1)
+    c_out = bd.make_tensor(out)
+
+    def call():
+        bd.bimamba_block_fwd(desc, cpf, cpb, c_in, None, h_in, tail_in, h_out, tail_out, c_out, ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for rep in range(3):
+        fresh = bd.to_device(synth.make_inputs(cfg, 40 + rep), cfg)
+        for k in static_in:
+            static_in[k].copy_(fresh[k])
+        h_in.copy_(0.1 * torch.randn(4, 256, N, generator=torch.Generator().manual_seed(50 + rep)))
+        tail_in.copy_(torch.randn(4, K - 1, tail_ch, generator=torch.Generator().manual_seed(60 + rep)).to(torch.bfloat16))
+        call()
+        torch.cuda.synchronize()
+        want = (out.clone(), h_out.clone(), tail_out.clone())
+        out.zero_(); h_out.zero_(); tail_out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want[0]) and torch.equal(h_out, want[1]) and torch.equal(tail_out, want[2]), rep
