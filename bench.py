@@ -143,7 +143,10 @@ def main():
         ach = mflops / (kernel_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                     "frac": ach / PEAK_BF16_MFMA_TFLOPS, "algorithmic_flops": mflops}
-    roofline.update({"traffic": read_traffic("sweep_" + args.workload), "kernel": kernel, "kernel_ms": kernel_ms})
+    traffic = read_traffic("sweep_" + args.workload)
+    if ssd and traffic is not None:
+        traffic *= 2.0   # the summary holds the mean of one launch; the probed interval holds both directions' launches
+    roofline.update({"traffic": traffic, "kernel": kernel, "kernel_ms": kernel_ms})
     result = {
         "metric": "bidirectional-scan tokens/s/GPU at d_inner=4096,L=8K; HBM GB/s vs peak",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
