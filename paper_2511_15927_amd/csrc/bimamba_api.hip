@@ -112,7 +112,8 @@ struct Plan {
 bool use_ssd(const bimamba_desc* d)
 {
     return d->a_kind == BIMAMBA_A_SCALAR_PER_HEAD && d->io_dtype == BIMAMBA_BF16 && d->time_chunks == 0 &&
-           d->state_split == 0 && ssd_supported(d->d_state, d->d_inner / d->n_heads);
+           d->state_split == 0 && ssd_supported(d->d_state, d->d_inner / d->n_heads) &&
+           d->batch <= 32767;   // the preparation kernel's grid holds both directions of every batch element
 }
 
 Plan make_plan(const bimamba_desc* d, bool inputs_shared)
@@ -241,8 +242,9 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
         return BIMAMBA_ERR_MISALIGNED;
     const bool shared = same_inputs(in_f, in_b);
     Plan plan = make_plan(d, shared);
-    // the chunked kernels read x two channels at a time
-    if (plan.ssd && !(pairs_readable(in_f->x) && pairs_readable(in_b->x))) plan.ssd = false;
+    // the chunked kernels read x two channels at a time and the carried state four states at a time
+    if (plan.ssd && !(pairs_readable(in_f->x) && pairs_readable(in_b->x) && is_aligned(h_in, 16) && is_aligned(h_out, 16)))
+        plan.ssd = false;
     if (plan.total > 0) {
         if (!workspace) return BIMAMBA_ERR_NULL_POINTER;
         if (!is_aligned(workspace, 16)) return BIMAMBA_ERR_MISALIGNED;
@@ -278,8 +280,9 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
             // forward scan adds, gates and stores (or each writes its own half)
             const bool separate = d->combine == BIMAMBA_COMBINE_SEPARATE;
             const bool raw = !separate && same_tensor(in_f->z, in_b->z);
+            SsdPrepPair pp{};
             for (int s = 0; s < 2; s++) {
-                SsdPrepArgs pa{};
+                SsdPrepArgs& pa = pp.dir[s];
                 const bimamba_inputs* in = s == 0 ? in_f : in_b;
                 const bimamba_params* p = s == 0 ? pf : pb;
                 pa.B = targ(in->B); pa.C = targ(in->C);
@@ -290,8 +293,8 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
                 pa.b_t = reinterpret_cast<__bf16*>(ws + plan.off_bt[s]);
                 pa.score_op = reinterpret_cast<float*>(ws + plan.off_score[s]);
                 pa.L = d->seqlen; pa.G = d->n_groups; pa.dir = s == 0 ? 1 : -1;
-                launch_ssd_prep(d->d_state, pa, plan.ssd_chunks, d->batch, st);
             }
+            launch_ssd_prep(d->d_state, pp, plan.ssd_chunks, d->batch, st);
             if (probe_start) (void)hipEventRecord(probe_start, st);
             for (int s = 1; s >= 0; s--) {
                 const bimamba_inputs* in = s == 0 ? in_f : in_b;

@@ -20,9 +20,9 @@ BM_DECLARE_SCAN(128, 1)
 BM_DECLARE_SCAN(128, 4)
 #undef BM_DECLARE_SCAN
 
-struct SsdPrepArgs;
+struct SsdPrepPair;
 struct SsdArgs;
 bool ssd_supported(int d_state, int headdim);
-void launch_ssd_prep(int d_state, const SsdPrepArgs& pa, int nchunk, int batch, hipStream_t st);
+void launch_ssd_prep(int d_state, const SsdPrepPair& pa, int nchunk, int batch, hipStream_t st);
 void launch_ssd_scan(int d_state, int headdim, const SsdArgs& sa, int batch, hipStream_t st);
 }  // namespace bm

@@ -16,14 +16,14 @@ static bool first_use_on_current_device(std::atomic<bool>* seen)
 }
 
 template <int N>
-static void prep_one(const SsdPrepArgs& pa, int nchunk, int batch, hipStream_t st)
+static void prep_one(const SsdPrepPair& pa, int nchunk, int batch, hipStream_t st)
 {
     static std::atomic<bool> seen[kMaxDevices];
     if (first_use_on_current_device(seen))
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ssd_prep_kernel<N>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)(ssd_prep_lds_bytes<N>()));
     const size_t lds = ssd_prep_lds_bytes<N>();
-    hipLaunchKernelGGL((ssd_prep_kernel<N>), dim3((unsigned)nchunk, (unsigned)pa.G, (unsigned)batch), dim3(256), lds, st, pa);
+    hipLaunchKernelGGL((ssd_prep_kernel<N>), dim3((unsigned)nchunk, (unsigned)pa.dir[0].G, 2u * (unsigned)batch), dim3(256), lds, st, pa);
 }
 
 template <int N, int P>
@@ -39,7 +39,7 @@ static void scan_one(const SsdArgs& sa, int batch, hipStream_t st)
 
 bool ssd_supported(int d_state, int headdim) { return (d_state == 64 || d_state == 128) && (headdim == 32 || headdim == 64); }
 
-void launch_ssd_prep(int d_state, const SsdPrepArgs& pa, int nchunk, int batch, hipStream_t st)
+void launch_ssd_prep(int d_state, const SsdPrepPair& pa, int nchunk, int batch, hipStream_t st)
 {
     if (d_state == 128) prep_one<128>(pa, nchunk, batch, st);
     else prep_one<64>(pa, nchunk, batch, st);

@@ -41,20 +41,27 @@ struct SsdPrepArgs {
     int dir;           // +1: scan position tau is token tau; -1: token L-1-tau
 };
 
+struct SsdPrepPair {
+    SsdPrepArgs dir[2];   // forward, reverse: one launch prepares both
+};
+
 template <int N>
 constexpr size_t ssd_prep_lds_bytes() { return 2 * (size_t)kQ * (N + 1) * sizeof(float); }
 
-// grid (nchunk, G, batch), block 256, dynamic LDS ssd_prep_lds_bytes<N>().  Reads the raw B and C rows of one chunk
+// grid (nchunk, G, 2 * batch), block 256, dynamic LDS ssd_prep_lds_bytes<N>(); blockIdx.z / batch selects the
+// direction.  Reads the raw B and C rows of one chunk
 // (plus the conv halo), applies the short conv + SiLU along the scan direction when they pass through it, and
 // keeps the fp32 result in LDS for the three outputs.
 template <int N>
-__global__ __launch_bounds__(256) void ssd_prep_kernel(const SsdPrepArgs a)
+__global__ __launch_bounds__(256) void ssd_prep_kernel(const SsdPrepPair both)
 {
     using T = unsigned short;
+    const int batch = gridDim.z / 2;
+    const SsdPrepArgs& a = both.dir[blockIdx.z / batch];
     extern __shared__ __attribute__((aligned(16))) unsigned char ssd_prep_lds[];
     float(*sB)[N + 1] = reinterpret_cast<float(*)[N + 1]>(ssd_prep_lds);
     float(*sC)[N + 1] = sB + kQ;
-    const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z % batch, tid = threadIdx.x;
     const int nchunk = gridDim.x;
     {
         constexpr int kCols = 2 * N, kParts = 256 / kCols, kLen = kQ / kParts;
@@ -446,9 +453,14 @@ __global__ __launch_bounds__(4 * P + 256) void ssd_kernel(const SsdArgs a)
         for (int hb = 0; hb < kHB; hb++) {
             const int nblk = iblk * kHB + hb;
 #pragma unroll
-            for (int r = 0; r < 16; r++) {
-                const int n = nblk * 32 + 4 * half + row_k(r);
-                hacc[hb][r] = a.h_in ? a.h_in[((size_t)b * a.Dn + ch0 + po) * N + n] : 0.0f;
+            for (int r = 0; r < 16; r++) hacc[hb][r] = 0.0f;
+            if (a.h_in) {   // registers 4q .. 4q+3 hold four adjacent states: 16-byte pieces (the host checks alignment)
+                const float* hrow = a.h_in + ((size_t)b * a.Dn + ch0 + po) * N + nblk * 32 + 4 * half;
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const float4 v = *reinterpret_cast<const float4*>(hrow + 8 * q);
+                    hacc[hb][4 * q] = v.x; hacc[hb][4 * q + 1] = v.y; hacc[hb][4 * q + 2] = v.z; hacc[hb][4 * q + 3] = v.w;
+                }
             }
         }
         auto publish_state = [&](int which) {
@@ -604,11 +616,11 @@ __global__ __launch_bounds__(4 * P + 256) void ssd_kernel(const SsdArgs a)
 #pragma unroll
             for (int hb = 0; hb < kHB; hb++) {
                 const int nblk = iblk * kHB + hb;
+                float* hrow = a.h_out + ((size_t)b * a.Dn + ch0 + po) * N + nblk * 32 + 4 * half;
 #pragma unroll
-                for (int r = 0; r < 16; r++) {
-                    const int n = nblk * 32 + 4 * half + row_k(r);
-                    a.h_out[((size_t)b * a.Dn + ch0 + po) * N + n] = hacc[hb][r];
-                }
+                for (int q = 0; q < 4; q++)
+                    *reinterpret_cast<float4*>(hrow + 8 * q) =
+                        make_float4(hacc[hb][4 * q], hacc[hb][4 * q + 1], hacc[hb][4 * q + 2], hacc[hb][4 * q + 3]);
             }
         }
     };

@@ -5,7 +5,8 @@
 Timing only: inputs are drawn on the GPU with the recipe's distributions (parity of every configuration is the
 tests' job).  Covers the 1.3B-scale layer, the long sequence, the headline shape at batch 1 and 8 with structured and
 general A, the Mamba-2 parameterisation, the block-diffusion loop (prefix once, then 32-token blocks re-scanned 8
-times from the cached state, eagerly and as a replayed HIP graph) and the 24-layer batch x length sweep.
+times from the cached state, eagerly and as a replayed HIP graph; then a 24-layer stack per denoising step at block
+lengths 32, 64 and 128, both parameterisations) and the 24-layer batch x length sweep.
 """
 import argparse
 import json
@@ -122,6 +123,58 @@ def time_block_loop(n_blocks=8, steps_per_block=8, prefix=4096):
     return row
 
 
+def time_block_stack(block, layers=synth.CFG4_LAYERS, steps_per_block=8, mamba2=False, batch=16, d_inner=4096):
+    """One denoising step of a `layers`-deep stack on one block: layer l's output is layer l+1's x; z, dt, B, C are
+    shared; every layer has its own parameters, cached state and conv tail.  The step that ends a block commits the
+    caches.  Timed eagerly and as a replayed HIP graph of a whole block (steps_per_block steps)."""
+    cfg = synth.m2_cfg(batch, block, d_inner) if mamba2 else synth.mixer_cfg(batch, block, d_inner)
+    desc = bd.make_desc(cfg)
+    N, K = cfg["d_state"], cfg["d_conv"]
+    tail_ch = d_inner + (2 * cfg["n_groups"] * N if cfg["conv_bc"] else 0)
+    inp = gpu_inputs(cfg)
+    params = [gpu_params(cfg, seed=200 + l) for l in range(layers)]
+    cparams = [(bd.make_params(a), bd.make_params(b)) for a, b in params]
+    h = [torch.zeros(batch, d_inner, N, dtype=torch.float32, device="cuda") for _ in range(layers)]
+    tail = [torch.zeros(batch, K - 1, tail_ch, dtype=torch.bfloat16, device="cuda") for _ in range(layers)]
+    bufs = [inp["x"], bd.alloc_out(cfg), bd.alloc_out(cfg)]
+    ws = bd.alloc_workspace(desc, 1)
+    c_in = [bd.make_inputs(dict(inp, x=b)) for b in bufs]
+    c_out = [bd.make_tensor(b) for b in bufs]
+
+    def one_block():
+        for s in range(steps_per_block):
+            last = s == steps_per_block - 1
+            src = 0
+            for l in range(layers):
+                dst = 1 if src != 1 else 2
+                bd.bimamba_block_fwd(desc, cparams[l][0], cparams[l][1], c_in[src], None, h[l], tail[l],
+                                     h[l] if last else None, tail[l] if last else None, c_out[dst], ws)
+                src = dst
+
+    eager_ms = timed(one_block, 3, 1)
+    graph_ms = None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            one_block()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            one_block()
+        graph_ms = timed(graph.replay, 3, 1)
+    except Exception as exc:  # graph capture is an optimisation of the loop, not part of the path
+        print("graph capture skipped: %r" % (exc,), file=sys.stderr)
+    best = eager_ms if graph_ms is None else min(eager_ms, graph_ms)
+    row = dict(name="block_stack", layout="mamba2" if mamba2 else "selective", batch=batch, block=block, d_inner=d_inner,
+               layers=layers, steps_per_block=steps_per_block, eager_ms_per_block=eager_ms, graph_ms_per_block=graph_ms,
+               us_per_layer_call=best * 1e3 / (layers * steps_per_block),
+               generated_tokens_per_s=batch * block / (best * 1e-3))
+    print(json.dumps(row), flush=True)
+    return row
+
+
 def time_stack(batch, seqlen, layers=synth.CFG4_LAYERS, steps=2):
     """24 mixer layers back to back: layer l's output is layer l+1's x; z, dt, B, C are shared by all layers;
     every layer has its own seeded parameters."""
@@ -179,6 +232,9 @@ def main():
             rows.append(time_fwd("paper_1p3b_layer_b8_L8192", synth.m2_cfg(8, 8192, 3840, headdim=32), steps=2, warmup=1))
     if "block" in want:
         rows.append(time_block_loop())
+        for block in (32, 64, 128):
+            rows.append(time_block_stack(block))
+            rows.append(time_block_stack(block, mamba2=True))
     if "stack" in want:
         for bt in synth.CFG4_BATCHES:
             for L in synth.CFG4_LENGTHS:
