@@ -119,30 +119,36 @@ __global__ __launch_bounds__(256) void ssd_prep_kernel(const SsdPrepPair both)
         const int n2 = idx / kQ, j2 = idx % kQ;
         a.b_t[((((size_t)b * nchunk + c) * a.G + g) * N + n2) * kQ + j2] = (__bf16)sB[j2][n2];
     }
-    // 4 x 4 outputs per thread
-    const int tj = tid / 16, ti = tid % 16;
-    float acc[4][4] = {};
-    for (int n = 0; n < N; n++) {
-        float bv[4], cv[4];
+    // Score tile B_j . C_i on the matrix cores, one 32 x 32 block per wave; only the three blocks on or below the
+    // diagonal are kept.  Each fp32 operand is split into a bf16 head and a bf16 remainder and the three significant
+    // cross products are accumulated in fp32, which keeps about 16 bits of the products.  With B rows as operand A
+    // and C rows as operand B, accumulator register r of lane l is row j%32 = 8*(r/4) + 4*(l/32) + r%4 of column
+    // i%32 = l%32: exactly the order in which the scan kernel feeds the tile to its MFMA as operand A,
+    // [block pair (0,0), (1,0), (1,1)][k-block r/8][lane][r%8].
+    const int wave = tid / 64, lane = tid % 64;
+    if (wave < 3) {
+        const int iblk = wave > 0, jblk = wave > 1;
+        const int rj = jblk * 32 + lane % 32, ri = iblk * 32 + lane % 32, koff = 8 * (lane / 32);
+        f32x16 acc = {0};
+        for (int ks = 0; ks < N / 16; ks++) {
+            bf16x8 ah, al, bh, bl;
 #pragma unroll
-        for (int q = 0; q < 4; q++) { bv[q] = sB[4 * tj + q][n]; cv[q] = sC[4 * ti + q][n]; }
+            for (int e = 0; e < 8; e++) {
+                const float bv = sB[rj][16 * ks + koff + e], cv = sC[ri][16 * ks + koff + e];
+                ah[e] = (__bf16)bv;
+                al[e] = (__bf16)(bv - (float)ah[e]);
+                bh[e] = (__bf16)cv;
+                bl[e] = (__bf16)(cv - (float)bh[e]);
+            }
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, acc, 0, 0, 0);
+        }
+        float* dst = a.score_op + (((size_t)b * nchunk + c) * a.G + g) * kScoreOp + ((size_t)(wave * 2) * 64 + lane) * 8;
 #pragma unroll
-        for (int q = 0; q < 4; q++)
-#pragma unroll
-            for (int r = 0; r < 4; r++) acc[q][r] = fmaf(bv[q], cv[r], acc[q][r]);
-    }
-    // Rows j = 4tj.., columns i = 4ti.. of the tile.  Only blocks on or below the diagonal are kept, in the order the
-    // scan kernel feeds them to the MFMA as operand A: [block pair (0,0), (1,0), (1,1)][k-block][lane][8], where lane
-    // 32h + i%32 holds rows j%32 = 16kb + 8q + 4h + e of column i in slots 4q + e.
-    const int jblk = tj / 8, iblk = ti / 8;
-    if (jblk <= iblk) {
-        float* dst = a.score_op + (((size_t)b * nchunk + c) * a.G + g) * kScoreOp;
-        const int jj = (4 * tj) % 32, kb = jj / 16, q = (jj % 16) / 8, h = (jj % 8) / 4;
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-            const int sl = 32 * h + (4 * ti + r) % 32;
-            *reinterpret_cast<float4*>(dst + ((((iblk + jblk) * 2 + kb) * 64 + sl) * 8 + 4 * q)) =
-                make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
+        for (int kb = 0; kb < 2; kb++) {
+            *reinterpret_cast<float4*>(dst + kb * 64 * 8) = make_float4(acc[8 * kb], acc[8 * kb + 1], acc[8 * kb + 2], acc[8 * kb + 3]);
+            *reinterpret_cast<float4*>(dst + kb * 64 * 8 + 4) = make_float4(acc[8 * kb + 4], acc[8 * kb + 5], acc[8 * kb + 6], acc[8 * kb + 7]);
         }
     }
 }
