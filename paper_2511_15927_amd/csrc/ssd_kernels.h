@@ -554,8 +554,10 @@ __global__ __launch_bounds__(4 * P + 256) void ssd_kernel(const SsdArgs a)
                     }
                 }
             }
-            // ---- state update of the blocks this wave owns
-            {
+            // ---- state update of the blocks this wave owns (the state after the last chunk matters only if it is
+            // committed)
+            const bool state_needed = c + 1 < a.nchunk || a.h_out != nullptr;
+            if (state_needed) {
                 const __bf16* b_t = sBT(buf);
                 const __bf16* xw_t = sXw(buf);
                 const float decay_q = el[kQ - 1];
@@ -613,8 +615,10 @@ __global__ __launch_bounds__(4 * P + 256) void ssd_kernel(const SsdArgs a)
                     }
                 }
             }
-            issue_gate(min(c + 1, a.nchunk - 1));
-            publish_state(buf ^ 1);
+            if (c + 1 < a.nchunk) {
+                issue_gate(c + 1);
+                publish_state(buf ^ 1);
+            }
             state_nonzero = true;
             lds_barrier();
         }
