@@ -84,3 +84,27 @@ def test_random_descriptor(gpu, oracle, seed):
     assert rel_l2(h, h_ref) < (1e-2 if mfma else 1e-5), (layout, cfg)
     if K > 1:
         assert np.array_equal(tail, t_ref)
+
+
+@pytest.mark.parametrize("layout", ["selective", "mamba2_mfma", "mamba2_valu"])
+def test_extreme_decay_and_silent_stretches(gpu, oracle, layout):
+    """Steps large enough to wipe the state within one token (Delta * |A| up to ~800), steps of zero, and stretches of
+    zero input: the decay factors under- and overflow only where the result is masked or multiplied by zero, so the
+    output must stay finite and within tolerance."""
+    if layout == "selective":
+        cfg = synth.mixer_cfg(2, 200, 128, io="bf16")
+    else:
+        cfg = synth.m2_cfg(2, 200, 128, headdim=64, d_state=64, dt_softplus=0, state_split=0 if layout == "mamba2_mfma" else 1)
+    pf, pb = synth.make_params(cfg, 77, 0), synth.make_params(cfg, 77, 1)
+    inp = synth.make_inputs(cfg, 77)
+    g = torch.Generator().manual_seed(78)
+    scale = torch.ones(2, 200, 1)
+    scale[:, 40:60] = 50.0 / 0.05          # ~50 per step
+    scale[:, 120:150] = 0.0                # no step at all: the state is frozen
+    inp["dt"] = synth.round_io(inp["dt"] * scale, "bf16")
+    inp["x"][:, 90:110] = 0.0
+    inp["x"] = synth.round_io(inp["x"] + 0.0, "bf16")
+    ref = oracle.bimamba_fwd(cfg, to_np(pf), to_np(pb), to_np(inp))
+    got = gpu.gpu_fwd(cfg, pf, pb, inp)
+    assert np.all(np.isfinite(got))
+    assert rel_l2(got, ref) < gpu.TOL["bf16"], layout
