@@ -34,17 +34,36 @@ def parse():
     return ap.parse_args()
 
 
-def read_traffic(kernel_key):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if there is one."""
+def read_counters(kernel_key):
+    """Counters of the dominant kernel from the committed rocprofv3 --pmc summary, if there is one."""
     path = os.path.join(ROOT, "profiles", kernel_key + "_pmc.txt")
     vals = {}
     try:
         for line in open(path):
             if "=" in line and not line.lstrip().startswith("#"):
                 k, v = line.split("=", 1)
-                vals[k.strip()] = v.strip()
-        return float(vals["FETCH_BYTES_PER_LAUNCH"]) + float(vals["WRITE_BYTES_PER_LAUNCH"])
+                vals[k.strip()] = float(v.strip())
     except Exception:
+        return {}
+    return vals
+
+
+def read_traffic(kernel_key):
+    """HBM bytes per launch of the dominant kernel (fetch + write, each scaled by the copy calibration)."""
+    c = read_counters(kernel_key)
+    try:
+        return c["FETCH_BYTES_PER_LAUNCH"] + c["WRITE_BYTES_PER_LAUNCH"]
+    except KeyError:
+        return None
+
+
+def read_valu_busy(kernel_key, waves_per_simd):
+    """Fraction of SIMD time with a vector-ALU instruction executing: per-wave VALU-active cycles over per-wave
+    resident cycles, times the waves that share a SIMD."""
+    c = read_counters(kernel_key)
+    try:
+        return min(1.0, waves_per_simd * c["SQ_ACTIVE_INST_VALU"] / c["SQ_WAVE_CYCLES"])
+    except (KeyError, ZeroDivisionError):
         return None
 
 
@@ -146,7 +165,9 @@ def main():
     traffic = read_traffic("sweep_" + args.workload)
     if ssd and traffic is not None:
         traffic *= 2.0   # the summary holds the mean of one launch; the probed interval holds both directions' launches
-    roofline.update({"traffic": traffic, "kernel": kernel, "kernel_ms": kernel_ms})
+    # both headline launches keep two waves on every SIMD (2048 waves, or 512 workgroups of 8 waves on 256 CUs)
+    roofline.update({"traffic": traffic, "kernel": kernel, "kernel_ms": kernel_ms,
+                     "valu_busy_from_profile": read_valu_busy("sweep_" + args.workload, 2.0)})
     result = {
         "metric": "bidirectional-scan tokens/s/GPU at d_inner=4096,L=8K; HBM GB/s vs peak",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
