@@ -205,14 +205,24 @@ bool pairs_readable(const bimamba_tensor& t)
 
 TensorArg targ(const bimamba_tensor& t) { return TensorArg{t.ptr, (long long)t.stride_batch, (long long)t.stride_token}; }
 
-void launch_scan(const bimamba_desc* d, int split, const SweepArgs& sa, const CarryArgs& ca, hipStream_t st,
-                 hipEvent_t ev_start, hipEvent_t ev_stop)
+// A call of a few dozen tokens with one lane per chain, up to 16 states and no conv on B and C runs as a single
+// launch: the scan kernel converts the caller's B and C rows itself instead of reading prepared fp32 rows.
+bool short_call(const bimamba_desc* d, const Plan& plan)
+{
+    return !plan.ssd && plan.split == 1 && plan.nseg == 1 && d->d_state <= 16 && !d->conv_bc &&
+           d->seqlen <= kShortCallTokens;
+}
+
+void launch_scan(const bimamba_desc* d, int split, int short_call, const SweepArgs& sa, const CarryArgs& ca,
+                 hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     const int scalar_a = d->a_kind == BIMAMBA_A_SCALAR_PER_HEAD, bf16 = d->io_dtype == BIMAMBA_BF16;
     // four or more waves per SIMD are available: trade prefetch depth for registers (occupancy)
     const int shallow = split == 1 && waves_of(d, 1) * sa.nseg >= 2 * kTargetWaves;
 #define BM_CASE(n, s) \
-    case (n) * 8 + (s): launch_scan_n##n##_s##s(scalar_a, bf16, sa, ca, d->batch, shallow, st, ev_start, ev_stop); break;
+    case (n) * 8 + (s):                                                                                          \
+        launch_scan_n##n##_s##s(scalar_a, bf16, sa, ca, d->batch, shallow, short_call, st, ev_start, ev_stop);     \
+        break;
     switch (d->d_state * 8 + split) {
         BM_CASE(4, 1) BM_CASE(8, 1) BM_CASE(16, 1) BM_CASE(16, 2) BM_CASE(16, 4) BM_CASE(32, 1) BM_CASE(32, 2)
         BM_CASE(32, 4) BM_CASE(64, 1) BM_CASE(64, 4) BM_CASE(128, 1) BM_CASE(128, 4)
@@ -257,7 +267,8 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
 
     if (d->batch > 0 && d->seqlen > 0) {
         // 1. fp32 B|C rows per direction (the chunked path prepares its own operand tiles from the raw rows)
-        const int nbuf = plan.ssd ? 0 : plan.two_bc ? 2 : 1;
+        const bool one_launch = short_call(d, plan);
+        const int nbuf = (plan.ssd || one_launch) ? 0 : plan.two_bc ? 2 : 1;
         for (int s = 0; s < nbuf; s++) {
             const bimamba_inputs* in = s == 0 ? in_f : in_b;
             const bimamba_params* p = s == 0 ? pf : pb;
@@ -329,6 +340,7 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
             DirArgs& da = sa.dir[s];
             da.x = targ(in->x); da.z = targ(in->z); da.dt = targ(in->dt);
             da.bc = reinterpret_cast<const float*>(ws + plan.off_bc[s]);
+            da.Braw = targ(in->B); da.Craw = targ(in->C);
             da.conv_w = p->conv_w; da.conv_b = p->conv_b; da.A = p->A; da.D = p->D; da.dt_bias = p->dt_bias;
         }
         sa.out = out->ptr; sa.out_sb = out->stride_batch; sa.out_st = out->stride_token;
@@ -348,7 +360,7 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
         ca.carry = sa.carry; ca.sumdt = sa.sumdt; ca.A[0] = pf->A; ca.A[1] = pb->A;
         ca.h_in = sa.h_in; ca.h_out = sa.h_out;
         ca.batch = d->batch; ca.nseg = plan.nseg; ca.Dn = d->d_inner; ca.P = sa.P;
-        launch_scan(d, plan.split, sa, ca, st, probe_start, probe_stop);
+        launch_scan(d, plan.split, one_launch, sa, ca, st, probe_start, probe_stop);
         }
     } else if (block_variant && d->batch > 0 && h_out && h_out != h_in) {
         // empty block: the state passes through unchanged

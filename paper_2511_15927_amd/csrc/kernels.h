@@ -34,6 +34,7 @@ struct TensorArg {
 struct DirArgs {
     TensorArg x, z, dt;
     const float* bc;  // prepared fp32 B|C rows: [batch][L][G][2N]
+    TensorArg Braw, Craw;  // the caller's B and C tensors (read directly by the short-call variant)
     const float* conv_w;
     const float* conv_b;
     const float* A;
@@ -103,6 +104,11 @@ __device__ __forceinline__ float sum_over_chain_lanes(float v)
 }
 
 enum { kSweep = 0, kSummary = 1 };
+// Where a token's B|C row comes from: the fp32 rows prep_bc_kernel prepared, or (short calls, one lane per chain, no
+// conv on B and C) a copy of the caller's rows that each wave converts into LDS itself at kernel start, which saves
+// the preparation launch when a call is a few dozen tokens long.
+enum { kBcPrepared = 0, kBcStaged = 1 };
+constexpr int kShortCallTokens = 64;
 // How the decay exp(Delta A[h, n]) is formed: one exponential per state; one per token for a scalar A per head; or, when
 // A is an arithmetic progression in n (detected on the device), two exponentials per token, a_n = a_first r^n.
 enum { kAPerState = 0, kAScalar = 1, kAProgression = 2 };
@@ -136,6 +142,7 @@ struct Chain {
     const float* bcrow;             // this token's B|C row of the tile's group
     long long xs, zs, dts, os, ps, bcs;
     unsigned ch, head, sub;         // channel, head, slice index (lane % S)
+    int tok, tstep;                 // kBcStaged: current token and its signed step (rows are indexed by token in LDS)
 };
 
 template <typename IO, int TILE>
@@ -262,14 +269,16 @@ __device__ __forceinline__ void token_step(Chain<N, S, AKIND, IO>& c, typename I
     c.orow += c.os;
     c.prow += c.ps;
     c.bcrow += c.bcs;
+    c.tok += c.tstep;
 }
 
 // Tokens [0, count) of the chain's walk from its current position, tile by tile with the next tile's loads in flight
 // and the next token's B|C slice requested before the current token is computed.  lds: this wave's private staging
 // area of 2 * TILE * 2N floats (S > 1 only).
-template <int N, int S, int AKIND, typename IO, int MODE, int TILE>
+template <int N, int S, int AKIND, typename IO, int MODE, int TILE, int BCSRC = kBcPrepared>
 __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, bool softplus_dt, float* lds, int lane)
 {
+    static_assert(BCSRC == kBcPrepared || (S == 1 && N <= 16), "staged rows exist for one lane per chain, <= 16 states");
     constexpr int NS = N / S;
     constexpr int kRowF4 = 2 * N / 4;              // float4s per B|C row
     constexpr int kStage = (TILE * kRowF4 + 63) / 64;  // float4s each lane moves per staged tile
@@ -304,6 +313,8 @@ __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, 
             stage_load(0);
             stage_store(0);
             load_bc_lds<N, S>(lds, 0, c.sub, row);
+        } else if constexpr (BCSRC == kBcStaged) {
+            load_bc_lds<N, 1>(lds, c.tok, 0, row);
         } else if constexpr (kBcScalarAhead<N, S>) {
             load_bc_scalar<N>(c.bcrow, row);
         }
@@ -328,6 +339,8 @@ __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, 
                 BcRow<NS> row_next;
                 if constexpr (S > 1) {
                     if (i + 1 < TILE) load_bc_lds<N, S>(tile_bc, i + 1, c.sub, row_next);
+                } else if constexpr (BCSRC == kBcStaged) {
+                    load_bc_lds<N, 1>(lds, done + i + 1 < count ? c.tok + c.tstep : c.tok, 0, row_next);
                 } else if constexpr (kBcScalarAhead<N, S>) {
                     // never read past the walk's last token: the row after it may lie outside the buffer
                     load_bc_scalar<N>(done + i + 1 < count ? c.bcrow + c.bcs : c.bcrow, row_next);
@@ -336,6 +349,8 @@ __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, 
                 token_step<N, S, AKIND, IO, MODE>(c, cur.x[i], delta[i], cur.z[i], cur.part[i], row);
                 if constexpr (S > 1) {
                     if (i + 1 < TILE) row = row_next;
+                } else if constexpr (BCSRC == kBcStaged) {
+                    row = row_next;
                 } else if constexpr (kBcScalarAhead<N, S>) {
                     __builtin_amdgcn_sched_barrier(0);
                     row = row_next;
@@ -358,6 +373,7 @@ __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, 
         if (mode_reads_partial(MODE)) part = c.prow[c.ch];
         BcRow<NS> row;
         if constexpr (S > 1) load_bc_direct<N, S>(c.bcrow, c.sub, row);
+        else if constexpr (BCSRC == kBcStaged) load_bc_lds<N, 1>(lds, c.tok, 0, row);
         else if constexpr (kBcScalarAhead<N, S>) load_bc_scalar<N>(c.bcrow, row);
         float delta = IO::cvt(dr);
         if (softplus_dt) delta = softplus(delta + c.dtb);
@@ -378,14 +394,14 @@ __device__ __forceinline__ unsigned xcd_aware_tile(unsigned g, unsigned n)
 }
 
 // grid (ceil(Dn / (64/S)), nseg, batch), block 128: wave 0 walks left-to-right, wave 1 right-to-left.
-template <int N, int S, int AKIND, typename IO, int KIND, int TILE>
+template <int N, int S, int AKIND, typename IO, int KIND, int TILE, int BCSRC = kBcPrepared>
 __device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, const int s)
 {
     using T = typename IO::T;
     constexpr int NS = N / S;
     constexpr int kCpw = 64 / S;  // channels per wave
     const int lane = threadIdx.x & 63;
-    float* lds = lds_all + (S > 1 ? s * (2 * TILE * 2 * N) : 0);
+    float* lds = lds_all + (BCSRC == kBcStaged ? s * (kShortCallTokens * 2 * N) : S > 1 ? s * (2 * TILE * 2 * N) : 0);
     const DirArgs& da = a.dir[s];
     const int b = blockIdx.z, seg = blockIdx.y;
     // Lanes past the last channel shadow channel Dn-1: they load the same inputs, compute the same values and
@@ -464,6 +480,18 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, c
     c.orow = (T*)a.out + (size_t)b * a.out_sb + (long long)tstart * a.out_st + (a.separate ? s * a.Dn : 0);
     c.prow = a.partial + ((size_t)b * a.L + tstart) * a.Dn;
     c.bcrow = da.bc + (((size_t)b * a.L + tstart) * a.G + grp) * (2 * N);
+    c.tok = tstart;
+    c.tstep = step;
+    if constexpr (BCSRC == kBcStaged) {
+        // this wave's own fp32 copy of its direction's B|C rows of the whole (short) call, indexed by token
+        const T* bsrc = (const T*)da.Braw.p + (size_t)b * da.Braw.sb + grp * N;
+        const T* csrc = (const T*)da.Craw.p + (size_t)b * da.Craw.sb + grp * N;
+        for (int idx = lane; idx < a.L * 2 * N; idx += 64) {
+            const int t = idx / (2 * N), col = idx % (2 * N);
+            lds[idx] = col < N ? IO::ld(bsrc + (long long)t * da.Braw.st + col) : IO::ld(csrc + (long long)t * da.Craw.st + col - N);
+        }
+        __builtin_amdgcn_wave_barrier();  // read back by other lanes of this wave only; LDS keeps wave order
+    }
     const bool sp = a.dt_softplus != 0;
 
     if (KIND == kSummary) {
@@ -476,15 +504,15 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, c
     }
 
     if (a.separate) {
-        run_range<N, S, AKIND, IO, kModeFinalOnly, TILE>(c, len, sp, lds, lane);
+        run_range<N, S, AKIND, IO, kModeFinalOnly, TILE, BCSRC>(c, len, sp, lds, lane);
     } else {
         // forward parks [t0, m), reverse parks [m, t1); then each finishes the other's half
         const int n_first = s == 0 ? (len + 1) / 2 : len / 2;
-        if (a.raw_partial) run_range<N, S, AKIND, IO, kModePartialRaw, TILE>(c, n_first, sp, lds, lane);
-        else run_range<N, S, AKIND, IO, kModePartial, TILE>(c, n_first, sp, lds, lane);
+        if (a.raw_partial) run_range<N, S, AKIND, IO, kModePartialRaw, TILE, BCSRC>(c, n_first, sp, lds, lane);
+        else run_range<N, S, AKIND, IO, kModePartial, TILE, BCSRC>(c, n_first, sp, lds, lane);
         __syncthreads();  // workgroup-scope release/acquire: the other wave's partials are visible from here on
-        if (a.raw_partial) run_range<N, S, AKIND, IO, kModeFinalAddRaw, TILE>(c, len - n_first, sp, lds, lane);
-        else run_range<N, S, AKIND, IO, kModeFinalAdd, TILE>(c, len - n_first, sp, lds, lane);
+        if (a.raw_partial) run_range<N, S, AKIND, IO, kModeFinalAddRaw, TILE, BCSRC>(c, len - n_first, sp, lds, lane);
+        else run_range<N, S, AKIND, IO, kModeFinalAdd, TILE, BCSRC>(c, len - n_first, sp, lds, lane);
     }
     if (s == 0 && a.nseg == 1 && a.h_out) {
         float* dst = a.h_out + ((size_t)b * a.Dn + ch) * N + sub * NS;
@@ -498,10 +526,12 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, c
 template <int N, typename IO>
 constexpr bool kProgressionEligible = (N >= 2 && N <= 32 && sizeof(typename IO::T) == 2);
 
-template <int N, int S, int AKIND, typename IO, int KIND, int TILE>
+template <int N, int S, int AKIND, typename IO, int KIND, int TILE, int BCSRC = kBcPrepared>
 __global__ __launch_bounds__(128) void sweep_kernel(const SweepArgs a)
 {
-    __shared__ __attribute__((aligned(16))) float lds_all[S > 1 ? 2 * 2 * TILE * 2 * N : 4];
+    __shared__ __attribute__((aligned(16))) float lds_all[BCSRC == kBcStaged ? 2 * kShortCallTokens * 2 * N
+                                                          : S > 1            ? 2 * 2 * TILE * 2 * N
+                                                                             : 4];
     const int s = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     if constexpr (AKIND == kAPerState && kProgressionEligible<N, IO>) {
         // Every lane checks its own chain's A row: A[h, n] == fma(n, A[h, 1] - A[h, 0], A[h, 0]) for all n.  The wave takes
@@ -515,12 +545,12 @@ __global__ __launch_bounds__(128) void sweep_kernel(const SweepArgs a)
 #pragma unroll
             for (int n = 0; n < N; n++) ok &= row[n] == fmaf((float)n, step, first);
             if (__all(ok)) {
-                sweep_body<N, S, kAProgression, IO, KIND, TILE>(a, lds_all, s);
+                sweep_body<N, S, kAProgression, IO, KIND, TILE, BCSRC>(a, lds_all, s);
                 return;
             }
         }
     }
-    sweep_body<N, S, AKIND, IO, KIND, TILE>(a, lds_all, s);
+    sweep_body<N, S, AKIND, IO, KIND, TILE, BCSRC>(a, lds_all, s);
 }
 
 // Stitch time segments: carry[s][b][seg] holds each segment's end state from a zero start (summary pass); replace it

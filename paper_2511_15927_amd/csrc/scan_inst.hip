@@ -28,9 +28,19 @@ static void launch_tile(const SweepArgs& sa, const CarryArgs& ca, int batch, hip
 // Shallow tiles exist for one lane per chain and up to 32 states (the case with enough chains for four or more waves
 // per SIMD); every other instantiation uses the deep tile.
 template <int AKIND, typename IO>
-static void launch_one(const SweepArgs& sa, const CarryArgs& ca, int batch, int shallow_tile, hipStream_t st,
-                       hipEvent_t ev_start, hipEvent_t ev_stop)
+static void launch_one(const SweepArgs& sa, const CarryArgs& ca, int batch, int shallow_tile, int short_call,
+                       hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop)
 {
+#if BM_S == 1 && BM_N <= 16
+    if (short_call) {   // one launch: the kernel converts the caller's B and C rows itself (see kBcStaged)
+        const dim3 grid((unsigned)((sa.Dn + 63) / 64), 1, (unsigned)batch);
+        if (ev_start) (void)hipEventRecord(ev_start, st);
+        hipLaunchKernelGGL((sweep_kernel<BM_N, BM_S, AKIND, IO, kSweep, 8, kBcStaged>), grid, dim3(128), 0, st, sa);
+        if (ev_stop) (void)hipEventRecord(ev_stop, st);
+        return;
+    }
+#endif
+    (void)short_call;
 #if BM_S == 1 && BM_N <= 32
     if (shallow_tile) {
         launch_tile<AKIND, IO, 4>(sa, ca, batch, st, ev_start, ev_stop);
@@ -45,14 +55,14 @@ static void launch_one(const SweepArgs& sa, const CarryArgs& ca, int batch, int 
 #define BM_NAME(n, s) BM_CAT4(launch_scan_n, n, _s, s)
 
 void BM_NAME(BM_N, BM_S)(int a_scalar_per_head, int io_bf16, const SweepArgs& sa, const CarryArgs& ca, int batch,
-                         int shallow_tile, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop)
+                         int shallow_tile, int short_call, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     if (a_scalar_per_head) {
-        if (io_bf16) launch_one<1, IoBF16>(sa, ca, batch, shallow_tile, st, ev_start, ev_stop);
-        else launch_one<1, IoF32>(sa, ca, batch, shallow_tile, st, ev_start, ev_stop);
+        if (io_bf16) launch_one<1, IoBF16>(sa, ca, batch, shallow_tile, short_call, st, ev_start, ev_stop);
+        else launch_one<1, IoF32>(sa, ca, batch, shallow_tile, short_call, st, ev_start, ev_stop);
     } else {
-        if (io_bf16) launch_one<0, IoBF16>(sa, ca, batch, shallow_tile, st, ev_start, ev_stop);
-        else launch_one<0, IoF32>(sa, ca, batch, shallow_tile, st, ev_start, ev_stop);
+        if (io_bf16) launch_one<0, IoBF16>(sa, ca, batch, shallow_tile, short_call, st, ev_start, ev_stop);
+        else launch_one<0, IoF32>(sa, ca, batch, shallow_tile, short_call, st, ev_start, ev_stop);
     }
 }
 
