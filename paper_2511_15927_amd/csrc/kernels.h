@@ -218,7 +218,20 @@ __device__ __forceinline__ void token_step(Chain<N, S, AKIND, IO>& c, typename I
     c.xh[2] = c.xh[1];
     c.xh[1] = c.xh[0];
     c.xh[0] = x0;
-    const float xc = silu(pre);
+    // With several lanes per chain the conv SiLU and the gate SiLU of a token are evaluated in one pass: slice 0 of the
+    // chain feeds the conv pre-activation, slice 1 feeds z, and both results are handed to all lanes of the chain with
+    // quad-permute moves (the values are the ones every lane would have computed for itself).
+    constexpr bool kSharedSilu = S >= 2 && MODE != kModeNoOutput && MODE != kModePartialRaw;
+    float xc, zg = 0.0f;
+    if constexpr (kSharedSilu) {
+        const float sv = silu(c.sub == 1 ? IO::cvt(zraw) : pre);
+        constexpr int kFrom0 = S == 2 ? 0xA0 : 0x00, kFrom1 = S == 2 ? 0xF5 : 0x55;   // quad_perm [0,0,2,2] / [1,1,3,3]; [0,0,0,0] / [1,1,1,1]
+        xc = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(sv), kFrom0, 0xF, 0xF, true));
+        zg = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(sv), kFrom1, 0xF, 0xF, true));
+    } else {
+        xc = silu(pre);
+        if constexpr (MODE != kModeNoOutput && MODE != kModePartialRaw) zg = silu(IO::cvt(zraw));
+    }
     const float u = delta * xc;
     float y = 0.0f;
     uniform_ro_ptr bcmem = (uniform_ro_ptr)c.bcrow;  // only for S = 1 rows too long to prefetch
@@ -256,9 +269,9 @@ __device__ __forceinline__ void token_step(Chain<N, S, AKIND, IO>& c, typename I
         if (MODE == kModePartialRaw) {
             c.prow[c.ch] = y;
         } else if (MODE == kModeFinalAddRaw) {
-            IO::st(c.orow + c.ch, (y + part) * silu(IO::cvt(zraw)));
+            IO::st(c.orow + c.ch, (y + part) * zg);
         } else {
-            const float g = y * silu(IO::cvt(zraw));
+            const float g = y * zg;
             if (MODE == kModePartial) c.prow[c.ch] = g;
             else IO::st(c.orow + c.ch, MODE == kModeFinalAdd ? g + part : g);
         }
