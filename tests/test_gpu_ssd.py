@@ -114,3 +114,23 @@ def test_ssd_strided_views_and_unaligned_fallback(gpu, oracle, lead):
     ref = oracle.bimamba_fwd(cfg, to_np(pf), to_np(pb), to_np(inp))
     assert rel_l2(out.float().cpu().numpy(), ref) < gpu.TOL["bf16"]
     assert torch.all(out_big[:, :, :4] == 0) and torch.all(out_big[:, :, 4 + Dn:] == 0)
+
+
+@pytest.mark.parametrize("L", [40, 130])
+def test_ssd_more_items_than_compute_units(gpu, oracle, L):
+    """More (batch, head) pairs than the chip has CUs (several rounds of workgroups), one and three chunks each: the
+    full-sequence call, and a block call that loads and commits every pair's state."""
+    cfg = synth.m2_cfg(3, L, 32 * 200, headdim=32, d_state=64)       # 600 items, one or three chunks each
+    pf, pb, inp = case(cfg, 1600 + L)
+    sel = sorted(np.random.default_rng(5).choice(cfg["d_inner"], size=300, replace=False).tolist())
+    ref = oracle.bimamba_fwd(cfg, to_np(pf), to_np(pb), to_np(inp), sel=sel)
+    got = gpu.gpu_fwd(cfg, pf, pb, inp)[..., sel]
+    assert rel_l2(got, ref) < gpu.TOL["bf16"]
+    g = torch.Generator().manual_seed(L)
+    h0 = (0.2 * torch.randn(3, cfg["d_inner"], 64, generator=g)).float()
+    tail0 = synth.round_io(torch.randn(3, 3, cfg["d_inner"] + 128, generator=g), "bf16")
+    ref, h_ref, t_ref = oracle.bimamba_block_fwd(cfg, to_np(pf), to_np(pb), to_np(inp), h_in=h0.numpy(), tail_in=tail0.numpy())
+    out, h, tail = gpu.gpu_block_fwd(cfg, pf, pb, inp, h_in=h0, tail_in=tail0)
+    assert rel_l2(out, ref) < gpu.TOL["bf16"]
+    assert rel_l2(h, h_ref) < 1e-2
+    assert np.array_equal(tail, t_ref)
