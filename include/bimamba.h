@@ -32,9 +32,10 @@
  *   - chunked matrix-core kernels (a_kind = SCALAR_PER_HEAD, bf16 I/O, d_state 64 or 128, 32 or 64 channels per
  *     head, time_chunks = state_split = 0): the recurrence over 64-token chunks as dense products on the MFMA
  *     units; their operands (conv output, B, C, the decayed score tile, a copy of the state) are rounded to bf16,
- *     accumulation and the carried state stay fp32.  Setting time_chunks or state_split, or passing x / z / out
- *     tensors that cannot be accessed as aligned runs of 2 (x) or 4 (z, out) channels, selects the lane-per-chain
- *     kernels for the call; the workspace size covers both.
+ *     accumulation and the carried state stay fp32.  They read x two channels at a time and the carried state four
+ *     states at a time: setting time_chunks or state_split, or passing an x whose pointer is not 4-byte aligned or
+ *     whose strides are odd, or an h_in / h_out that is not 16-byte aligned, selects the lane-per-chain kernels for
+ *     the call; the workspace size covers both.
  *
  * Execution: calls validate their arguments on the host, enqueue kernels on the caller's HIP stream
  * and return without synchronising.  Calls on different streams are independent as long as their
