@@ -134,3 +134,29 @@ def test_ssd_more_items_than_compute_units(gpu, oracle, L):
     assert rel_l2(out, ref) < gpu.TOL["bf16"]
     assert rel_l2(h, h_ref) < 1e-2
     assert np.array_equal(tail, t_ref)
+
+
+def test_ssd_state_not_16_byte_aligned_falls_back(gpu, oracle):
+    """The matrix-core kernels move the cached state as 16-byte pieces.  A state buffer that is only 4-byte aligned
+    must still work: the call runs on the lane-per-chain kernels inside the same workspace."""
+    from paper_2511_15927_amd import binding as bd
+    cfg = synth.m2_cfg(2, 70, 128, headdim=64, d_state=64)
+    pf, pb, inp = case(cfg, 1700)
+    g = torch.Generator().manual_seed(3)
+    h0 = (0.2 * torch.randn(2, 128, 64, generator=g)).float()
+    ref, h_ref, _ = oracle.bimamba_block_fwd(cfg, to_np(pf), to_np(pb), to_np(inp), h_in=h0.numpy(), want_tail=False)
+    n = h0.numel()
+    buf_in = torch.zeros(n + 1, dtype=torch.float32, device="cuda")
+    buf_out = torch.zeros(n + 1, dtype=torch.float32, device="cuda")
+    h_in, h_out = buf_in[1:].view(2, 128, 64), buf_out[1:].view(2, 128, 64)
+    h_in.copy_(h0)
+    assert h_in.data_ptr() % 16 == 4
+    desc = bd.make_desc(cfg)
+    dpf, dpb, dinp = bd.to_device(pf), bd.to_device(pb), bd.to_device(inp, cfg)
+    out, ws = bd.alloc_out(cfg), bd.alloc_workspace(desc, 1)
+    bd.bimamba_block_fwd(desc, bd.make_params(dpf), bd.make_params(dpb), bd.make_inputs(dinp), None, h_in, None, h_out,
+                         None, bd.make_tensor(out), ws)
+    torch.cuda.synchronize()
+    assert rel_l2(out.float().cpu().numpy(), ref) < gpu.TOL["bf16"]
+    assert rel_l2(h_out.cpu().numpy(), h_ref) < 1e-5      # the lane-per-chain kernels keep the state to fp32 accuracy
+    assert float(buf_out[0]) == 0.0
