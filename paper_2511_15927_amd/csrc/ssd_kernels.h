@@ -328,8 +328,20 @@ __global__ __launch_bounds__(4 * P + 256) void ssd_kernel(const SsdArgs a)
             if (c * kQ + lane > last) dl = 0.0f;
             const float l2 = wave_inclusive_sum(dl * a2);
             const float l2_end = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(l2), 63));
-            pw_l2[lane] = l2;
-            pw_dl[lane] = dl;
+            // The decay exp(l_i - l_j) of a score element is separable, e_i f_j with e_i = exp(l_i - l_mid) and
+            // f_j = exp(l_mid - l_j): two exponentials per position instead of one per element.  Both factors stay
+            // well inside the fp32 range as long as the chunk's total decay does (2^-100 here); a chunk that decays
+            // faster keeps the per-element form.
+            const float l2_first = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(l2), 0));
+            const float l2_mid = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(l2), kQ / 2 - 1));
+            const bool separable = l2_first - l2_end <= 100.0f;
+            if (separable) {
+                pw_l2[lane] = fast_exp2(l2 - l2_mid);          // e_i
+                pw_dl[lane] = fast_exp2(l2_mid - l2) * dl;     // f_j Delta_j
+            } else {
+                pw_l2[lane] = l2;
+                pw_dl[lane] = dl;
+            }
             pw_wgt[lane] = fast_exp2(l2_end - l2) * dl;
             if (pwave == 0) scal[buf * kQ + lane] = fast_exp2(l2);
             __builtin_amdgcn_wave_barrier();
@@ -346,16 +358,25 @@ __global__ __launch_bounds__(4 * P + 256) void ssd_kernel(const SsdArgs a)
                 const int iblk = bp > 0, jblk = bp > 1;
                 const int i = iblk * 32 + sl % 32;
                 const int jb = jblk * 32 + 16 * kb + 8 * hi + 4 * (sl / 32);
+                const bool diagonal = iblk == jblk;    // only the diagonal blocks hold elements with j > i
                 const float l2i = pw_l2[i];
-                const float4 la = *reinterpret_cast<const float4*>(&pw_l2[jb]);
                 const float4 da = *reinterpret_cast<const float4*>(&pw_dl[jb]);
-                const float lj[4] = {la.x, la.y, la.z, la.w};
                 const float dj[4] = {da.x, da.y, da.z, da.w};
                 bf16x4 v;
+                if (separable) {
 #pragma unroll
-                for (int e = 0; e < 4; e++) {
-                    const float val = sv[m][e] * fast_exp2(l2i - lj[e]) * dj[e];
-                    v[e] = (__bf16)(jb + e > i ? 0.0f : val);
+                    for (int e = 0; e < 4; e++) {
+                        const float val = sv[m][e] * l2i * dj[e];
+                        v[e] = (__bf16)((diagonal && jb + e > i) ? 0.0f : val);
+                    }
+                } else {
+                    const float4 la = *reinterpret_cast<const float4*>(&pw_l2[jb]);
+                    const float lj[4] = {la.x, la.y, la.z, la.w};
+#pragma unroll
+                    for (int e = 0; e < 4; e++) {
+                        const float val = sv[m][e] * fast_exp2(l2i - lj[e]) * dj[e];
+                        v[e] = (__bf16)((diagonal && jb + e > i) ? 0.0f : val);
+                    }
                 }
                 *reinterpret_cast<bf16x4*>(&sM(buf)[(((iblk * 2 + jblk) * 2 + kb) * 64 + sl) * 8 + 4 * hi]) = v;
             }
