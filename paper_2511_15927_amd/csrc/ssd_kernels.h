@@ -113,11 +113,18 @@ __global__ __launch_bounds__(256) void ssd_prep_kernel(const SsdPrepPair both)
     }
     __syncthreads();
     const size_t Lpad = (size_t)nchunk * kQ;
-    for (int idx = tid; idx < kQ * N; idx += 256) {
-        const int j = idx / N, n = idx % N;
-        a.c_rows[(((size_t)b * Lpad + c * kQ + j) * a.G + g) * N + n] = (__bf16)sC[j][n];
-        const int n2 = idx / kQ, j2 = idx % kQ;
-        a.b_t[((((size_t)b * nchunk + c) * a.G + g) * N + n2) * kQ + j2] = (__bf16)sB[j2][n2];
+    // bf16 C rows and the transposed bf16 B tile, written as 16-byte pieces (8 states of a row, 8 positions of a state)
+    for (int idx = tid; idx < kQ * N / 8; idx += 256) {
+        const int j = idx / (N / 8), n8 = idx % (N / 8);
+        const int n2 = idx / (kQ / 8), j8 = idx % (kQ / 8);
+        bf16x8 cv, bv;
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            cv[e] = (__bf16)sC[j][8 * n8 + e];
+            bv[e] = (__bf16)sB[8 * j8 + e][n2];
+        }
+        *reinterpret_cast<bf16x8*>(&a.c_rows[(((size_t)b * Lpad + c * kQ + j) * a.G + g) * N + 8 * n8]) = cv;
+        *reinterpret_cast<bf16x8*>(&a.b_t[((((size_t)b * nchunk + c) * a.G + g) * N + n2) * kQ + 8 * j8]) = bv;
     }
     // Score tile B_j . C_i on the matrix cores, one 32 x 32 block per wave; only the three blocks on or below the
     // diagonal are kept.  Each fp32 operand is split into a bf16 head and a bf16 remainder and the three significant
