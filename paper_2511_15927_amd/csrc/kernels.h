@@ -428,6 +428,12 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, c
     const int t1 = min(a.L, t0 + a.seg_len);
     const int len = t1 - t0;
     if (len <= 0) return;
+    if (KIND == kSummary) {
+        // the end state of the segment a direction scans last feeds no other segment: it is needed only when the
+        // forward state is committed
+        const bool scanned_last = s == 0 ? seg == a.nseg - 1 : seg == 0;
+        if (scanned_last && !(s == 0 && a.h_out)) return;
+    }
     const int step = s == 0 ? 1 : -1;
     const int tstart = s == 0 ? t0 : t1 - 1;
 
