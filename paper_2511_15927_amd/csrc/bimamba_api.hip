@@ -64,15 +64,45 @@ long long waves_of(const bimamba_desc* d, int split)
     return 2LL * d->batch * ((d->d_inner + cpw - 1) / cpw);
 }
 
-// Lanes per chain: spreading a chain's states over 2 lanes doubles the number of waves without repeating the decay
-// exponentials (the per-token conv / gate work is repeated instead), so it is the first lever when the
-// (batch x channel x direction) chains alone leave SIMDs with fewer than two waves.  Four lanes per chain repeat too
-// much of that work to pay off below 64 states (measured), so beyond two lanes the sequence is cut instead.
+// Launch geometry of the lane-per-chain kernels, from measurements on MI355X (1024 SIMDs) with w = the number of waves
+// that one lane per chain gives (2 * batch * d_inner / 64):
+//   w >= 2048          one lane per chain, whole sequence: two or more waves per SIMD already.
+//   1024 <= w < 2048   two lanes per chain (each holds half the states), whole sequence: doubles the waves without
+//                      repeating the decay factors; 6 % faster than cutting the sequence at w = 1024.
+//   w < 1024           one lane per chain and the sequence cut into time segments until about 16 waves per SIMD
+//                      exist (segments of at least 128 tokens): the segment summaries cost a second, cheaper pass,
+//                      but every SIMD then holds enough waves to issue back to back and to hide the loads.  (Up to
+//                      49 % faster than two lanes per chain with fewer segments, which this rule replaced.)
+//                      If even that leaves fewer than two waves per SIMD (short sequences), two lanes per chain.
+// Four lanes per chain repeat too much per-token work to pay off below 64 states.  With 64 or 128 states a lane cannot
+// hold a whole chain without starving the SIMD of registers, so those shapes split the states first (four lanes per
+// chain) and cut the sequence only as far as two waves per SIMD need, in segments of at least 256 tokens.
+constexpr int kWavesForSegments = 16384;
+constexpr int kMinSegmentTokens = 128;
+
+bool many_states(const bimamba_desc* d) { return d->d_state > 32; }
+
+int segments_for(const bimamba_desc* d, long long waves)
+{
+    const int L = d->seqlen;
+    if (L <= 0 || waves <= 0) return 1;
+    const int want = many_states(d) ? kTargetWaves : kWavesForSegments;
+    const int min_tokens = many_states(d) ? 256 : kMinSegmentTokens;
+    long long n = (want + waves - 1) / waves;
+    const long long max_by_len = L / min_tokens > 0 ? L / min_tokens : 1;
+    if (n > max_by_len) n = max_by_len;
+    return (int)(n < 1 ? 1 : n);
+}
+
 int pick_split(const bimamba_desc* d)
 {
     if (d->state_split > 0) return d->state_split;
-    if (waves_of(d, 1) >= kTargetWaves) return 1;
-    if (split_supported(d->d_state, 2)) return 2;
+    const long long w = waves_of(d, 1);
+    if (w >= kTargetWaves) return 1;
+    const bool two = split_supported(d->d_state, 2);
+    if (w >= kTargetWaves / 2) return two ? 2 : (d->d_state >= 64 && split_supported(d->d_state, 4)) ? 4 : 1;
+    if (!many_states(d) && d->time_chunks == 0 && w * segments_for(d, w) >= kTargetWaves) return 1;
+    if (two) return 2;
     if (d->d_state >= 64 && split_supported(d->d_state, 4)) return 4;
     return 1;
 }
@@ -85,13 +115,8 @@ int pick_chunks(const bimamba_desc* d, int split)
     if (d->time_chunks > 0) {
         n = d->time_chunks;
     } else {
-        // Each extra segment re-evaluates the decay exponentials in a summary pass, so only cut the sequence when
-        // chains and state splitting together cannot fill the chip.
         const long long waves = waves_of(d, split);
-        n = 1;
-        if (waves > 0 && waves < kTargetWaves) n = (int)((kTargetWaves + waves - 1) / waves);
-        const int max_by_len = L / 256 > 0 ? L / 256 : 1;  // keep segments at least 256 tokens long
-        if (n > max_by_len) n = max_by_len;
+        n = waves >= kTargetWaves ? 1 : segments_for(d, waves);
     }
     if (n > L) n = L;
     if (n > 4096) n = 4096;

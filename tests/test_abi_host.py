@@ -84,7 +84,7 @@ def test_workspace_and_chunk_planning():
     d1 = bd.make_desc(synth.CONFIGS["headline"])
     assert bd.bimamba_time_chunks(d1) == 1                       # chains x 2 lanes per chain already fill the chip
     d2 = bd.make_desc(synth.CONFIGS["cfg2"])
-    assert bd.bimamba_time_chunks(d2) == 8                       # batch 1: 2 lanes per chain, then the sequence is cut
+    assert bd.bimamba_time_chunks(d2) == 128                     # batch 1: one lane per chain, 16 waves per SIMD from time segments
     assert bd.bimamba_time_chunks(bd.make_desc(synth.CONFIGS["cfg3_block"])) == 1
     assert bd.bimamba_time_chunks(bd.make_desc(synth.mixer_cfg(1, 100, 64, time_chunks=7))) == 7
     assert bd.bimamba_time_chunks(bd.make_desc(synth.mixer_cfg(1, 5, 64, time_chunks=7))) == 5
