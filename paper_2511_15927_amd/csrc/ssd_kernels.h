@@ -245,7 +245,18 @@ __global__ __launch_bounds__(4 * P + 256) void ssd_kernel(const SsdArgs a)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool producer = wave >= kConsThreads / 64;
-    const int head = blockIdx.x, b = blockIdx.z;
+    // Workgroups go to the 8 XCDs round-robin by linear id and each XCD has its own L2.  All heads of a batch element
+    // read the same C / B^T / score tiles, so the (batch, head) items are dealt out such that an XCD receives a
+    // contiguous, batch-major run of them and fetches each tile from HBM once instead of once per XCD.
+    int head = blockIdx.x, b = blockIdx.z;
+    {
+        const unsigned total = gridDim.x * gridDim.z, id = blockIdx.x + gridDim.x * blockIdx.z;
+        if (total % 8 == 0) {
+            const unsigned item = (id % 8) * (total / 8) + id / 8;
+            head = (int)(item % gridDim.x);
+            b = (int)(item / gridDim.x);
+        }
+    }
     const int grp = head / a.HG;
     const int ch0 = head * P;
     const size_t Lpad = (size_t)a.nchunk * kQ;
