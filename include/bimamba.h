@@ -60,7 +60,7 @@ enum bimamba_status {
     BIMAMBA_OK = 0,
     BIMAMBA_ERR_NULL_POINTER = -1,        /* a required pointer is NULL */
     BIMAMBA_ERR_BAD_SHAPE = -2,           /* non-positive or inconsistent dimension, stride smaller than the row */
-    BIMAMBA_ERR_UNSUPPORTED = -3,         /* dtype / d_state / d_conv / grouping outside the compiled set */
+    BIMAMBA_ERR_UNSUPPORTED = -3,         /* dtype / d_state / d_conv / grouping / token stride outside the compiled set */
     BIMAMBA_ERR_MISALIGNED = -4,          /* pointer not aligned to its element size (or 16 bytes for the workspace) */
     BIMAMBA_ERR_WORKSPACE_TOO_SMALL = -5, /* workspace_bytes < bimamba_workspace_bytes() */
     BIMAMBA_ERR_HIP = -6                  /* a kernel launch failed (hipGetLastError) */
@@ -112,8 +112,9 @@ typedef struct bimamba_params {
 } bimamba_params;
 
 /* One activation tensor [batch, L, channels]: element (b, t, c) lives at ptr + b*stride_batch + t*stride_token + c
- * (in elements of io_dtype).  stride_token >= channels.  Strided views let x, z, dt, B, C be column slices of one
- * projection output.  ptr may be NULL only when batch == 0 or seqlen == 0 (nothing is accessed). */
+ * (in elements of io_dtype).  channels <= stride_token <= 2^26 (BIMAMBA_ERR_UNSUPPORTED beyond: the kernels form row
+ * offsets inside a tile of tokens in 32 bits).  Strided views let x, z, dt, B, C be column slices of one projection
+ * output.  ptr may be NULL only when batch == 0 or seqlen == 0 (nothing is accessed). */
 typedef struct bimamba_tensor {
     void* ptr;
     int64_t stride_batch;

@@ -66,19 +66,21 @@ long long waves_of(const bimamba_desc* d, int split)
 
 // Launch geometry of the lane-per-chain kernels, from measurements on MI355X (1024 SIMDs) with w = the number of waves
 // that one lane per chain gives (2 * batch * d_inner / 64):
-//   w >= 2048          one lane per chain, whole sequence: two or more waves per SIMD already.
-//   1024 <= w < 2048   two lanes per chain (each holds half the states), whole sequence: doubles the waves without
-//                      repeating the decay factors; 6 % faster than cutting the sequence at w = 1024.
-//   w < 1024           one lane per chain and the sequence cut into time segments until about 16 waves per SIMD
-//                      exist (segments of at least 128 tokens): the segment summaries cost a second, cheaper pass,
-//                      but every SIMD then holds enough waves to issue back to back and to hide the loads.  (Up to
-//                      49 % faster than two lanes per chain with fewer segments, which this rule replaced.)
-//                      If even that leaves fewer than two waves per SIMD (short sequences), two lanes per chain.
+//   w >= 2048   one lane per chain, whole sequence: two or more waves per SIMD already.
+//   w <  2048   two lanes per chain (each holds half the states), whole sequence, when the 2w waves fill the SIMDs
+//               evenly: at most three per SIMD (what the kernel's registers allow at once) and at least 0.9 of a whole
+//               number.  Doubling the waves this way repeats the per-channel work but needs no second pass.
+//               Otherwise one lane per chain and the sequence cut into time segments until about 16 waves per SIMD
+//               exist: the segment summaries cost a second, cheaper pass, but every SIMD then holds enough waves
+//               to issue back to back and to hide the loads, whatever the batch.  Segments stay at 256 tokens or
+//               more when that still gives four waves per SIMD, at 128 or more otherwise.
+//               If even that leaves fewer than two waves per SIMD (short sequences), two lanes per chain.
 // Four lanes per chain repeat too much per-token work to pay off below 64 states.  With 64 or 128 states a lane cannot
 // hold a whole chain without starving the SIMD of registers, so those shapes split the states first (four lanes per
 // chain) and cut the sequence only as far as two waves per SIMD need, in segments of at least 256 tokens.
 constexpr int kWavesForSegments = 16384;
 constexpr int kMinSegmentTokens = 128;
+constexpr int kSimds = 1024;
 
 bool many_states(const bimamba_desc* d) { return d->d_state > 32; }
 
@@ -87,11 +89,19 @@ int segments_for(const bimamba_desc* d, long long waves)
     const int L = d->seqlen;
     if (L <= 0 || waves <= 0) return 1;
     const int want = many_states(d) ? kTargetWaves : kWavesForSegments;
-    const int min_tokens = many_states(d) ? 256 : kMinSegmentTokens;
+    long long min_tokens = 256;
+    if (!many_states(d) && waves * (L / 256) < 4 * kSimds) min_tokens = kMinSegmentTokens;
     long long n = (want + waves - 1) / waves;
     const long long max_by_len = L / min_tokens > 0 ? L / min_tokens : 1;
     if (n > max_by_len) n = max_by_len;
     return (int)(n < 1 ? 1 : n);
+}
+
+// Two lanes per chain fill the SIMDs evenly in one round of resident waves.
+bool two_lanes_fit(long long w)
+{
+    const long long per_simd_x10 = 2 * w * 10 / kSimds, whole = (2 * w + kSimds - 1) / kSimds;
+    return whole >= 2 && whole <= 3 && per_simd_x10 >= 9 * whole;
 }
 
 int pick_split(const bimamba_desc* d)
@@ -99,12 +109,11 @@ int pick_split(const bimamba_desc* d)
     if (d->state_split > 0) return d->state_split;
     const long long w = waves_of(d, 1);
     if (w >= kTargetWaves) return 1;
-    const bool two = split_supported(d->d_state, 2);
-    if (w >= kTargetWaves / 2) return two ? 2 : (d->d_state >= 64 && split_supported(d->d_state, 4)) ? 4 : 1;
-    if (!many_states(d) && d->time_chunks == 0 && w * segments_for(d, w) >= kTargetWaves) return 1;
-    if (two) return 2;
-    if (d->d_state >= 64 && split_supported(d->d_state, 4)) return 4;
-    return 1;
+    const bool two = split_supported(d->d_state, 2), four = d->d_state >= 64 && split_supported(d->d_state, 4);
+    if (many_states(d)) return w >= kTargetWaves / 2 && two ? 2 : four ? 4 : two ? 2 : 1;
+    if (two && two_lanes_fit(w)) return 2;
+    if (d->time_chunks == 0 && w * segments_for(d, w) >= kTargetWaves) return 1;
+    return two ? 2 : 1;
 }
 
 int pick_chunks(const bimamba_desc* d, int split)
@@ -116,7 +125,8 @@ int pick_chunks(const bimamba_desc* d, int split)
         n = d->time_chunks;
     } else {
         const long long waves = waves_of(d, split);
-        n = waves >= kTargetWaves ? 1 : segments_for(d, waves);
+        const bool whole = split == 2 && d->state_split == 0 && !many_states(d) && two_lanes_fit(waves_of(d, 1));
+        n = waves >= kTargetWaves || whole ? 1 : segments_for(d, waves);
     }
     if (n > L) n = L;
     if (n > 4096) n = 4096;
@@ -179,12 +189,15 @@ Plan make_plan(const bimamba_desc* d, bool inputs_shared)
     return p;
 }
 
+constexpr int64_t kMaxTokenStride = 1 << 26;  // elements
+
 int check_tensor(const bimamba_tensor& t, int channels, size_t elem, const bimamba_desc* d)
 {
     const bool empty = d->batch == 0 || d->seqlen == 0;  // nothing is read or written: the pointer may be NULL
     if (!t.ptr && !empty) return BIMAMBA_ERR_NULL_POINTER;
     if (!is_aligned(t.ptr, elem)) return BIMAMBA_ERR_MISALIGNED;
     if (t.stride_token < channels) return BIMAMBA_ERR_BAD_SHAPE;
+    if (t.stride_token > kMaxTokenStride) return BIMAMBA_ERR_UNSUPPORTED;  // row offsets inside a tile are 32-bit
     if (d->batch > 1 && t.stride_batch < (int64_t)d->seqlen * t.stride_token - (t.stride_token - channels))
         return BIMAMBA_ERR_BAD_SHAPE;
     return BIMAMBA_OK;
@@ -242,11 +255,9 @@ void launch_scan(const bimamba_desc* d, int split, int short_call, const SweepAr
                  hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     const int scalar_a = d->a_kind == BIMAMBA_A_SCALAR_PER_HEAD, bf16 = d->io_dtype == BIMAMBA_BF16;
-    // four or more waves per SIMD are available: trade prefetch depth for registers (occupancy)
-    const int shallow = split == 1 && waves_of(d, 1) * sa.nseg >= 2 * kTargetWaves;
 #define BM_CASE(n, s) \
     case (n) * 8 + (s):                                                                                          \
-        launch_scan_n##n##_s##s(scalar_a, bf16, sa, ca, d->batch, shallow, short_call, st, ev_start, ev_stop);     \
+        launch_scan_n##n##_s##s(scalar_a, bf16, sa, ca, d->batch, short_call, st, ev_start, ev_stop);              \
         break;
     switch (d->d_state * 8 + split) {
         BM_CASE(4, 1) BM_CASE(8, 1) BM_CASE(16, 1) BM_CASE(16, 2) BM_CASE(16, 4) BM_CASE(32, 1) BM_CASE(32, 2)
@@ -460,7 +471,7 @@ const char* bimamba_status_string(int status)
         case BIMAMBA_OK: return "ok";
         case BIMAMBA_ERR_NULL_POINTER: return "a required pointer is NULL";
         case BIMAMBA_ERR_BAD_SHAPE: return "bad shape: non-positive or inconsistent dimension or stride";
-        case BIMAMBA_ERR_UNSUPPORTED: return "unsupported dtype, d_state, d_conv or grouping";
+        case BIMAMBA_ERR_UNSUPPORTED: return "unsupported dtype, d_state, d_conv, grouping or token stride";
         case BIMAMBA_ERR_MISALIGNED: return "misaligned pointer";
         case BIMAMBA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case BIMAMBA_ERR_HIP: return "HIP launch error";

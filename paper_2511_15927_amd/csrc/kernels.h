@@ -16,6 +16,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace bm {
 
@@ -58,20 +59,46 @@ struct SweepArgs {
     int try_progression;  // let each wave test whether its chains' A rows are arithmetic in n (see sweep_kernel)
 };
 
+// Buffer resource of a raw (untyped, unstrided) range starting at a wave-uniform address.  An access adds a
+// wave-uniform byte offset and a 32-bit per-lane byte offset to that address inside the memory instruction itself, so
+// it needs no vector address arithmetic.  The range is left unbounded: callers keep every offset inside the tensor.
+typedef __amdgpu_buffer_rsrc_t Rsrc;
+__device__ __forceinline__ Rsrc raw_range(const void* base)
+{
+    return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, -1, 0x00020000);
+}
+
 struct IoF32 {
     using T = float;
     static __device__ __forceinline__ float ld(const T* p) { return *p; }
     static __device__ __forceinline__ float cvt(T v) { return v; }
     static __device__ __forceinline__ void st(T* p, float v) { *p = v; }
+    static __device__ __forceinline__ T ld_raw(Rsrc r, unsigned lane_off, int row_off)
+    {
+        return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, lane_off, row_off, 0));
+    }
+    static __device__ __forceinline__ void st_raw(Rsrc r, unsigned lane_off, int row_off, float v)
+    {
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, lane_off, row_off, 0);
+    }
 };
 struct IoBF16 {
     using T = unsigned short;
     static __device__ __forceinline__ float cvt(T v) { return __uint_as_float(((unsigned)v) << 16); }
     static __device__ __forceinline__ float ld(const T* p) { return cvt(*p); }
-    static __device__ __forceinline__ void st(T* p, float v)
+    static __device__ __forceinline__ T round(float v)
     {
         __bf16 r = (__bf16)v;  // round to nearest even (v_cvt_pk_bf16_f32)
-        *p = __builtin_bit_cast(unsigned short, r);
+        return __builtin_bit_cast(unsigned short, r);
+    }
+    static __device__ __forceinline__ void st(T* p, float v) { *p = round(v); }
+    static __device__ __forceinline__ T ld_raw(Rsrc r, unsigned lane_off, int row_off)
+    {
+        return __builtin_amdgcn_raw_buffer_load_b16(r, lane_off, row_off, 0);
+    }
+    static __device__ __forceinline__ void st_raw(Rsrc r, unsigned lane_off, int row_off, float v)
+    {
+        __builtin_amdgcn_raw_buffer_store_b16(round(v), r, lane_off, row_off, 0);
     }
 };
 
@@ -103,6 +130,15 @@ __device__ __forceinline__ float sum_over_chain_lanes(float v)
     return v;
 }
 
+// The value lane J of the caller's chain holds (S = 2: lane pairs, S = 4: quads), by a quad-permute move.
+template <int S, int J>
+__device__ __forceinline__ float chain_lane_value(float v)
+{
+    static_assert((S == 2 || S == 4) && J < S, "chains are lane pairs or quads");
+    constexpr int kSel = S == 2 ? (J == 0 ? 0xA0 : 0xF5) : J * 0x55;  // [0,0,2,2] / [1,1,3,3]; [J,J,J,J]
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), kSel, 0xF, 0xF, true));
+}
+
 enum { kSweep = 0, kSummary = 1 };
 // Where a token's B|C row comes from: the fp32 rows prep_bc_kernel prepared, or (short calls, one lane per chain, no
 // conv on B and C) a copy of the caller's rows that each wave converts into LDS itself at kernel start, which saves
@@ -124,8 +160,39 @@ __host__ __device__ constexpr bool mode_reads_partial(int m) { return m == kMode
 // a SIMD holds one or two waves (the prefetch depth hides HBM latency); 4 when it can hold four or more (fewer
 // registers per wave, and the other waves hide the latency).
 
+// TILE consecutive tokens (scan order) of one tensor as a raw range: the range starts at the tile's lowest-address
+// row, so a token's row offset is never negative whatever the sign of the caller's stride or the direction of the
+// walk.  first / inc are bytes; |inc| * (TILE - 1) fits an int (the host rejects larger token strides).
+template <int TILE>
+struct TileRows {
+    Rsrc range;
+    int first, inc;  // row offset of the tile's first token, signed step per token
+    __device__ __forceinline__ int row(int i) const { return first + i * inc; }
+};
+
+template <int TILE, typename T>
+__device__ __forceinline__ TileRows<TILE> tile_rows(T* first_row, long long step)
+{
+    TileRows<TILE> t;
+    t.inc = (int)step * (int)sizeof(T);
+    // Row offsets are cheap to form (one scalar add each); left visible as loop invariants they would all be kept live
+    // across the walk, a few dozen scalar registers more than there are.
+    asm volatile("" : "+s"(t.inc));
+    t.first = step < 0 ? -(TILE - 1) * t.inc : 0;
+    t.range = raw_range(step < 0 ? first_row + (TILE - 1) * step : first_row);
+    return t;
+}
+
+// The lane's element of a row given by pointer (tokens outside whole tiles).
+template <typename T>
+__device__ __forceinline__ T* lane_elem(T* row, unsigned byte_off)
+{
+    using Byte = std::conditional_t<std::is_const_v<T>, const char, char>;
+    return reinterpret_cast<T*>(reinterpret_cast<Byte*>(row) + byte_off);
+}
+
 // Per-lane constants and running state of one chain slice.  Row pointers are wave-uniform and advance by signed
-// per-token steps; ch / head are the lane's constant offsets into a row.
+// per-token steps; the lane's place in a row is a constant byte offset.
 template <int N, int S, int AKIND, typename IO>
 struct Chain {
     using T = typename IO::T;
@@ -141,7 +208,8 @@ struct Chain {
     float* prow;
     const float* bcrow;             // this token's B|C row of the tile's group
     long long xs, zs, dts, os, ps, bcs;
-    unsigned ch, head, sub;         // channel, head, slice index (lane % S)
+    unsigned ch_io, head_io, ch_f32;  // the lane's byte offset into a row: channel / head in the I/O dtype, channel in fp32
+    unsigned sub;                   // slice index (lane % S)
     int tok, tstep;                 // kBcStaged: current token and its signed step (rows are indexed by token in LDS)
 };
 
@@ -154,14 +222,36 @@ struct RawTile {
 template <int N, int S, int AKIND, typename IO, int MODE, int TILE>
 __device__ __forceinline__ void load_tile(const Chain<N, S, AKIND, IO>& c, long long ahead, RawTile<IO, TILE>& r)
 {
+    const TileRows<TILE> tx = tile_rows<TILE>(c.xrow + ahead * c.xs, c.xs);
+    const TileRows<TILE> td = tile_rows<TILE>(c.dtrow + ahead * c.dts, c.dts);
+    const TileRows<TILE> tz = tile_rows<TILE>(c.zrow + ahead * c.zs, c.zs);
+    const TileRows<TILE> tp = tile_rows<TILE>(c.prow + ahead * c.ps, c.ps);
 #pragma unroll
     for (int i = 0; i < TILE; i++) {
-        r.x[i] = (c.xrow + (ahead + i) * c.xs)[c.ch];
-        r.dt[i] = (c.dtrow + (ahead + i) * c.dts)[c.head];
-        if (mode_reads_z(MODE)) r.z[i] = (c.zrow + (ahead + i) * c.zs)[c.ch];
-        if (mode_reads_partial(MODE)) r.part[i] = (c.prow + (ahead + i) * c.ps)[c.ch];
+        r.x[i] = IO::ld_raw(tx.range, c.ch_io, tx.row(i));
+        r.dt[i] = IO::ld_raw(td.range, c.head_io, td.row(i));
+        if (mode_reads_z(MODE)) r.z[i] = IO::ld_raw(tz.range, c.ch_io, tz.row(i));
+        if (mode_reads_partial(MODE)) r.part[i] = IoF32::ld_raw(tp.range, c.ch_f32, tp.row(i));
     }
 }
+
+// Where a token's result goes: token i of a tile addressed as raw ranges, or rows given by pointer.
+template <typename IO, int TILE>
+struct TileSink {
+    const TileRows<TILE>&o, &p;
+    unsigned ch_io, ch_f32;
+    int i;
+    __device__ __forceinline__ void park(float v) const { IoF32::st_raw(p.range, ch_f32, p.row(i), v); }
+    __device__ __forceinline__ void final(float v) const { IO::st_raw(o.range, ch_io, o.row(i), v); }
+};
+template <typename IO>
+struct RowSink {
+    typename IO::T* orow;
+    float* prow;
+    unsigned ch_io, ch_f32;
+    __device__ __forceinline__ void park(float v) const { *lane_elem(prow, ch_f32) = v; }
+    __device__ __forceinline__ void final(float v) const { IO::st(lane_elem(orow, ch_io), v); }
+};
 
 // One token's B (first NS) and C (last NS) values for this lane's state slice.
 template <int NS>
@@ -203,10 +293,11 @@ __device__ __forceinline__ void load_bc_lds(const float* tile, int i, unsigned s
     load_bc_direct<N, S>(tile + i * 2 * N, sub, r);
 }
 
-// One token of one chain slice: conv + SiLU, discretise, state updates, skip term, gate, output.
-template <int N, int S, int AKIND, typename IO, int MODE>
+// One token of one chain slice: conv + SiLU, discretise, state updates, skip term, gate, output.  Advances the B|C
+// row and the token counter; the caller advances the other rows.
+template <int N, int S, int AKIND, typename IO, int MODE, typename Sink>
 __device__ __forceinline__ void token_step(Chain<N, S, AKIND, IO>& c, typename IO::T xraw, float delta,
-                                           typename IO::T zraw, float part, const BcRow<N / S>& row)
+                                           typename IO::T zraw, float part, const BcRow<N / S>& row, const Sink& sink)
 {
     constexpr int NS = N / S;
     const float x0 = IO::cvt(xraw);
@@ -225,9 +316,8 @@ __device__ __forceinline__ void token_step(Chain<N, S, AKIND, IO>& c, typename I
     float xc, zg = 0.0f;
     if constexpr (kSharedSilu) {
         const float sv = silu(c.sub == 1 ? IO::cvt(zraw) : pre);
-        constexpr int kFrom0 = S == 2 ? 0xA0 : 0x00, kFrom1 = S == 2 ? 0xF5 : 0x55;   // quad_perm [0,0,2,2] / [1,1,3,3]; [0,0,0,0] / [1,1,1,1]
-        xc = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(sv), kFrom0, 0xF, 0xF, true));
-        zg = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(sv), kFrom1, 0xF, 0xF, true));
+        xc = chain_lane_value<S, 0>(sv);
+        zg = chain_lane_value<S, 1>(sv);
     } else {
         xc = silu(pre);
         if constexpr (MODE != kModeNoOutput && MODE != kModePartialRaw) zg = silu(IO::cvt(zraw));
@@ -267,22 +357,27 @@ __device__ __forceinline__ void token_step(Chain<N, S, AKIND, IO>& c, typename I
         y = sum_over_chain_lanes<S>(y);
         y = fmaf(c.dval, xc, y);
         if (MODE == kModePartialRaw) {
-            c.prow[c.ch] = y;
+            sink.park(y);
         } else if (MODE == kModeFinalAddRaw) {
-            IO::st(c.orow + c.ch, (y + part) * zg);
+            sink.final((y + part) * zg);
         } else {
             const float g = y * zg;
-            if (MODE == kModePartial) c.prow[c.ch] = g;
-            else IO::st(c.orow + c.ch, MODE == kModeFinalAdd ? g + part : g);
+            if (MODE == kModePartial) sink.park(g);
+            else sink.final(MODE == kModeFinalAdd ? g + part : g);
         }
     }
-    c.xrow += c.xs;
-    c.dtrow += c.dts;
-    c.zrow += c.zs;
-    c.orow += c.os;
-    c.prow += c.ps;
     c.bcrow += c.bcs;
     c.tok += c.tstep;
+}
+
+template <int N, int S, int AKIND, typename IO>
+__device__ __forceinline__ void advance_rows(Chain<N, S, AKIND, IO>& c, int tokens)
+{
+    c.xrow += tokens * c.xs;
+    c.dtrow += tokens * c.dts;
+    c.zrow += tokens * c.zs;
+    c.orow += tokens * c.os;
+    c.prow += tokens * c.ps;
 }
 
 // Tokens [0, count) of the chain's walk from its current position, tile by tile with the next tile's loads in flight
@@ -299,8 +394,8 @@ __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, 
     if (count <= 0) return;
     int done = 0;
     if (count >= TILE) {
-        Tile cur;
-        load_tile<N, S, AKIND, IO, MODE, TILE>(c, 0, cur);
+        Tile nxt;
+        load_tile<N, S, AKIND, IO, MODE, TILE>(c, 0, nxt);
         BcRow<NS> row;
         float4 stage[kStage];
         int buf = 0;
@@ -332,20 +427,46 @@ __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, 
             load_bc_scalar<N>(c.bcrow, row);
         }
         while (true) {
+            // the tile requested one iteration (or, the first time, a moment) ago; its registers are free for the next
+            // request from here on
+            const Tile cur = nxt;
             const bool more = done + 2 * TILE <= count;
-            Tile nxt;
             if (more) {
                 load_tile<N, S, AKIND, IO, MODE, TILE>(c, TILE, nxt);
                 if constexpr (S > 1) stage_load(TILE);
             }
             const float* tile_bc = lds + buf * (TILE * 2 * N);
+            const TileRows<TILE> to = tile_rows<TILE>(c.orow, c.os), tpk = tile_rows<TILE>(c.prow, c.ps);
             // Delta of the whole tile up front: one uniform branch per tile instead of one per token
             float delta[TILE];
 #pragma unroll
             for (int i = 0; i < TILE; i++) delta[i] = IO::cvt(cur.dt[i]);
             if (softplus_dt) {
+                if constexpr (S > 1 && TILE % S == 0) {
+                    // the S lanes of a chain need the same TILE values: each evaluates TILE / S of them and hands
+                    // them round with quad-permute moves
+                    constexpr int kPer = TILE / S;
+                    float mine[kPer];
 #pragma unroll
-                for (int i = 0; i < TILE; i++) delta[i] = softplus(delta[i] + c.dtb);
+                    for (int i = 0; i < kPer; i++) {
+                        float v = delta[i];
+#pragma unroll
+                        for (int j = 1; j < S; j++) v = c.sub == (unsigned)j ? delta[j * kPer + i] : v;
+                        mine[i] = softplus(v + c.dtb);
+                    }
+#pragma unroll
+                    for (int i = 0; i < kPer; i++) {
+                        delta[i] = chain_lane_value<S, 0>(mine[i]);
+                        delta[kPer + i] = chain_lane_value<S, 1>(mine[i]);
+                        if constexpr (S == 4) {
+                            delta[2 * kPer + i] = chain_lane_value<S, 2>(mine[i]);
+                            delta[3 * kPer + i] = chain_lane_value<S, 3>(mine[i]);
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < TILE; i++) delta[i] = softplus(delta[i] + c.dtb);
+                }
             }
 #pragma unroll
             for (int i = 0; i < TILE; i++) {
@@ -359,7 +480,8 @@ __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, 
                     load_bc_scalar<N>(done + i + 1 < count ? c.bcrow + c.bcs : c.bcrow, row_next);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                token_step<N, S, AKIND, IO, MODE>(c, cur.x[i], delta[i], cur.z[i], cur.part[i], row);
+                token_step<N, S, AKIND, IO, MODE>(c, cur.x[i], delta[i], cur.z[i], cur.part[i], row,
+                                                  TileSink<IO, TILE>{to, tpk, c.ch_io, c.ch_f32, i});
                 if constexpr (S > 1) {
                     if (i + 1 < TILE) row = row_next;
                 } else if constexpr (BCSRC == kBcStaged) {
@@ -370,8 +492,8 @@ __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, 
                 }
             }
             done += TILE;
+            advance_rows(c, TILE);
             if (!more) break;
-            cur = nxt;
             if constexpr (S > 1) {
                 buf ^= 1;
                 stage_store(buf);
@@ -380,17 +502,18 @@ __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, 
         }
     }
     for (; done < count; done++) {
-        typename IO::T xr = c.xrow[c.ch], dr = c.dtrow[c.head], zr = 0;
+        typename IO::T xr = *lane_elem(c.xrow, c.ch_io), dr = *lane_elem(c.dtrow, c.head_io), zr = 0;
         float part = 0.0f;
-        if (mode_reads_z(MODE)) zr = c.zrow[c.ch];
-        if (mode_reads_partial(MODE)) part = c.prow[c.ch];
+        if (mode_reads_z(MODE)) zr = *lane_elem(c.zrow, c.ch_io);
+        if (mode_reads_partial(MODE)) part = *lane_elem(c.prow, c.ch_f32);
         BcRow<NS> row;
         if constexpr (S > 1) load_bc_direct<N, S>(c.bcrow, c.sub, row);
         else if constexpr (BCSRC == kBcStaged) load_bc_lds<N, 1>(lds, c.tok, 0, row);
         else if constexpr (kBcScalarAhead<N, S>) load_bc_scalar<N>(c.bcrow, row);
         float delta = IO::cvt(dr);
         if (softplus_dt) delta = softplus(delta + c.dtb);
-        token_step<N, S, AKIND, IO, MODE>(c, xr, delta, zr, part, row);
+        token_step<N, S, AKIND, IO, MODE>(c, xr, delta, zr, part, row, RowSink<IO>{c.orow, c.prow, c.ch_io, c.ch_f32});
+        advance_rows(c, 1);
     }
 }
 
@@ -406,20 +529,33 @@ __device__ __forceinline__ unsigned xcd_aware_tile(unsigned g, unsigned n)
     return g / kGroup * kGroup + (g % 8) * S + (g / 8) % S;
 }
 
-// grid (ceil(Dn / (64/S)), nseg, batch), block 128: wave 0 walks left-to-right, wave 1 right-to-left.
-template <int N, int S, int AKIND, typename IO, int KIND, int TILE, int BCSRC = kBcPrepared>
-__device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, const int s)
+// The channel tile of wave w of this workgroup.  A workgroup holds two adjacent tiles (waves 0 / 1 walk the first
+// left-to-right / right-to-left, waves 2 / 3 the second), so each of a CU's four SIMDs gets one wave of every
+// workgroup and the SIMDs stay evenly loaded.  With an odd number of tiles the last workgroup's second pair shadows
+// the first: same inputs, same values, same addresses.
+template <int S>
+__device__ __forceinline__ int tile_of_wave(int w, int Dn)
 {
+    constexpr int kCpw = 64 / S;
+    const unsigned pair = xcd_aware_tile<(S + 1) / 2>(blockIdx.x, gridDim.x);
+    return min((int)(pair * 2 + (w >> 1)), (Dn + kCpw - 1) / kCpw - 1);
+}
+
+// grid (ceil(ceil(Dn / (64/S)) / 2), nseg, batch), block 256.
+template <int N, int S, int AKIND, typename IO, int KIND, int TILE, int BCSRC = kBcPrepared>
+__device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, const int w)
+{
+    const int s = w & 1;
     using T = typename IO::T;
     constexpr int NS = N / S;
     constexpr int kCpw = 64 / S;  // channels per wave
     const int lane = threadIdx.x & 63;
-    float* lds = lds_all + (BCSRC == kBcStaged ? s * (kShortCallTokens * 2 * N) : S > 1 ? s * (2 * TILE * 2 * N) : 0);
+    float* lds = lds_all + (BCSRC == kBcStaged ? w * (kShortCallTokens * 2 * N) : S > 1 ? w * (2 * TILE * 2 * N) : 0);
     const DirArgs& da = a.dir[s];
     const int b = blockIdx.z, seg = blockIdx.y;
     // Lanes past the last channel shadow channel Dn-1: they load the same inputs, compute the same values and
     // store them to the same addresses, so no lane needs masking anywhere below.
-    const int tile = xcd_aware_tile<S>(blockIdx.x, gridDim.x);
+    const int tile = tile_of_wave<S>(w, a.Dn);
     const int ch = min((int)(tile * kCpw + lane / S), a.Dn - 1);
     const int sub = lane % S;
     const int head = ch / a.P;
@@ -438,8 +574,9 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, c
     const int tstart = s == 0 ? t0 : t1 - 1;
 
     Chain<N, S, AKIND, IO> c;
-    c.ch = ch;
-    c.head = head;
+    c.ch_io = (unsigned)ch * (unsigned)sizeof(T);
+    c.head_io = (unsigned)head * (unsigned)sizeof(T);
+    c.ch_f32 = (unsigned)ch * 4u;
     c.sub = sub;
     // per-lane constants
     {
@@ -546,30 +683,29 @@ template <int N, typename IO>
 constexpr bool kProgressionEligible = (N >= 2 && N <= 32 && sizeof(typename IO::T) == 2);
 
 template <int N, int S, int AKIND, typename IO, int KIND, int TILE, int BCSRC = kBcPrepared>
-__global__ __launch_bounds__(128) void sweep_kernel(const SweepArgs a)
+__global__ __launch_bounds__(256) void sweep_kernel(const SweepArgs a)
 {
-    __shared__ __attribute__((aligned(16))) float lds_all[BCSRC == kBcStaged ? 2 * kShortCallTokens * 2 * N
-                                                          : S > 1            ? 2 * 2 * TILE * 2 * N
+    __shared__ __attribute__((aligned(16))) float lds_all[BCSRC == kBcStaged ? 4 * kShortCallTokens * 2 * N
+                                                          : S > 1            ? 4 * 2 * TILE * 2 * N
                                                                              : 4];
-    const int s = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     if constexpr (AKIND == kAPerState && kProgressionEligible<N, IO>) {
         // Every lane checks its own chain's A row: A[h, n] == fma(n, A[h, 1] - A[h, 0], A[h, 0]) for all n.  The wave takes
         // the two-exponential form only if all of its chains qualify (a wave-uniform vote, no extra launch).
         if (a.try_progression) {
-            const int tile = xcd_aware_tile<S>(blockIdx.x, gridDim.x);
-            const int ch = min((int)(tile * (64 / S) + (threadIdx.x & 63) / S), a.Dn - 1);
-            const float* row = a.dir[s].A + (size_t)(ch / a.P) * N;
+            const int ch = min((int)(tile_of_wave<S>(w, a.Dn) * (64 / S) + (threadIdx.x & 63) / S), a.Dn - 1);
+            const float* row = a.dir[w & 1].A + (size_t)(ch / a.P) * N;
             const float first = row[0], step = row[1] - row[0];
             bool ok = true;
 #pragma unroll
             for (int n = 0; n < N; n++) ok &= row[n] == fmaf((float)n, step, first);
             if (__all(ok)) {
-                sweep_body<N, S, kAProgression, IO, KIND, TILE, BCSRC>(a, lds_all, s);
+                sweep_body<N, S, kAProgression, IO, KIND, TILE, BCSRC>(a, lds_all, w);
                 return;
             }
         }
     }
-    sweep_body<N, S, AKIND, IO, KIND, TILE, BCSRC>(a, lds_all, s);
+    sweep_body<N, S, AKIND, IO, KIND, TILE, BCSRC>(a, lds_all, w);
 }
 
 // Stitch time segments: carry[s][b][seg] holds each segment's end state from a zero start (summary pass); replace it

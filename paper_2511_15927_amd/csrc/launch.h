@@ -5,7 +5,7 @@
 namespace bm {
 #define BM_DECLARE_SCAN(n, s)                                                                                      \
     void launch_scan_n##n##_s##s(int a_scalar_per_head, int io_bf16, const SweepArgs& sa, const CarryArgs& ca,     \
-                                 int batch, int shallow_tile, int short_call, hipStream_t st, hipEvent_t ev_start,    \
+                                 int batch, int short_call, hipStream_t st, hipEvent_t ev_start,                   \
                                  hipEvent_t ev_stop);
 BM_DECLARE_SCAN(4, 1)
 BM_DECLARE_SCAN(8, 1)

@@ -3,66 +3,149 @@
 #include "kernels.h"
 #include "launch.h"
 
+#include <atomic>
+
 #if !defined(BM_N) || !defined(BM_S)
 #error "compile with -DBM_N=<d_state> -DBM_S=<lanes per chain>"
 #endif
 
 namespace bm {
+namespace {  // this file is compiled once per (BM_N, BM_S): nothing below may be shared between those objects
 
-template <int AKIND, typename IO, int TILE>
-static void launch_tile(const SweepArgs& sa, const CarryArgs& ca, int batch, hipStream_t st, hipEvent_t ev_start,
-                        hipEvent_t ev_stop)
-{
-    constexpr int kCpw = 64 / BM_S;
-    const dim3 grid((unsigned)((sa.Dn + kCpw - 1) / kCpw), (unsigned)sa.nseg, (unsigned)batch);
-    if (sa.nseg > 1) {
-        hipLaunchKernelGGL((sweep_kernel<BM_N, BM_S, AKIND, IO, kSummary, TILE>), grid, dim3(128), 0, st, sa);
-        const long long threads = 2LL * ca.batch * ca.Dn;
-        hipLaunchKernelGGL((carry_kernel<BM_N, AKIND>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, ca);
+// Even spread of a launch over the CUs.  The dispatcher places a workgroup wherever one fits, so a launch with fewer
+// workgroups than the chip can hold ends up with some CUs full and others half empty, and the full ones set the
+// kernel's duration.  Asking for a slice of LDS that nothing touches caps the workgroups resident on a CU at the
+// number an even spread needs (per round, when the launch takes several), which makes the spread even.
+constexpr int kLdsPerCu = 160 * 1024;
+constexpr int kLdsPerLaunchDefault = 64 * 1024;  // above this a kernel needs hipFuncAttributeMaxDynamicSharedMemorySize
+constexpr int kBlock = 256;
+
+// What a CU holds of one kernel: workgroups resident at once (registers, static LDS) and the static LDS of each.
+struct KernelFit {
+    std::atomic<int> resident{0};  // 0 = not asked yet
+    std::atomic<int> static_lds{0};
+
+    template <typename Kernel>
+    int ask(Kernel kernel)
+    {
+        int r = resident.load(std::memory_order_relaxed);
+        if (r == 0) {
+            hipFuncAttributes fa;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&r, kernel, kBlock, 0) != hipSuccess || r < 1) r = 1;
+            static_lds.store(hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kernel)) == hipSuccess ? (int)fa.sharedSizeBytes : 0,
+                             std::memory_order_relaxed);
+            resident.store(r, std::memory_order_relaxed);
+        }
+        return r;
     }
-    if (ev_start) (void)hipEventRecord(ev_start, st);
-    hipLaunchKernelGGL((sweep_kernel<BM_N, BM_S, AKIND, IO, kSweep, TILE>), grid, dim3(128), 0, st, sa);
-    if (ev_stop) (void)hipEventRecord(ev_stop, st);
+};
+
+static long long workgroups_per_cu(const dim3& grid)
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int> cached[kMaxDevices];
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) {
+        cus = cached[dev].load(std::memory_order_relaxed);
+        if (cus == 0) {
+            if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+            cached[dev].store(cus, std::memory_order_relaxed);
+        }
+    }
+    return ((long long)grid.x * grid.y * grid.z + cus - 1) / cus;
 }
 
-// Shallow tiles exist for one lane per chain and up to 32 states (the case with enough chains for four or more waves
-// per SIMD); every other instantiation uses the deep tile.
+static long long rounds(long long per_cu, int resident) { return (per_cu + resident - 1) / resident; }
+
+// Bytes of dynamic LDS to ask for so that the launch spreads evenly (0: nothing to gain, or more than a launch may
+// ask for without raising the kernel's limit).
+template <typename Kernel>
+static unsigned spread_lds(Kernel kernel, KernelFit* fit, const dim3& grid)
+{
+    const int resident = fit->ask(kernel);
+    const long long per_cu = workgroups_per_cu(grid), n = rounds(per_cu, resident);
+    const int cap = (int)((per_cu + n - 1) / n);
+    if (cap >= resident) return 0;
+    // between the largest slice of which cap + 1 fit and the largest of which cap fit
+    const int slice = (kLdsPerCu / cap + kLdsPerCu / (cap + 1)) / 2 / 256 * 256;
+    const int extra = slice - fit->static_lds.load(std::memory_order_relaxed);
+    return slice > kLdsPerLaunchDefault || extra < 0 ? 0u : (unsigned)extra;
+}
+
+static dim3 sweep_grid(const SweepArgs& sa, int batch)
+{
+    constexpr int kCpw = 64 / BM_S;
+    return dim3((unsigned)(((sa.Dn + kCpw - 1) / kCpw + 1) / 2), (unsigned)sa.nseg, (unsigned)batch);
+}
+
+template <int AKIND, typename IO, int TILE>
+struct Tiled {
+    static inline KernelFit fit_summary, fit_sweep;
+    static constexpr auto summary = sweep_kernel<BM_N, BM_S, AKIND, IO, kSummary, TILE>;
+    static constexpr auto sweep = sweep_kernel<BM_N, BM_S, AKIND, IO, kSweep, TILE>;
+
+    static void launch(const SweepArgs& sa, const CarryArgs& ca, int batch, hipStream_t st, hipEvent_t ev_start,
+                       hipEvent_t ev_stop)
+    {
+        const dim3 grid = sweep_grid(sa, batch);
+        if (sa.nseg > 1) {
+            hipLaunchKernelGGL(summary, grid, dim3(kBlock), spread_lds(summary, &fit_summary, grid), st, sa);
+            const long long threads = 2LL * ca.batch * ca.Dn;
+            hipLaunchKernelGGL((carry_kernel<BM_N, AKIND>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, ca);
+        }
+        const unsigned lds = spread_lds(sweep, &fit_sweep, grid);
+        if (ev_start) (void)hipEventRecord(ev_start, st);
+        hipLaunchKernelGGL(sweep, grid, dim3(kBlock), lds, st, sa);
+        if (ev_stop) (void)hipEventRecord(ev_stop, st);
+    }
+};
+
+// One lane per chain and up to 32 states come with two prefetch depths: the deep tile hides memory latency when a
+// SIMD holds few waves, the shallow one needs fewer registers, so more waves are resident at once.  The shallow tile
+// is taken when it gets the launch through in fewer rounds of resident workgroups.
 template <int AKIND, typename IO>
-static void launch_one(const SweepArgs& sa, const CarryArgs& ca, int batch, int shallow_tile, int short_call,
-                       hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop)
+static void launch_one(const SweepArgs& sa, const CarryArgs& ca, int batch, int short_call, hipStream_t st,
+                       hipEvent_t ev_start, hipEvent_t ev_stop)
 {
 #if BM_S == 1 && BM_N <= 16
     if (short_call) {   // one launch: the kernel converts the caller's B and C rows itself (see kBcStaged)
-        const dim3 grid((unsigned)((sa.Dn + 63) / 64), 1, (unsigned)batch);
+        const dim3 grid((unsigned)(((sa.Dn + 63) / 64 + 1) / 2), 1, (unsigned)batch);
+        static KernelFit fit_short;
+        auto sweep = sweep_kernel<BM_N, BM_S, AKIND, IO, kSweep, 8, kBcStaged>;
+        const unsigned lds = spread_lds(sweep, &fit_short, grid);
         if (ev_start) (void)hipEventRecord(ev_start, st);
-        hipLaunchKernelGGL((sweep_kernel<BM_N, BM_S, AKIND, IO, kSweep, 8, kBcStaged>), grid, dim3(128), 0, st, sa);
+        hipLaunchKernelGGL(sweep, grid, dim3(kBlock), lds, st, sa);
         if (ev_stop) (void)hipEventRecord(ev_stop, st);
         return;
     }
 #endif
     (void)short_call;
+    using Deep = Tiled<AKIND, IO, 8>;
 #if BM_S == 1 && BM_N <= 32
-    if (shallow_tile) {
-        launch_tile<AKIND, IO, 4>(sa, ca, batch, st, ev_start, ev_stop);
+    using Shallow = Tiled<AKIND, IO, 4>;
+    const long long per_cu = workgroups_per_cu(sweep_grid(sa, batch));
+    if (rounds(per_cu, Shallow::fit_sweep.ask(Shallow::sweep)) < rounds(per_cu, Deep::fit_sweep.ask(Deep::sweep))) {
+        Shallow::launch(sa, ca, batch, st, ev_start, ev_stop);
         return;
     }
 #endif
-    (void)shallow_tile;
-    launch_tile<AKIND, IO, 8>(sa, ca, batch, st, ev_start, ev_stop);
+    Deep::launch(sa, ca, batch, st, ev_start, ev_stop);
 }
+
+}  // namespace
 
 #define BM_CAT4(a, b, c, d) a##b##c##d
 #define BM_NAME(n, s) BM_CAT4(launch_scan_n, n, _s, s)
 
 void BM_NAME(BM_N, BM_S)(int a_scalar_per_head, int io_bf16, const SweepArgs& sa, const CarryArgs& ca, int batch,
-                         int shallow_tile, int short_call, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop)
+                         int short_call, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     if (a_scalar_per_head) {
-        if (io_bf16) launch_one<1, IoBF16>(sa, ca, batch, shallow_tile, short_call, st, ev_start, ev_stop);
-        else launch_one<1, IoF32>(sa, ca, batch, shallow_tile, short_call, st, ev_start, ev_stop);
+        if (io_bf16) launch_one<1, IoBF16>(sa, ca, batch, short_call, st, ev_start, ev_stop);
+        else launch_one<1, IoF32>(sa, ca, batch, short_call, st, ev_start, ev_stop);
     } else {
-        if (io_bf16) launch_one<0, IoBF16>(sa, ca, batch, shallow_tile, short_call, st, ev_start, ev_stop);
-        else launch_one<0, IoF32>(sa, ca, batch, shallow_tile, short_call, st, ev_start, ev_stop);
+        if (io_bf16) launch_one<0, IoBF16>(sa, ca, batch, short_call, st, ev_start, ev_stop);
+        else launch_one<0, IoF32>(sa, ca, batch, short_call, st, ev_start, ev_stop);
     }
 }
 

@@ -58,6 +58,8 @@ def test_null_and_shape_errors_are_decided_on_the_host():
     assert call_fwd(desc, p, p, narrow, out) == -2
     overlap = bd.Inputs(bd.Tensor(0x1000, 128, 128), inp.z, inp.dt, inp.B, inp.C)
     assert call_fwd(desc, p, p, overlap, out) == -2
+    wide = bd.Inputs(bd.Tensor(0x1000, 64 * ((1 << 26) + 1), (1 << 26) + 1), inp.z, inp.dt, inp.B, inp.C)
+    assert call_fwd(desc, p, p, wide, out) == -3                 # token stride beyond what a tile's 32-bit row offsets reach
 
 
 @pytest.mark.parametrize("field,value,code", [
