@@ -28,6 +28,8 @@ def parse():
     ap.add_argument("--workload", default="headline", help="name in synth.CONFIGS (default: d_inner=4096, L=8192, batch 8, bf16)")
     ap.add_argument("--general-a", action="store_true", help="draw A with no structure across states")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-general-a", action="store_true",
+                    help="skip the structure-free-A comparison leg (profiling runs: it launches the same kernel)")
     ap.add_argument("--cpu-batches", type=int, default=2, help="batch elements the oracle is timed on")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run three 1 GiB device-to-device copies (a known-size reference for HBM counters)")
@@ -130,7 +132,7 @@ def main():
     value = tokens / (ms_per_step * 1e-3)
     # the same workload with a structure-free A[d, n] (one exponential per state instead of the detected progression)
     general = None
-    if not args.general_a and cfg["a_kind"] == 0:
+    if not args.general_a and not args.no_general_a and cfg["a_kind"] == 0:
         gpf, gpb = dict(pf), dict(pb)
         gpf["A"], gpb["A"] = synth.random_A(cfg, seed), synth.random_A(cfg, seed + 1)
         dgf, dgb = bd.to_device(gpf), bd.to_device(gpb)

@@ -4,11 +4,11 @@
 // d_state recurrence values in registers.  S adjacent lanes share a chain, each holding d_state/S of the states
 // (S = 1, 2 or 4, chosen by the host so that the launch has enough waves to fill 1024 SIMDs); their partial dot
 // products C_t . h_t are summed with DPP lane swaps.  A wave therefore covers 64/S adjacent channels and every
-// per-token access of x / dt / z / out is one contiguous run, addressed as a wave-uniform row pointer plus a constant
-// lane offset.  A workgroup holds the forward wave and the reverse wave of the same channels.  For the additive
-// combine (eq. 6) the two waves meet in the middle of the segment: in the first half of its walk each wave parks
-// its output as an fp32 partial, in the second half it adds the partial the other wave parked there and performs the
-// single rounding to the I/O dtype.
+// per-token access of x / dt / z / out is one contiguous run, addressed as a wave-uniform row plus a constant lane
+// offset.  A workgroup holds the forward wave and the reverse wave of two adjacent channel tiles, one wave for each of
+// a CU's four SIMDs.  For the additive combine (eq. 6) the two waves of a tile meet in the middle of the segment: in
+// the first half of its walk each wave parks its output as an fp32 partial, in the second half it adds the partial
+// the other wave parked there and performs the single rounding to the I/O dtype.
 //
 // B_t and C_t come from an fp32 copy made by prep_bc_kernel.  With S = 1 they are wave-uniform and are fetched one
 // token ahead with scalar loads; with S > 1 each lane needs its own slice, so a tile of rows is staged through LDS
