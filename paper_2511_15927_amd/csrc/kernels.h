@@ -57,6 +57,8 @@ struct SweepArgs {
     int dt_softplus, d_per_head, separate;
     int raw_partial;      // both directions gate with the same z: park y ungated and gate once at the final store
     int try_progression;  // let each wave test whether its chains' A rows are arithmetic in n (see sweep_kernel)
+    int layer_wgs;        // workgroups the dispatcher places before a CU gets its next one (the CU count); set by the launcher
+    int turn_mask;        // 0: leave wave priorities alone; 1 / 3: two / up to four waves share a SIMD and take turns
 };
 
 // Buffer resource of a raw (untyped, unstrided) range starting at a wave-uniform address.  An access adds a
@@ -380,11 +382,32 @@ __device__ __forceinline__ void advance_rows(Chain<N, S, AKIND, IO>& c, int toke
     c.prow += tokens * c.ps;
 }
 
+// Waves that share a SIMD take turns at the top issue priority.  Left alone, the arbiter favours the oldest wave: the
+// workgroups a CU received first run ahead, finish early and leave the younger ones alone on the SIMD, where a
+// single wave cannot keep the vector pipe busy (measured at two waves per SIMD: lifetimes 1.84 and 2.38 ms for the two
+// halves of the launch, 2.27 ms for all with turns).  The turn is a function of the constant-rate clock, which all
+// waves read alike, and of the order in which the workgroups reached the CU, so at any moment the waves of a SIMD
+// hold different priorities however far they have drifted apart.
+constexpr int kTurnShift = 12;  // a turn lasts 2^12 ticks of the 100 MHz clock
+__device__ __forceinline__ void take_turn(const SweepArgs& a)
+{
+    // read from the kernel arguments where needed, not carried through the walk in registers
+    const unsigned mask = (unsigned)a.turn_mask;
+    if (mask == 0) return;
+    const unsigned turn = ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) / (unsigned)a.layer_wgs;
+    const unsigned p = ((unsigned)(wall_clock64() >> kTurnShift) + turn) & mask;
+    if (p == 0) __builtin_amdgcn_s_setprio(0);
+    else if (p == 1) __builtin_amdgcn_s_setprio(1);
+    else if (p == 2) __builtin_amdgcn_s_setprio(2);
+    else __builtin_amdgcn_s_setprio(3);
+}
+
 // Tokens [0, count) of the chain's walk from its current position, tile by tile with the next tile's loads in flight
 // and the next token's B|C slice requested before the current token is computed.  lds: this wave's private staging
 // area of 2 * TILE * 2N floats (S > 1 only).
 template <int N, int S, int AKIND, typename IO, int MODE, int TILE, int BCSRC = kBcPrepared>
-__device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, bool softplus_dt, float* lds, int lane)
+__device__ __forceinline__ void run_range(const SweepArgs& a, Chain<N, S, AKIND, IO>& c, int count, bool softplus_dt, float* lds,
+                                          int lane)
 {
     static_assert(BCSRC == kBcPrepared || (S == 1 && N <= 16), "staged rows exist for one lane per chain, <= 16 states");
     constexpr int NS = N / S;
@@ -432,6 +455,8 @@ __device__ __forceinline__ void run_range(Chain<N, S, AKIND, IO>& c, int count, 
             const Tile cur = nxt;
             const bool more = done + 2 * TILE <= count;
             if (more) {
+                // every fourth tile (the clock read is not free), here because this block starts at a branch anyway
+                if ((done & (4 * TILE - 1)) == 0) take_turn(a);
                 load_tile<N, S, AKIND, IO, MODE, TILE>(c, TILE, nxt);
                 if constexpr (S > 1) stage_load(TILE);
             }
@@ -651,7 +676,7 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, c
     const bool sp = a.dt_softplus != 0;
 
     if (KIND == kSummary) {
-        run_range<N, S, AKIND, IO, kModeNoOutput, TILE>(c, len, sp, lds, lane);
+        run_range<N, S, AKIND, IO, kModeNoOutput, TILE>(a, c, len, sp, lds, lane);
         float* dst = a.carry + ((((size_t)s * gridDim.z + b) * a.nseg + seg) * a.Dn + ch) * N + sub * NS;
 #pragma unroll
         for (int n = 0; n < NS; n++) dst[n] = c.h[n];
@@ -660,15 +685,15 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, c
     }
 
     if (a.separate) {
-        run_range<N, S, AKIND, IO, kModeFinalOnly, TILE, BCSRC>(c, len, sp, lds, lane);
+        run_range<N, S, AKIND, IO, kModeFinalOnly, TILE, BCSRC>(a, c, len, sp, lds, lane);
     } else {
         // forward parks [t0, m), reverse parks [m, t1); then each finishes the other's half
         const int n_first = s == 0 ? (len + 1) / 2 : len / 2;
-        if (a.raw_partial) run_range<N, S, AKIND, IO, kModePartialRaw, TILE, BCSRC>(c, n_first, sp, lds, lane);
-        else run_range<N, S, AKIND, IO, kModePartial, TILE, BCSRC>(c, n_first, sp, lds, lane);
+        if (a.raw_partial) run_range<N, S, AKIND, IO, kModePartialRaw, TILE, BCSRC>(a, c, n_first, sp, lds, lane);
+        else run_range<N, S, AKIND, IO, kModePartial, TILE, BCSRC>(a, c, n_first, sp, lds, lane);
         __syncthreads();  // workgroup-scope release/acquire: the other wave's partials are visible from here on
-        if (a.raw_partial) run_range<N, S, AKIND, IO, kModeFinalAddRaw, TILE, BCSRC>(c, len - n_first, sp, lds, lane);
-        else run_range<N, S, AKIND, IO, kModeFinalAdd, TILE, BCSRC>(c, len - n_first, sp, lds, lane);
+        if (a.raw_partial) run_range<N, S, AKIND, IO, kModeFinalAddRaw, TILE, BCSRC>(a, c, len - n_first, sp, lds, lane);
+        else run_range<N, S, AKIND, IO, kModeFinalAdd, TILE, BCSRC>(a, c, len - n_first, sp, lds, lane);
     }
     if (s == 0 && a.nseg == 1 && a.h_out) {
         float* dst = a.h_out + ((size_t)b * a.Dn + ch) * N + sub * NS;

@@ -40,7 +40,7 @@ struct KernelFit {
     }
 };
 
-static long long workgroups_per_cu(const dim3& grid)
+static int cu_count()
 {
     constexpr int kMaxDevices = 64;
     static std::atomic<int> cached[kMaxDevices];
@@ -52,7 +52,26 @@ static long long workgroups_per_cu(const dim3& grid)
             cached[dev].store(cus, std::memory_order_relaxed);
         }
     }
+    return cus;
+}
+
+static long long workgroups_per_cu(const dim3& grid)
+{
+    const long long cus = cu_count();
     return ((long long)grid.x * grid.y * grid.z + cus - 1) / cus;
+}
+
+// How the waves that share a SIMD take turns at the issue priority (see take_turn): workgroups reach a CU in layers
+// of one per CU, and a workgroup puts one wave on each SIMD, so a SIMD holds one wave per resident layer.
+static SweepArgs with_turns(const SweepArgs& sa, const dim3& grid, int resident)
+{
+    SweepArgs s = sa;
+    // Only when the whole launch is resident at once: with several rounds the workgroups start at different times
+    // anyway and turns were measured to cost 5-6 %.
+    const long long per_cu = workgroups_per_cu(grid);
+    s.layer_wgs = cu_count();
+    s.turn_mask = per_cu < 2 || per_cu > resident ? 0 : per_cu == 2 ? 1 : 3;
+    return s;
 }
 
 static long long rounds(long long per_cu, int resident) { return (per_cu + resident - 1) / resident; }
@@ -89,13 +108,14 @@ struct Tiled {
     {
         const dim3 grid = sweep_grid(sa, batch);
         if (sa.nseg > 1) {
-            hipLaunchKernelGGL(summary, grid, dim3(kBlock), spread_lds(summary, &fit_summary, grid), st, sa);
+            hipLaunchKernelGGL(summary, grid, dim3(kBlock), spread_lds(summary, &fit_summary, grid), st,
+                               with_turns(sa, grid, fit_summary.ask(summary)));
             const long long threads = 2LL * ca.batch * ca.Dn;
             hipLaunchKernelGGL((carry_kernel<BM_N, AKIND>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, ca);
         }
         const unsigned lds = spread_lds(sweep, &fit_sweep, grid);
         if (ev_start) (void)hipEventRecord(ev_start, st);
-        hipLaunchKernelGGL(sweep, grid, dim3(kBlock), lds, st, sa);
+        hipLaunchKernelGGL(sweep, grid, dim3(kBlock), lds, st, with_turns(sa, grid, fit_sweep.ask(sweep)));
         if (ev_stop) (void)hipEventRecord(ev_stop, st);
     }
 };
@@ -114,7 +134,7 @@ static void launch_one(const SweepArgs& sa, const CarryArgs& ca, int batch, int 
         auto sweep = sweep_kernel<BM_N, BM_S, AKIND, IO, kSweep, 8, kBcStaged>;
         const unsigned lds = spread_lds(sweep, &fit_short, grid);
         if (ev_start) (void)hipEventRecord(ev_start, st);
-        hipLaunchKernelGGL(sweep, grid, dim3(kBlock), lds, st, sa);
+        hipLaunchKernelGGL(sweep, grid, dim3(kBlock), lds, st, with_turns(sa, grid, fit_short.ask(sweep)));
         if (ev_stop) (void)hipEventRecord(ev_stop, st);
         return;
     }
