@@ -65,11 +65,11 @@ long long waves_of(const bimamba_desc* d, int split)
 }
 
 // Launch geometry of the lane-per-chain kernels, from measurements on MI355X (1024 SIMDs) with w = the number of waves
-// that one lane per chain gives (2 * batch * d_inner / 64):
-//   w >= 2048   one lane per chain, whole sequence: two or more waves per SIMD already.
-//   w <  2048   two lanes per chain (each holds half the states), whole sequence, when the 2w waves fill the SIMDs
-//               evenly: at most three per SIMD (what the kernel's registers allow at once) and at least 0.9 of a whole
-//               number.  Doubling the waves this way repeats the per-channel work but needs no second pass.
+// that one lane per chain gives (2 * batch * d_inner / 64), up to 32 states:
+//   w > 1536    one lane per chain, whole sequence: 1.5 or more waves per SIMD already.
+//   else        two lanes per chain (each holds half the states), whole sequence, when the 2w waves fill the SIMDs
+//               well in one round of resident waves: 1.8 to 2, or 2.35 to 3 per SIMD (the kernel's registers allow
+//               three at once).  Doubling the waves this way repeats the per-channel work but needs no second pass.
 //               Otherwise one lane per chain and the sequence cut into time segments until about 16 waves per SIMD
 //               exist: the segment summaries cost a second, cheaper pass, but every SIMD then holds enough waves
 //               to issue back to back and to hide the loads, whatever the batch.  Segments stay at 256 tokens or
@@ -97,18 +97,21 @@ int segments_for(const bimamba_desc* d, long long waves)
     return (int)(n < 1 ? 1 : n);
 }
 
-// Two lanes per chain fill the SIMDs evenly in one round of resident waves.
+// Two lanes per chain fill the SIMDs well in one round of resident waves.
 bool two_lanes_fit(long long w)
 {
-    const long long per_simd_x10 = 2 * w * 10 / kSimds, whole = (2 * w + kSimds - 1) / kSimds;
-    return whole >= 2 && whole <= 3 && per_simd_x10 >= 9 * whole;
+    const long long per_simd_x100 = 2 * w * 100 / kSimds;
+    return (per_simd_x100 >= 180 && per_simd_x100 <= 200) || (per_simd_x100 >= 235 && per_simd_x100 <= 300);
 }
+
+// One lane per chain needs no help from segments or lane splitting.
+bool enough_chains(const bimamba_desc* d, long long w) { return many_states(d) ? w >= kTargetWaves : 2 * w > 3 * kSimds; }
 
 int pick_split(const bimamba_desc* d)
 {
     if (d->state_split > 0) return d->state_split;
     const long long w = waves_of(d, 1);
-    if (w >= kTargetWaves) return 1;
+    if (enough_chains(d, w)) return 1;
     const bool two = split_supported(d->d_state, 2), four = d->d_state >= 64 && split_supported(d->d_state, 4);
     if (many_states(d)) return w >= kTargetWaves / 2 && two ? 2 : four ? 4 : two ? 2 : 1;
     if (two && two_lanes_fit(w)) return 2;
@@ -125,7 +128,9 @@ int pick_chunks(const bimamba_desc* d, int split)
         n = d->time_chunks;
     } else {
         const long long waves = waves_of(d, split);
-        const bool whole = split == 2 && d->state_split == 0 && !many_states(d) && two_lanes_fit(waves_of(d, 1));
+        const long long w = waves_of(d, 1);
+        const bool whole = d->state_split == 0 && !many_states(d) &&
+                           (split == 1 ? enough_chains(d, w) : split == 2 && two_lanes_fit(w));
         n = waves >= kTargetWaves || whole ? 1 : segments_for(d, waves);
     }
     if (n > L) n = L;

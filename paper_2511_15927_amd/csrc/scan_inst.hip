@@ -17,24 +17,38 @@ namespace {  // this file is compiled once per (BM_N, BM_S): nothing below may b
 // kernel's duration.  Asking for a slice of LDS that nothing touches caps the workgroups resident on a CU at the
 // number an even spread needs (per round, when the launch takes several), which makes the spread even.
 constexpr int kLdsPerCu = 160 * 1024;
-constexpr int kLdsPerLaunchDefault = 64 * 1024;  // above this a kernel needs hipFuncAttributeMaxDynamicSharedMemorySize
 constexpr int kBlock = 256;
+constexpr int kMaxDevices = 64;
+
+static int current_device()
+{
+    int dev = 0;
+    return hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices ? dev : -1;
+}
 
 // What a CU holds of one kernel: workgroups resident at once (registers, static LDS) and the static LDS of each.
+// Asked once per device; the same call lifts the kernel's dynamic-LDS limit to the whole CU, which the slices of
+// launches with one or two workgroups per CU need.
 struct KernelFit {
-    std::atomic<int> resident{0};  // 0 = not asked yet
-    std::atomic<int> static_lds{0};
+    std::atomic<int> resident[kMaxDevices];  // 0 = not asked yet
+    std::atomic<int> static_lds[kMaxDevices];
+    std::atomic<int> lifted[kMaxDevices];    // the raised limit took effect
 
     template <typename Kernel>
-    int ask(Kernel kernel)
+    int ask(Kernel kernel, int dev)
     {
-        int r = resident.load(std::memory_order_relaxed);
+        if (dev < 0) return 1;
+        int r = resident[dev].load(std::memory_order_acquire);
         if (r == 0) {
             hipFuncAttributes fa;
+            const void* fn = reinterpret_cast<const void*>(kernel);
             if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&r, kernel, kBlock, 0) != hipSuccess || r < 1) r = 1;
-            static_lds.store(hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kernel)) == hipSuccess ? (int)fa.sharedSizeBytes : 0,
-                             std::memory_order_relaxed);
-            resident.store(r, std::memory_order_relaxed);
+            const int fixed = hipFuncGetAttributes(&fa, fn) == hipSuccess ? (int)fa.sharedSizeBytes : 0;
+            static_lds[dev].store(fixed, std::memory_order_relaxed);
+            lifted[dev].store(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu - fixed) == hipSuccess,
+                              std::memory_order_relaxed);
+            (void)hipGetLastError();
+            resident[dev].store(r, std::memory_order_release);
         }
         return r;
     }
@@ -42,10 +56,10 @@ struct KernelFit {
 
 static int cu_count()
 {
-    constexpr int kMaxDevices = 64;
     static std::atomic<int> cached[kMaxDevices];
-    int dev = 0, cus = 256;
-    if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) {
+    const int dev = current_device();
+    int cus = 256;
+    if (dev >= 0) {
         cus = cached[dev].load(std::memory_order_relaxed);
         if (cus == 0) {
             if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
@@ -76,19 +90,20 @@ static SweepArgs with_turns(const SweepArgs& sa, const dim3& grid, int resident)
 
 static long long rounds(long long per_cu, int resident) { return (per_cu + resident - 1) / resident; }
 
-// Bytes of dynamic LDS to ask for so that the launch spreads evenly (0: nothing to gain, or more than a launch may
-// ask for without raising the kernel's limit).
+// Bytes of dynamic LDS to ask for so that the launch spreads evenly (0: nothing to gain).
 template <typename Kernel>
 static unsigned spread_lds(Kernel kernel, KernelFit* fit, const dim3& grid)
 {
-    const int resident = fit->ask(kernel);
+    const int dev = current_device(), resident = fit->ask(kernel, dev);
+    if (dev < 0) return 0;
     const long long per_cu = workgroups_per_cu(grid), n = rounds(per_cu, resident);
     const int cap = (int)((per_cu + n - 1) / n);
     if (cap >= resident) return 0;
     // between the largest slice of which cap + 1 fit and the largest of which cap fit
     const int slice = (kLdsPerCu / cap + kLdsPerCu / (cap + 1)) / 2 / 256 * 256;
-    const int extra = slice - fit->static_lds.load(std::memory_order_relaxed);
-    return slice > kLdsPerLaunchDefault || extra < 0 ? 0u : (unsigned)extra;
+    const int extra = slice - fit->static_lds[dev].load(std::memory_order_relaxed);
+    if (extra < 0 || (slice > 64 * 1024 && !fit->lifted[dev].load(std::memory_order_relaxed))) return 0;
+    return (unsigned)extra;
 }
 
 static dim3 sweep_grid(const SweepArgs& sa, int batch)
@@ -109,13 +124,13 @@ struct Tiled {
         const dim3 grid = sweep_grid(sa, batch);
         if (sa.nseg > 1) {
             hipLaunchKernelGGL(summary, grid, dim3(kBlock), spread_lds(summary, &fit_summary, grid), st,
-                               with_turns(sa, grid, fit_summary.ask(summary)));
+                               with_turns(sa, grid, fit_summary.ask(summary, current_device())));
             const long long threads = 2LL * ca.batch * ca.Dn;
             hipLaunchKernelGGL((carry_kernel<BM_N, AKIND>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, ca);
         }
         const unsigned lds = spread_lds(sweep, &fit_sweep, grid);
         if (ev_start) (void)hipEventRecord(ev_start, st);
-        hipLaunchKernelGGL(sweep, grid, dim3(kBlock), lds, st, with_turns(sa, grid, fit_sweep.ask(sweep)));
+        hipLaunchKernelGGL(sweep, grid, dim3(kBlock), lds, st, with_turns(sa, grid, fit_sweep.ask(sweep, current_device())));
         if (ev_stop) (void)hipEventRecord(ev_stop, st);
     }
 };
@@ -134,7 +149,7 @@ static void launch_one(const SweepArgs& sa, const CarryArgs& ca, int batch, int 
         auto sweep = sweep_kernel<BM_N, BM_S, AKIND, IO, kSweep, 8, kBcStaged>;
         const unsigned lds = spread_lds(sweep, &fit_short, grid);
         if (ev_start) (void)hipEventRecord(ev_start, st);
-        hipLaunchKernelGGL(sweep, grid, dim3(kBlock), lds, st, with_turns(sa, grid, fit_short.ask(sweep)));
+        hipLaunchKernelGGL(sweep, grid, dim3(kBlock), lds, st, with_turns(sa, grid, fit_short.ask(sweep, current_device())));
         if (ev_stop) (void)hipEventRecord(ev_stop, st);
         return;
     }
@@ -144,7 +159,8 @@ static void launch_one(const SweepArgs& sa, const CarryArgs& ca, int batch, int 
 #if BM_S == 1 && BM_N <= 32
     using Shallow = Tiled<AKIND, IO, 4>;
     const long long per_cu = workgroups_per_cu(sweep_grid(sa, batch));
-    if (rounds(per_cu, Shallow::fit_sweep.ask(Shallow::sweep)) < rounds(per_cu, Deep::fit_sweep.ask(Deep::sweep))) {
+    const int dev = current_device();
+    if (rounds(per_cu, Shallow::fit_sweep.ask(Shallow::sweep, dev)) < rounds(per_cu, Deep::fit_sweep.ask(Deep::sweep, dev))) {
         Shallow::launch(sa, ca, batch, st, ev_start, ev_stop);
         return;
     }
