@@ -297,9 +297,14 @@ __device__ __forceinline__ void load_bc_lds(const float* tile, int i, unsigned s
 
 // One token of one chain slice: conv + SiLU, discretise, state updates, skip term, gate, output.  Advances the B|C
 // row and the token counter; the caller advances the other rows.
-template <int N, int S, int AKIND, typename IO, int MODE, typename Sink>
+// REFILL (scalar-register rows): `row` holds this token's B|C on entry and the values at `next` on exit.  The
+// state updates (which read B) and the output dot product (which reads C) run as two loops, and each half of the row
+// is requested again as soon as its loop is done, into the registers it just freed: one row of scalar registers
+// instead of two, with more than half a token of work between a request and its first use.
+template <int N, int S, int AKIND, typename IO, int MODE, bool REFILL, typename Sink>
 __device__ __forceinline__ void token_step(Chain<N, S, AKIND, IO>& c, typename IO::T xraw, float delta,
-                                           typename IO::T zraw, float part, const BcRow<N / S>& row, const Sink& sink)
+                                           typename IO::T zraw, float part, BcRow<N / S>& row, const float* next,
+                                           const Sink& sink)
 {
     constexpr int NS = N / S;
     const float x0 = IO::cvt(xraw);
@@ -329,7 +334,37 @@ __device__ __forceinline__ void token_step(Chain<N, S, AKIND, IO>& c, typename I
     uniform_ro_ptr bcmem = (uniform_ro_ptr)c.bcrow;  // only for S = 1 rows too long to prefetch
     constexpr bool kFromMem = (S == 1 && N > 16);
     auto bc = [&](int n) -> float { return kFromMem ? bcmem[n < NS ? n : n - NS + N] : row.v[n]; };
-    if (AKIND == kAPerState) {
+    if constexpr (REFILL) {
+        uniform_ro_ptr q = (uniform_ro_ptr)next;
+        if (AKIND == kAPerState) {
+#pragma unroll
+            for (int n = 0; n < NS; n++) c.h[n] = fmaf(fast_exp2(delta * c.a2[n]), c.h[n], u * row.v[n]);
+        } else if (AKIND == kAProgression) {
+            float an = fast_exp2(delta * c.a2[0]);
+            const float ratio = fast_exp2(delta * c.d2);
+#pragma unroll
+            for (int n = 0; n < NS; n++) {
+                c.h[n] = fmaf(an, c.h[n], u * row.v[n]);
+                an *= ratio;
+            }
+        } else {
+            const float a = fast_exp2(delta * c.a2[0]);
+#pragma unroll
+            for (int n = 0; n < NS; n++) c.h[n] = fmaf(a, c.h[n], u * row.v[n]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int n = 0; n < NS; n++) row.v[n] = q[n];
+        __builtin_amdgcn_sched_barrier(0);
+        if (MODE != kModeNoOutput) {
+#pragma unroll
+            for (int n = 0; n < NS; n++) y = fmaf(row.v[NS + n], c.h[n], y);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int n = 0; n < NS; n++) row.v[NS + n] = q[N + n];
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else if (AKIND == kAPerState) {
 #pragma unroll
         for (int n = 0; n < NS; n++) {
             const float a = fast_exp2(delta * c.a2[n]);
@@ -413,6 +448,10 @@ __device__ __forceinline__ void run_range(const SweepArgs& a, Chain<N, S, AKIND,
     constexpr int NS = N / S;
     constexpr int kRowF4 = 2 * N / 4;              // float4s per B|C row
     constexpr int kStage = (TILE * kRowF4 + 63) / 64;  // float4s each lane moves per staged tile
+    // With the shallow tile (many waves per SIMD) token_step refills the one scalar row itself; with the deep tile
+    // (two or three waves per SIMD, less cover for a scalar load) the next token's row is requested a whole token
+    // ahead into a second set of registers.
+    constexpr bool kRefill = kBcScalarAhead<N, S> && BCSRC == kBcPrepared && TILE == 4;
     using Tile = RawTile<IO, TILE>;
     if (count <= 0) return;
     int done = 0;
@@ -500,18 +539,20 @@ __device__ __forceinline__ void run_range(const SweepArgs& a, Chain<N, S, AKIND,
                     if (i + 1 < TILE) load_bc_lds<N, S>(tile_bc, i + 1, c.sub, row_next);
                 } else if constexpr (BCSRC == kBcStaged) {
                     load_bc_lds<N, 1>(lds, done + i + 1 < count ? c.tok + c.tstep : c.tok, 0, row_next);
-                } else if constexpr (kBcScalarAhead<N, S>) {
-                    // never read past the walk's last token: the row after it may lie outside the buffer
-                    load_bc_scalar<N>(done + i + 1 < count ? c.bcrow + c.bcs : c.bcrow, row_next);
+                }
+                // never read past the walk's last token: the row after it may lie outside the buffer
+                const float* next = kBcScalarAhead<N, S> ? (done + i + 1 < count ? c.bcrow + c.bcs : c.bcrow) : nullptr;
+                if constexpr (kBcScalarAhead<N, S> && BCSRC == kBcPrepared && !kRefill) {
+                    load_bc_scalar<N>(next, row_next);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                token_step<N, S, AKIND, IO, MODE>(c, cur.x[i], delta[i], cur.z[i], cur.part[i], row,
+                token_step<N, S, AKIND, IO, MODE, kRefill>(c, cur.x[i], delta[i], cur.z[i], cur.part[i], row, next,
                                                   TileSink<IO, TILE>{to, tpk, c.ch_io, c.ch_f32, i});
                 if constexpr (S > 1) {
                     if (i + 1 < TILE) row = row_next;
                 } else if constexpr (BCSRC == kBcStaged) {
                     row = row_next;
-                } else if constexpr (kBcScalarAhead<N, S>) {
+                } else if constexpr (kBcScalarAhead<N, S> && !kRefill) {
                     __builtin_amdgcn_sched_barrier(0);
                     row = row_next;
                 }
@@ -537,7 +578,8 @@ __device__ __forceinline__ void run_range(const SweepArgs& a, Chain<N, S, AKIND,
         else if constexpr (kBcScalarAhead<N, S>) load_bc_scalar<N>(c.bcrow, row);
         float delta = IO::cvt(dr);
         if (softplus_dt) delta = softplus(delta + c.dtb);
-        token_step<N, S, AKIND, IO, MODE>(c, xr, delta, zr, part, row, RowSink<IO>{c.orow, c.prow, c.ch_io, c.ch_f32});
+        token_step<N, S, AKIND, IO, MODE, false>(c, xr, delta, zr, part, row, nullptr,
+                                                 RowSink<IO>{c.orow, c.prow, c.ch_io, c.ch_f32});
         advance_rows(c, 1);
     }
 }
