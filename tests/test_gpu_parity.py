@@ -233,3 +233,27 @@ def test_large_batch_shallow_tile(gpu, oracle):
     for L, ra in ((100, True), (37, False)):
         cfg = synth.mixer_cfg(32, L, 4096)
         check_fwd(gpu, oracle, cfg, 1600 + L, random_a=ra, sel=sampled(16, 4096, 9))
+
+
+@pytest.mark.parametrize("Dn,split", [(192, 1), (96, 2), (48, 4), (320, 1), (160, 2)])
+def test_odd_number_of_channel_tiles(gpu, oracle, Dn, split):
+    """A workgroup covers two channel tiles; with an odd number of tiles the last workgroup's second pair of waves
+    shadows the first (same values to the same addresses).  Whole sequence and time segments, with a committed state."""
+    N = 64 if split == 4 else 16
+    for chunks in (1, 3):
+        cfg = synth.mixer_cfg(3, 75, Dn, d_state=N, io="f32", state_split=split, time_chunks=chunks)
+        check_fwd(gpu, oracle, cfg, 1700 + Dn + chunks)
+    cfg = synth.mixer_cfg(2, 40, Dn, d_state=N, io="f32", state_split=split)
+    pf, pb, inp = case(cfg, 1750 + Dn)
+    ref, h_ref, _ = oracle.bimamba_block_fwd(cfg, to_np(pf), to_np(pb), to_np(inp), want_tail=False)
+    got, h_got, _ = gpu.gpu_block_fwd(cfg, pf, pb, inp)
+    assert rel_l2(got, ref) < gpu.TOL["f32"]
+    assert rel_l2(h_got, h_ref) < 1e-5
+
+
+@pytest.mark.parametrize("batch,L", [(8, 300), (11, 150), (13, 130), (9, 520), (40, 70)])
+def test_launch_geometries_of_the_batch_sweep(gpu, oracle, batch, L):
+    """Shapes on either side of each geometry rule at d_inner 4096: two lanes per chain in one round, time segments,
+    one lane per chain from 1.5 waves per SIMD, more than one round of workgroups (no turns), sampled channels."""
+    cfg = synth.mixer_cfg(batch, L, 4096)
+    check_fwd(gpu, oracle, cfg, 1800 + batch, sel=sampled(16, 4096, batch))
