@@ -777,7 +777,7 @@ __global__ __launch_bounds__(256) void sweep_kernel(const SweepArgs a)
 
 // Stitch time segments: carry[s][b][seg] holds each segment's end state from a zero start (summary pass); replace it
 // by the state entering the segment, folding (decay product, end state) pairs in scan order:
-//   h_next = exp(A * sum_dt_seg) * h + S_seg.      One thread per (direction, batch, channel).
+//   h_next = exp(A * sum_dt_seg) * h + S_seg.
 struct CarryArgs {
     float* carry;
     const float* sumdt;
@@ -787,45 +787,41 @@ struct CarryArgs {
     int batch, nseg, Dn, P;
 };
 
+// One thread per (direction, batch, channel, state).  A thread's walk over the segments is a dependent chain, but the
+// addresses are not: the summaries of kAhead segments are requested together, then folded in order.
 template <int N, int AKIND>
 __global__ __launch_bounds__(256) void carry_kernel(const CarryArgs a)
 {
+    constexpr int kAhead = 16;
     const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const long long total = 2LL * a.batch * a.Dn;
+    const long long total = 2LL * a.batch * a.Dn * N;
     if (idx >= total) return;
-    const int ch = (int)(idx % a.Dn);
-    const int b = (int)((idx / a.Dn) % a.batch);
-    const int s = (int)(idx / ((long long)a.Dn * a.batch));
+    const int n = (int)(idx % N);
+    const int ch = (int)((idx / N) % a.Dn);
+    const int b = (int)((idx / ((long long)N * a.Dn)) % a.batch);
+    const int s = (int)(idx / ((long long)N * a.Dn * a.batch));
     const int head = ch / a.P;
-    float a2[AKIND == 0 ? N : 1];
-    if (AKIND == 0) {
+    const float a2 = a.A[s][AKIND == 0 ? (size_t)head * N + n : (size_t)head] * kLog2e;
+    float h = (s == 0 && a.h_in) ? a.h_in[((size_t)b * a.Dn + ch) * N + n] : 0.0f;
+    const size_t first_row = ((size_t)s * a.batch + b) * a.nseg * a.Dn + ch;   // segment seg: first_row + seg * Dn
+    auto row_of = [&](int i) { return first_row + (size_t)(s == 0 ? i : a.nseg - 1 - i) * a.Dn; };
+    for (int i0 = 0; i0 < a.nseg; i0 += kAhead) {
+        float end_state[kAhead], sd[kAhead];
 #pragma unroll
-        for (int n = 0; n < N; n++) a2[n] = a.A[s][(size_t)head * N + n] * kLog2e;
-    } else {
-        a2[0] = a.A[s][head] * kLog2e;
-    }
-    float h[N];
-    const float* hin = (s == 0 && a.h_in) ? a.h_in + ((size_t)b * a.Dn + ch) * N : nullptr;
+        for (int j = 0; j < kAhead; j++) {
+            const size_t row = row_of(min(i0 + j, a.nseg - 1));
+            end_state[j] = a.carry[row * N + n];
+            sd[j] = a.sumdt[row];
+        }
 #pragma unroll
-    for (int n = 0; n < N; n++) h[n] = hin ? hin[n] : 0.0f;
-    for (int i = 0; i < a.nseg; i++) {
-        const int seg = s == 0 ? i : a.nseg - 1 - i;
-        const size_t row = (((size_t)s * a.batch + b) * a.nseg + seg) * a.Dn + ch;
-        float* S = a.carry + row * N;
-        const float sd = a.sumdt[row];
-#pragma unroll
-        for (int n = 0; n < N; n++) {
-            const float end_state = S[n];
-            S[n] = h[n];
-            const float p = fast_exp2(sd * a2[AKIND == 0 ? n : 0]);
-            h[n] = fmaf(p, h[n], end_state);
+        for (int j = 0; j < kAhead; j++) {
+            if (i0 + j < a.nseg) {
+                a.carry[row_of(i0 + j) * N + n] = h;
+                h = fmaf(fast_exp2(sd[j] * a2), h, end_state[j]);
+            }
         }
     }
-    if (s == 0 && a.h_out) {
-        float* dst = a.h_out + ((size_t)b * a.Dn + ch) * N;
-#pragma unroll
-        for (int n = 0; n < N; n++) dst[n] = h[n];
-    }
+    if (s == 0 && a.h_out) a.h_out[((size_t)b * a.Dn + ch) * N + n] = h;
 }
 
 // B and C rows as the scan consumes them: fp32, [batch][L][G][B(0..N) | C(0..N)], raw values or conv + SiLU'd like x

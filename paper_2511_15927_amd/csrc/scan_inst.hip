@@ -125,7 +125,7 @@ struct Tiled {
         if (sa.nseg > 1) {
             hipLaunchKernelGGL(summary, grid, dim3(kBlock), spread_lds(summary, &fit_summary, grid), st,
                                with_turns(sa, grid, fit_summary.ask(summary, current_device())));
-            const long long threads = 2LL * ca.batch * ca.Dn;
+            const long long threads = 2LL * ca.batch * ca.Dn * BM_N;
             hipLaunchKernelGGL((carry_kernel<BM_N, AKIND>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, ca);
         }
         const unsigned lds = spread_lds(sweep, &fit_sweep, grid);
