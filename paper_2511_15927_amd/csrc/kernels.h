@@ -584,6 +584,124 @@ __device__ __forceinline__ void run_range(const SweepArgs& a, Chain<N, S, AKIND,
     }
 }
 
+// Segment summary without the recurrence (one lane per chain, scalar-register rows).  From a zero start the end state
+// of a segment is  S[n] = sum_t exp(A[n] * W_t) * Delta_t xc_t B_t[n],  W_t = the Delta of the tokens that follow t
+// in scan order.  Walking the segment from its scan-last token towards its scan-first one, W_t is a running sum and a
+// token costs two VALU per state (coefficient step, accumulate) where the recurrence costs three (decay step, input
+// product, update).  The conv of a token needs the raw x of the three tokens that precede it in scan order, which
+// this walk meets later: a token is folded in three steps after its own x arrived, once the window is complete, with
+// its Delta taken from a three-deep delay line.  On entry c is positioned at the segment's scan-first token with
+// scan-order steps and a zero state; c.xh holds the raw x of the three tokens before the segment.  On return c.h is
+// the end state and c.sum_dt the segment's total Delta.
+template <int N, int AKIND, typename IO, int TILE>
+__device__ __forceinline__ void summarise_from_the_end(Chain<N, 1, AKIND, IO>& c, int len, bool softplus_dt)
+{
+    using Tile = RawTile<IO, TILE>;
+    // reposition at the scan-last token and walk against the scan order
+    c.xrow += (long long)(len - 1) * c.xs;
+    c.dtrow += (long long)(len - 1) * c.dts;
+    c.bcrow += (long long)(len - 1) * c.bcs;
+    c.xs = -c.xs;
+    c.dts = -c.dts;
+    c.bcs = -c.bcs;
+    float xw0 = 0.0f, xw1 = 0.0f, xw2 = 0.0f, xw3 = 0.0f;   // raw x, xw0 the newest (three tokens before the one folded)
+    float d1 = 0.0f, d2 = 0.0f, d3 = 0.0f;                   // Delta, d3 the oldest (the token folded next)
+    float wsum = 0.0f;                                       // W of the token folded next
+    int folded = 0;                                          // tokens folded so far; the next one is scan index len-1-folded
+    float brow[N];
+    uniform_ro_ptr q = (uniform_ro_ptr)c.bcrow;
+#pragma unroll
+    for (int n = 0; n < N; n++) brow[n] = q[n];
+    auto push = [&](float x, float delta) {
+        xw3 = xw2; xw2 = xw1; xw1 = xw0; xw0 = x;
+        d3 = d2; d2 = d1; d1 = delta;
+    };
+    // folds the token whose x sits in xw3 and whose Delta was in d3 before the push that completed its window
+    auto fold = [&](float delta) {
+        float pre = c.cb;
+        pre = fmaf(c.w4[0], xw0, pre);
+        pre = fmaf(c.w4[1], xw1, pre);
+        pre = fmaf(c.w4[2], xw2, pre);
+        pre = fmaf(c.w4[3], xw3, pre);
+        const float u = delta * silu(pre);
+        if (AKIND == kAPerState) {
+#pragma unroll
+            for (int n = 0; n < N; n++) c.h[n] = fmaf(fast_exp2(wsum * c.a2[n]) * u, brow[n], c.h[n]);
+        } else if (AKIND == kAProgression) {
+            float cn = fast_exp2(wsum * c.a2[0]) * u;
+            const float ratio = fast_exp2(wsum * c.d2);
+#pragma unroll
+            for (int n = 0; n < N; n++) {
+                c.h[n] = fmaf(cn, brow[n], c.h[n]);
+                cn *= ratio;
+            }
+        } else {
+            const float cn = fast_exp2(wsum * c.a2[0]) * u;
+#pragma unroll
+            for (int n = 0; n < N; n++) c.h[n] = fmaf(cn, brow[n], c.h[n]);
+        }
+        wsum += delta;
+        folded++;
+        // the row of the token folded next, into the registers just read (never past the segment's first row)
+        __builtin_amdgcn_sched_barrier(0);
+        if (folded < len) c.bcrow += c.bcs;
+        uniform_ro_ptr nq = (uniform_ro_ptr)c.bcrow;
+#pragma unroll
+        for (int n = 0; n < N; n++) brow[n] = nq[n];
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto delta_of = [&](typename IO::T raw) {
+        const float v = IO::cvt(raw);
+        return softplus_dt ? softplus(v + c.dtb) : v;
+    };
+    // the first three tokens only fill the window
+    const int lead = min(3, len);
+    for (int k = 0; k < lead; k++) {
+        push(IO::cvt(*lane_elem(c.xrow, c.ch_io)), delta_of(*lane_elem(c.dtrow, c.head_io)));
+        advance_rows(c, 1);
+    }
+    int left = len - lead;   // tokens whose x is still to come; each arrival completes the window of one token
+    if (left >= TILE) {
+        Tile nxt;
+        load_tile<N, 1, AKIND, IO, kModeNoOutput, TILE>(c, 0, nxt);
+        while (true) {
+            const Tile cur = nxt;
+            const bool more = left >= 2 * TILE;
+            if (more) load_tile<N, 1, AKIND, IO, kModeNoOutput, TILE>(c, TILE, nxt);
+            float delta[TILE];
+#pragma unroll
+            for (int i = 0; i < TILE; i++) delta[i] = IO::cvt(cur.dt[i]);
+            if (softplus_dt) {
+#pragma unroll
+                for (int i = 0; i < TILE; i++) delta[i] = softplus(delta[i] + c.dtb);
+            }
+#pragma unroll
+            for (int i = 0; i < TILE; i++) {
+                const float due = d3;
+                push(IO::cvt(cur.x[i]), delta[i]);
+                fold(due);
+            }
+            left -= TILE;
+            advance_rows(c, TILE);
+            if (!more) break;
+        }
+    }
+    for (; left > 0; left--) {
+        const float due = d3;
+        push(IO::cvt(*lane_elem(c.xrow, c.ch_io)), delta_of(*lane_elem(c.dtrow, c.head_io)));
+        fold(due);
+        advance_rows(c, 1);
+    }
+    // the tokens before the segment complete the windows of its first three tokens
+#pragma unroll
+    for (int i = 0; i < 3; i++) {
+        const float due = d3;
+        push(c.xh[i], 0.0f);
+        if (lead + i >= 3 && folded < len) fold(due);   // (segments shorter than three tokens fill the window here)
+    }
+    c.sum_dt = wsum;
+}
+
 // Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own L2.  With S lanes per chain
 // a wave's row accesses cover only 1/S of a 128-byte line (bf16), so the S channel tiles that share a line are
 // given to workgroups 8 apart: same XCD, dispatched together, and the line is fetched from HBM once.  Within each
@@ -718,7 +836,8 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, c
     const bool sp = a.dt_softplus != 0;
 
     if (KIND == kSummary) {
-        run_range<N, S, AKIND, IO, kModeNoOutput, TILE>(a, c, len, sp, lds, lane);
+        if constexpr (kBcScalarAhead<N, S>) summarise_from_the_end<N, AKIND, IO, TILE>(c, len, sp);
+        else run_range<N, S, AKIND, IO, kModeNoOutput, TILE>(a, c, len, sp, lds, lane);
         float* dst = a.carry + ((((size_t)s * gridDim.z + b) * a.nseg + seg) * a.Dn + ch) * N + sub * NS;
 #pragma unroll
         for (int n = 0; n < NS; n++) dst[n] = c.h[n];

@@ -108,3 +108,25 @@ def test_recipe_A_is_an_exact_fp32_progression():
     A = synth.make_params(cfg, 1, 0)["A"].numpy()
     n = np.arange(16, dtype=np.float32)
     assert np.array_equal(A[0], np.float32(A[0, 0]) + n * np.float32(A[0, 1] - A[0, 0]))
+
+
+def test_end_state_from_a_zero_start_is_a_weighted_sum(oracle):
+    """The segment summaries are formed without the recurrence: from a zero start
+        h_end[d, n] = sum_t exp(A[d, n] * W_t) * Delta_t * xc_t[d] * B_t[n],   W_t = sum_{s > t} Delta_s,
+    accumulated from the last token backwards, which is what the recurrence unrolls to."""
+    cfg, pf, pb, inp = tiny_case(seed=21, seqlen=37, d_inner=6, d_state=8, n_heads=6, n_groups=1, a_kind=0, d_kind=0,
+                                 conv_bc=0, dt_softplus=1)
+    f64 = lambda a: np.asarray(a, dtype=np.float64)
+    _, h_ref = oracle.one_direction(cfg, pf, inp, +1)
+    L, Dn, N = cfg["seqlen"], cfg["d_inner"], cfg["d_state"]
+    for b in range(cfg["batch"]):
+        x, Bm = f64(inp["x"][b]), f64(inp["B"][b]).reshape(L, N)
+        xc = conv_silu_scan_order(x, f64(pf["conv_w"])[:Dn], f64(pf["conv_b"])[:Dn])
+        dt = F.softplus(torch.from_numpy(f64(inp["dt"][b]) + f64(pf["dt_bias"])[None, :])).numpy()
+        A = f64(pf["A"])
+        h = np.zeros((Dn, N))
+        W = np.zeros(Dn)
+        for t in range(L - 1, -1, -1):
+            h += np.exp(A * W[:, None]) * (dt[t] * xc[t])[:, None] * Bm[t][None, :]
+            W += dt[t]
+        assert rel_l2(h, f64(h_ref[b])) < 1e-12
