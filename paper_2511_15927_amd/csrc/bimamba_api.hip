@@ -66,7 +66,7 @@ long long waves_of(const bimamba_desc* d, int split)
 
 // Launch geometry of the lane-per-chain kernels, from measurements on MI355X (1024 SIMDs) with w = the number of waves
 // that one lane per chain gives (2 * batch * d_inner / 64), up to 32 states:
-//   w > 1536    one lane per chain, whole sequence: 1.5 or more waves per SIMD already.
+//   w >= 1920   one lane per chain, whole sequence: close to two waves per SIMD already.
 //   else        two lanes per chain (each holds half the states), whole sequence, when the 2w waves fill the SIMDs
 //               well in one round of resident waves: 1.8 to 2, or 2.35 to 3 per SIMD (the kernel's registers allow
 //               three at once).  Doubling the waves this way repeats the per-channel work but needs no second pass.
@@ -105,7 +105,7 @@ bool two_lanes_fit(long long w)
 }
 
 // One lane per chain needs no help from segments or lane splitting.
-bool enough_chains(const bimamba_desc* d, long long w) { return many_states(d) ? w >= kTargetWaves : 2 * w > 3 * kSimds; }
+bool enough_chains(const bimamba_desc* d, long long w) { return many_states(d) ? w >= kTargetWaves : 8 * w >= 15 * kSimds; }
 
 int pick_split(const bimamba_desc* d)
 {
