@@ -795,15 +795,26 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, c
     }
     // conv history: the K-1 raw tokens that precede the walk's first token in scan order
     {
+        // all requested together from clamped (always valid) addresses, then selected: a short call cannot afford to
+        // wait for them one after the other
         const T* xb = (const T*)da.x.p + (size_t)b * da.x.sb + ch;
+        const bool cached_tail = s == 0 && a.tail_in != nullptr && a.K > 1;
+        T from_seq[3], from_tail[3] = {0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < 3; i++) from_seq[i] = xb[(long long)min(max(tstart - step * (1 + i), 0), a.L - 1) * da.x.st];
+        if (cached_tail) {
+#pragma unroll
+            for (int i = 0; i < 3; i++)
+                from_tail[i] = ((const T*)a.tail_in)[((size_t)b * (a.K - 1) + min(max(a.K - 1 + tstart - step * (1 + i), 0), a.K - 2)) *
+                                                         a.tail_ch + ch];
+        }
 #pragma unroll
         for (int i = 0; i < 3; i++) {
             const int t = tstart - step * (1 + i);
             float v = 0.0f;
             if (i < a.K - 1) {
-                if (t >= 0 && t < a.L) v = IO::ld(xb + (long long)t * da.x.st);
-                else if (t < 0 && s == 0 && a.tail_in)
-                    v = IO::ld((const T*)a.tail_in + ((size_t)b * (a.K - 1) + (a.K - 1 + t)) * a.tail_ch + ch);
+                if (t >= 0 && t < a.L) v = IO::cvt(from_seq[i]);
+                else if (t < 0 && cached_tail) v = IO::cvt(from_tail[i]);
             }
             c.xh[i] = v;
         }
@@ -827,9 +838,21 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, c
         // this wave's own fp32 copy of its direction's B|C rows of the whole (short) call, indexed by token
         const T* bsrc = (const T*)da.Braw.p + (size_t)b * da.Braw.sb + grp * N;
         const T* csrc = (const T*)da.Craw.p + (size_t)b * da.Craw.sb + grp * N;
-        for (int idx = lane; idx < a.L * 2 * N; idx += 64) {
+        // every load is requested before the first value is used: the call is too short to wait for them one by one
+        constexpr int kPerLane = kShortCallTokens * 2 * N / 64;
+        const int count = a.L * 2 * N;
+        T raw[kPerLane];
+#pragma unroll
+        for (int j = 0; j < kPerLane; j++) {
+            if (j * 64 >= count) break;
+            const int idx = min(j * 64 + lane, count - 1);
             const int t = idx / (2 * N), col = idx % (2 * N);
-            lds[idx] = col < N ? IO::ld(bsrc + (long long)t * da.Braw.st + col) : IO::ld(csrc + (long long)t * da.Craw.st + col - N);
+            raw[j] = col < N ? bsrc[(long long)t * da.Braw.st + col] : csrc[(long long)t * da.Craw.st + col - N];
+        }
+#pragma unroll
+        for (int j = 0; j < kPerLane; j++) {
+            if (j * 64 >= count) break;
+            if (j * 64 + lane < count) lds[j * 64 + lane] = IO::cvt(raw[j]);
         }
         __builtin_amdgcn_wave_barrier();  // read back by other lanes of this wave only; LDS keeps wave order
     }
