@@ -26,15 +26,22 @@ static void prep_one(const SsdPrepPair& pa, int nchunk, int batch, hipStream_t s
     hipLaunchKernelGGL((ssd_prep_kernel<N>), dim3((unsigned)nchunk, (unsigned)pa.dir[0].G, 2u * (unsigned)batch), dim3(256), lds, st, pa);
 }
 
+template <int N, int P, bool SINGLE>
+static void scan_variant(const SsdArgs& sa, int batch, hipStream_t st)
+{
+    static std::atomic<bool> seen[kMaxDevices];
+    constexpr size_t lds = SsdLds<N, P, SINGLE>::bytes();
+    if (first_use_on_current_device(seen))
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ssd_kernel<N, P, SINGLE>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL((ssd_kernel<N, P, SINGLE>), dim3((unsigned)sa.H, 1, (unsigned)batch), dim3(4 * P + 256), lds, st, sa);
+}
+
+// Calls of a single chunk (block-diffusion steps) take the instantiation of which two workgroups fit a CU.
 template <int N, int P>
 static void scan_one(const SsdArgs& sa, int batch, hipStream_t st)
 {
-    static std::atomic<bool> seen[kMaxDevices];
-    if (first_use_on_current_device(seen))
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ssd_kernel<N, P>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)(SsdLds<N, P>::bytes()));
-    const size_t lds = SsdLds<N, P>::bytes();
-    hipLaunchKernelGGL((ssd_kernel<N, P>), dim3((unsigned)sa.H, 1, (unsigned)batch), dim3(4 * P + 256), lds, st, sa);
+    if (sa.nchunk == 1) scan_variant<N, P, true>(sa, batch, st);
+    else scan_variant<N, P, false>(sa, batch, st);
 }
 
 bool ssd_supported(int d_state, int headdim) { return (d_state == 64 || d_state == 128) && (headdim == 32 || headdim == 64); }

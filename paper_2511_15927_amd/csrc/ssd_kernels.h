@@ -179,8 +179,10 @@ struct SsdArgs {
 };
 
 // LDS of ssd_kernel: two buffers of per-chunk tiles (filled by the producer waves one chunk ahead of the consumer
-// waves) and two copies of the state in MFMA operand form.
-template <int N, int P>
+// waves) and two copies of the state in MFMA operand form.  SINGLE (calls of one chunk, i.e. block-diffusion steps):
+// one of each and one set of scan tables shared by the producer waves (they all write the same values), which brings
+// the workgroup under half a CU's LDS so that two workgroups overlap their load-compute-store chains on a CU.
+template <int N, int P, bool SINGLE = false>
 struct SsdLds {
     static constexpr int kRowC = N + kPadK, kRowT = kQ + kPadK;
     static constexpr int kC = kQ * kRowC;    // C rows of the chunk               [kQ][kRowC] bf16
@@ -190,8 +192,10 @@ struct SsdLds {
     static constexpr int kTileElems = kC + kBT + 2 * kX + kM;
     static constexpr int kHT = (N / 32) * (P / 32) * 2 * 64 * 8;   // state operand copy, bf16
     static constexpr int kProducerWaves = 4;
-    // + exp(l_i) per buffer, + per producer wave: cumulative log2 decay, Delta, end-of-chunk weight of each position
-    static constexpr size_t bytes() { return (size_t)(2 * kTileElems + 2 * kHT) * sizeof(__bf16) + (2 + 3 * kProducerWaves) * kQ * sizeof(float); }
+    static constexpr int kBufs = SINGLE ? 1 : 2;
+    static constexpr int kScanTables = SINGLE ? 1 : kProducerWaves;
+    // + exp(l_i) per buffer, + per scan table: cumulative log2 decay, Delta, end-of-chunk weight of each position
+    static constexpr size_t bytes() { return (size_t)(kBufs * kTileElems + kBufs * kHT) * sizeof(__bf16) + (kBufs + 3 * kScanTables) * kQ * sizeof(float); }
 };
 
 // LDS-only barrier: waits for this wave's LDS traffic, not for global loads that were issued ahead on purpose.
@@ -219,10 +223,12 @@ __device__ __forceinline__ float wave_inclusive_sum(float v)
 // chunk ahead they compute Delta and the cumulative decay, build the masked decayed score operand, run conv + SiLU,
 // and stage the C / B^T tiles, with the global loads of the chunk after that already in flight.  One LDS barrier per
 // chunk.  (The producers' per-head work does not shrink with the head width, so their count does not either.)
-template <int N, int P>
-__global__ __launch_bounds__(4 * P + 256) void ssd_kernel(const SsdArgs a)
+template <int N, int P, bool SINGLE = false>
+__global__ __launch_bounds__(4 * P + 256, SINGLE ? 4 : 1) void ssd_kernel(const SsdArgs a_in)
 {
-    using Lds = SsdLds<N, P>;
+    using Lds = SsdLds<N, P, SINGLE>;
+    SsdArgs a = a_in;
+    if (SINGLE) a.nchunk = 1;   // known at compile time: the chunk pipeline below folds away
     constexpr int kPB = P / 32;       // channel blocks
     constexpr int kNB = N / 32;       // state blocks
     constexpr int kHB = kNB / 2;      // state blocks owned per consumer wave
@@ -234,8 +240,8 @@ __global__ __launch_bounds__(4 * P + 256) void ssd_kernel(const SsdArgs a)
     using T = unsigned short;
     extern __shared__ __attribute__((aligned(16))) unsigned char ssd_lds[];
     __bf16* const tiles = reinterpret_cast<__bf16*>(ssd_lds);
-    __bf16* const sHT = tiles + 2 * Lds::kTileElems;
-    float* const scal = reinterpret_cast<float*>(sHT + 2 * Lds::kHT);   // [2][kQ]: exp(l_i), decay from the chunk start
+    __bf16* const sHT = tiles + Lds::kBufs * Lds::kTileElems;
+    float* const scal = reinterpret_cast<float*>(sHT + Lds::kBufs * Lds::kHT);   // [kBufs][kQ]: exp(l_i), decay from the chunk start
     auto sC = [&](int buf) { return tiles + buf * Lds::kTileElems; };
     auto sBT = [&](int buf) { return tiles + buf * Lds::kTileElems + Lds::kC; };
     auto sXc = [&](int buf) { return tiles + buf * Lds::kTileElems + Lds::kC + Lds::kBT; };
@@ -270,7 +276,8 @@ __global__ __launch_bounds__(4 * P + 256) void ssd_kernel(const SsdArgs a)
         const int ptid = tid - kConsThreads;
         const int pwave = wave - kConsThreads / 64;
         const int cp = ptid % kCP, tg = ptid / kCP;   // conv role: channels 2cp, 2cp+1; positions kPos*tg .. of each chunk
-        float* const pw_l2 = scal + 2 * kQ + pwave * 3 * kQ;   // wave-private, written and read by this wave only
+        // wave-private, written and read by this wave only (SINGLE: one copy, every wave writes the same values)
+        float* const pw_l2 = scal + Lds::kBufs * kQ + (SINGLE ? 0 : pwave) * 3 * kQ;
         float* const pw_dl = pw_l2 + kQ;
         float* const pw_wgt = pw_dl + kQ;
         const float a2 = a.A[head] * kLog2e;
@@ -341,7 +348,7 @@ __global__ __launch_bounds__(4 * P + 256) void ssd_kernel(const SsdArgs a)
             // Delta, inclusive cumulative log2-decay and end-of-chunk weight of position `lane` (every producer wave
             // computes them for itself; the first one publishes exp(l) for the consumers)
             float dl = IoBF16::cvt(dtraw);
-            issue_dt(cn);
+            if (!SINGLE) issue_dt(cn);
             if (a.dt_softplus) dl = softplus(dl + dtb);
             if (c * kQ + lane > last) dl = 0.0f;
             const float l2 = wave_inclusive_sum(dl * a2);
@@ -368,7 +375,7 @@ __global__ __launch_bounds__(4 * P + 256) void ssd_kernel(const SsdArgs a)
 #pragma unroll
             for (int m = 0; m < kHS; m++) { sv[m][0] = gt[m].x; sv[m][1] = gt[m].y; sv[m][2] = gt[m].z; sv[m][3] = gt[m].w; }
             asm volatile("" ::: "memory");   // the re-issue below must not move above the reads of gt
-            issue_score(cn);
+            if (!SINGLE) issue_score(cn);
 #pragma unroll
             for (int m = 0; m < kHS; m++) {
                 const int hs = m * kProdThreads + ptid;
@@ -406,7 +413,7 @@ __global__ __launch_bounds__(4 * P + 256) void ssd_kernel(const SsdArgs a)
                 xr[1][q] = __uint_as_float(xraw[q] & 0xffff0000u);
             }
             asm volatile("" ::: "memory");
-            issue_x(cn);
+            if (!SINGLE) issue_x(cn);
             if (edge_chunk(c)) {
 #pragma unroll
                 for (int q = 0; q < kPos + 3; q++) {
@@ -455,7 +462,7 @@ __global__ __launch_bounds__(4 * P + 256) void ssd_kernel(const SsdArgs a)
                 *reinterpret_cast<bf16x8*>(&sBT(buf)[b_dst[i]]) = btile[i];
             }
             asm volatile("" ::: "memory");
-            issue_tiles(cn);
+            if (!SINGLE) issue_tiles(cn);
             __builtin_amdgcn_wave_barrier();   // the next chunk's scan results overwrite pw_* only after these reads
         };
         issue_dt(0);
