@@ -87,13 +87,15 @@ __global__ __launch_bounds__(256) void ssd_prep_kernel(const SsdPrepPair both)
         float xr[kLen + 3];
 #pragma unroll
         for (int q = 0; q < kLen + 3; q++) xr[q] = (tau0 + q >= 0 && tau0 + q <= last) ? IoBF16::cvt(raw[q]) : 0.0f;
-        if (c == 0 && seg == 0 && a.dir > 0 && a.tail_in && a.conv_bc) {
+        if (c == 0 && seg == 0 && a.dir > 0 && a.tail_in && a.conv_bc && a.K > 1) {
+            // requested together from clamped rows (a tap beyond the conv width has a zero weight)
+            T cached[3];
 #pragma unroll
-            for (int q = 0; q < 3; q++) {
-                const int back = 3 - q;   // how many tokens before the block
-                if (back <= a.K - 1)
-                    xr[q] = IoBF16::ld((const T*)a.tail_in + ((size_t)b * (a.K - 1) + (a.K - 1 - back)) * a.tail_ch + row);
-            }
+            for (int q = 0; q < 3; q++)   // 3 - q tokens before the block
+                cached[q] = ((const T*)a.tail_in)[((size_t)b * (a.K - 1) + max(a.K - 1 - (3 - q), 0)) * a.tail_ch + row];
+#pragma unroll
+            for (int q = 0; q < 3; q++)
+                if (3 - q <= a.K - 1) xr[q] = IoBF16::cvt(cached[q]);
         }
         float(*dstm)[N + 1] = which ? sC : sB;
 #pragma unroll
@@ -420,14 +422,20 @@ __global__ __launch_bounds__(4 * P + 256, SINGLE ? 4 : 1) void ssd_kernel(const 
                     const int tau = c * kQ + kPos * tg + q - 3;
                     if (tau < 0 || tau > last) xr[0][q] = xr[1][q] = 0.0f;
                 }
-                if (c == 0 && a.dir > 0 && a.tail_in && tg == 0) {
+                if (c == 0 && a.dir > 0 && a.tail_in && tg == 0 && a.K > 1) {
+                    // requested together from clamped rows (a tap beyond the conv width has a zero weight)
+                    T cached[3][2];
+#pragma unroll
+                    for (int q = 0; q < 3; q++) {   // 3 - q tokens before the block
+                        const T* tp = (const T*)a.tail_in + ((size_t)b * (a.K - 1) + max(a.K - 1 - (3 - q), 0)) * a.tail_ch + ch0 + 2 * cp;
+                        cached[q][0] = tp[0];
+                        cached[q][1] = tp[1];
+                    }
 #pragma unroll
                     for (int q = 0; q < 3; q++) {
-                        const int back = 3 - q;                       // how many tokens before the block
-                        if (back <= a.K - 1) {
-                            const T* tp = (const T*)a.tail_in + ((size_t)b * (a.K - 1) + (a.K - 1 - back)) * a.tail_ch + ch0 + 2 * cp;
-                            xr[0][q] = IoBF16::ld(tp);
-                            xr[1][q] = IoBF16::ld(tp + 1);
+                        if (3 - q <= a.K - 1) {
+                            xr[0][q] = IoBF16::cvt(cached[q][0]);
+                            xr[1][q] = IoBF16::cvt(cached[q][1]);
                         }
                     }
                 }
