@@ -26,22 +26,41 @@ static void prep_one(const SsdPrepPair& pa, int nchunk, int batch, hipStream_t s
     hipLaunchKernelGGL((ssd_prep_kernel<N>), dim3((unsigned)nchunk, (unsigned)pa.dir[0].G, 2u * (unsigned)batch), dim3(256), lds, st, pa);
 }
 
-template <int N, int P, bool SINGLE>
+static int cu_count()
+{
+    static std::atomic<int> cached[kMaxDevices];
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) {
+        cus = cached[dev].load(std::memory_order_relaxed);
+        if (cus == 0) {
+            if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+            cached[dev].store(cus, std::memory_order_relaxed);
+        }
+    }
+    return cus;
+}
+
+template <int N, int P, bool SINGLE, int GROUPS>
 static void scan_variant(const SsdArgs& sa, int batch, hipStream_t st)
 {
     static std::atomic<bool> seen[kMaxDevices];
     constexpr size_t lds = SsdLds<N, P, SINGLE>::bytes();
+    auto kernel = ssd_kernel<N, P, SINGLE, GROUPS>;
     if (first_use_on_current_device(seen))
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ssd_kernel<N, P, SINGLE>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL((ssd_kernel<N, P, SINGLE>), dim3((unsigned)sa.H, 1, (unsigned)batch), dim3(4 * P + 256), lds, st, sa);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)sa.H, 1, (unsigned)batch), dim3(4 * P + 256 * GROUPS), lds, st, sa);
 }
 
-// Calls of a single chunk (block-diffusion steps) take the instantiation of which two workgroups fit a CU.
+// Calls of a single chunk (block-diffusion steps) take the instantiation of which two workgroups fit a CU.  Long calls
+// that leave at least half of the CUs empty (batch 1 or 2) split the producers into two groups, which shortens the
+// per-chunk chain of each workgroup (-4 to -9 %); with the chip full the extra waves only compete for issue slots
+// (+4 to +7 %), so those keep one group.
 template <int N, int P>
 static void scan_one(const SsdArgs& sa, int batch, hipStream_t st)
 {
-    if (sa.nchunk == 1) scan_variant<N, P, true>(sa, batch, st);
-    else scan_variant<N, P, false>(sa, batch, st);
+    if (sa.nchunk == 1) scan_variant<N, P, true, 1>(sa, batch, st);
+    else if (2LL * sa.H * batch <= cu_count()) scan_variant<N, P, false, 2>(sa, batch, st);
+    else scan_variant<N, P, false, 1>(sa, batch, st);
 }
 
 bool ssd_supported(int d_state, int headdim) { return (d_state == 64 || d_state == 128) && (headdim == 32 || headdim == 64); }

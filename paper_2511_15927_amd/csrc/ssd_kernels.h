@@ -225,9 +225,14 @@ __device__ __forceinline__ float wave_inclusive_sum(float v)
 // chunk ahead they compute Delta and the cumulative decay, build the masked decayed score operand, run conv + SiLU,
 // and stage the C / B^T tiles, with the global loads of the chunk after that already in flight.  One LDS barrier per
 // chunk.  (The producers' per-head work does not shrink with the head width, so their count does not either.)
-template <int N, int P, bool SINGLE = false>
-__global__ __launch_bounds__(4 * P + 256, SINGLE ? 4 : 1) void ssd_kernel(const SsdArgs a_in)
+// Block: 4*P + 256*PG threads.
+// PG = 2 splits the producers into two groups of four waves: one builds the score operand and stages the tiles, the
+// other runs conv + SiLU (both run the short scan for themselves).  A producer wave's chain of dependent stages per
+// chunk is then about half as long, which is what sets the chunk period of long calls; the CU holds twelve waves.
+template <int N, int P, bool SINGLE = false, int PG = 1>
+__global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(const SsdArgs a_in)
 {
+    static_assert(PG == 1 || (PG == 2 && !SINGLE), "one or two producer groups; the single-chunk form keeps one");
     using Lds = SsdLds<N, P, SINGLE>;
     SsdArgs a = a_in;
     if (SINGLE) a.nchunk = 1;   // known at compile time: the chunk pipeline below folds away
@@ -275,8 +280,10 @@ __global__ __launch_bounds__(4 * P + 256, SINGLE ? 4 : 1) void ssd_kernel(const 
         // ------------------------------------------------------------------ producers
         constexpr int kCP = P / 2;                 // channel pairs of the head
         constexpr int kPos = kQ * kCP / kProdThreads;   // chunk positions per thread in the conv role (8 or 4)
-        const int ptid = tid - kConsThreads;
-        const int pwave = wave - kConsThreads / 64;
+        const int ptid = (tid - kConsThreads) % kProdThreads;    // index within the wave's group
+        const int pwave = (wave - kConsThreads / 64) % 4;
+        const int group = (wave - kConsThreads / 64) / 4;
+        const bool do_score = PG == 1 || group == 0, do_conv = PG == 1 || group == 1;
         const int cp = ptid % kCP, tg = ptid / kCP;   // conv role: channels 2cp, 2cp+1; positions kPos*tg .. of each chunk
         // wave-private, written and read by this wave only (SINGLE: one copy, every wave writes the same values)
         float* const pw_l2 = scal + Lds::kBufs * kQ + (SINGLE ? 0 : pwave) * 3 * kQ;
@@ -362,121 +369,132 @@ __global__ __launch_bounds__(4 * P + 256, SINGLE ? 4 : 1) void ssd_kernel(const 
             const float l2_first = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(l2), 0));
             const float l2_mid = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(l2), kQ / 2 - 1));
             const bool separable = l2_first - l2_end <= 100.0f;
-            if (separable) {
-                pw_l2[lane] = fast_exp2(l2 - l2_mid);          // e_i
-                pw_dl[lane] = fast_exp2(l2_mid - l2) * dl;     // f_j Delta_j
-            } else {
-                pw_l2[lane] = l2;
-                pw_dl[lane] = dl;
-            }
-            pw_wgt[lane] = fast_exp2(l2_end - l2) * dl;
-            if (pwave == 0) scal[buf * kQ + lane] = fast_exp2(l2);
-            __builtin_amdgcn_wave_barrier();
-            // masked score operand: (B_j . C_i) exp(l_i - l_j) Delta_j for j <= i, else 0
-            float sv[kHS][4];
-#pragma unroll
-            for (int m = 0; m < kHS; m++) { sv[m][0] = gt[m].x; sv[m][1] = gt[m].y; sv[m][2] = gt[m].z; sv[m][3] = gt[m].w; }
-            asm volatile("" ::: "memory");   // the re-issue below must not move above the reads of gt
-            if (!SINGLE) issue_score(cn);
-#pragma unroll
-            for (int m = 0; m < kHS; m++) {
-                const int hs = m * kProdThreads + ptid;
-                const int bp = hs / 256, kb = (hs / 128) % 2, sl = (hs / 2) % 64, hi = hs % 2;
-                const int iblk = bp > 0, jblk = bp > 1;
-                const int i = iblk * 32 + sl % 32;
-                const int jb = jblk * 32 + 16 * kb + 8 * hi + 4 * (sl / 32);
-                const bool diagonal = iblk == jblk;    // only the diagonal blocks hold elements with j > i
-                const float l2i = pw_l2[i];
-                const float4 da = *reinterpret_cast<const float4*>(&pw_dl[jb]);
-                const float dj[4] = {da.x, da.y, da.z, da.w};
-                bf16x4 v;
+            // (with two groups, wave i of each group shares slot i of the tables and writes only what its role reads)
+            if (do_score) {
                 if (separable) {
-#pragma unroll
-                    for (int e = 0; e < 4; e++) {
-                        const float val = sv[m][e] * l2i * dj[e];
-                        v[e] = (__bf16)((diagonal && jb + e > i) ? 0.0f : val);
-                    }
+                    pw_l2[lane] = fast_exp2(l2 - l2_mid);          // e_i
+                    pw_dl[lane] = fast_exp2(l2_mid - l2) * dl;     // f_j Delta_j
                 } else {
-                    const float4 la = *reinterpret_cast<const float4*>(&pw_l2[jb]);
-                    const float lj[4] = {la.x, la.y, la.z, la.w};
-#pragma unroll
-                    for (int e = 0; e < 4; e++) {
-                        const float val = sv[m][e] * fast_exp2(l2i - lj[e]) * dj[e];
-                        v[e] = (__bf16)((diagonal && jb + e > i) ? 0.0f : val);
-                    }
+                    pw_l2[lane] = l2;
+                    pw_dl[lane] = dl;
                 }
-                *reinterpret_cast<bf16x4*>(&sM(buf)[(((iblk * 2 + jblk) * 2 + kb) * 64 + sl) * 8 + 4 * hi]) = v;
+                if (pwave == 0) scal[buf * kQ + lane] = fast_exp2(l2);
             }
-            // conv + SiLU of two channels at kPos positions
-            float xr[2][kPos + 3];
+            if (do_conv) pw_wgt[lane] = fast_exp2(l2_end - l2) * dl;
+            __builtin_amdgcn_wave_barrier();
+            if (do_score) {
+                // masked score operand: (B_j . C_i) exp(l_i - l_j) Delta_j for j <= i, else 0
+                float sv[kHS][4];
 #pragma unroll
-            for (int q = 0; q < kPos + 3; q++) {
-                xr[0][q] = __uint_as_float(xraw[q] << 16);
-                xr[1][q] = __uint_as_float(xraw[q] & 0xffff0000u);
+                for (int m = 0; m < kHS; m++) { sv[m][0] = gt[m].x; sv[m][1] = gt[m].y; sv[m][2] = gt[m].z; sv[m][3] = gt[m].w; }
+                asm volatile("" ::: "memory");   // the re-issue below must not move above the reads of gt
+                if (!SINGLE) issue_score(cn);
+#pragma unroll
+                for (int m = 0; m < kHS; m++) {
+                    const int hs = m * kProdThreads + ptid;
+                    const int bp = hs / 256, kb = (hs / 128) % 2, sl = (hs / 2) % 64, hi = hs % 2;
+                    const int iblk = bp > 0, jblk = bp > 1;
+                    const int i = iblk * 32 + sl % 32;
+                    const int jb = jblk * 32 + 16 * kb + 8 * hi + 4 * (sl / 32);
+                    const bool diagonal = iblk == jblk;    // only the diagonal blocks hold elements with j > i
+                    const float l2i = pw_l2[i];
+                    const float4 da = *reinterpret_cast<const float4*>(&pw_dl[jb]);
+                    const float dj[4] = {da.x, da.y, da.z, da.w};
+                    bf16x4 v;
+                    if (separable) {
+#pragma unroll
+                        for (int e = 0; e < 4; e++) {
+                            const float val = sv[m][e] * l2i * dj[e];
+                            v[e] = (__bf16)((diagonal && jb + e > i) ? 0.0f : val);
+                        }
+                    } else {
+                        const float4 la = *reinterpret_cast<const float4*>(&pw_l2[jb]);
+                        const float lj[4] = {la.x, la.y, la.z, la.w};
+#pragma unroll
+                        for (int e = 0; e < 4; e++) {
+                            const float val = sv[m][e] * fast_exp2(l2i - lj[e]) * dj[e];
+                            v[e] = (__bf16)((diagonal && jb + e > i) ? 0.0f : val);
+                        }
+                    }
+                    *reinterpret_cast<bf16x4*>(&sM(buf)[(((iblk * 2 + jblk) * 2 + kb) * 64 + sl) * 8 + 4 * hi]) = v;
+                }
             }
-            asm volatile("" ::: "memory");
-            if (!SINGLE) issue_x(cn);
-            if (edge_chunk(c)) {
+            if (do_conv) {
+                // conv + SiLU of two channels at kPos positions
+                float xr[2][kPos + 3];
 #pragma unroll
                 for (int q = 0; q < kPos + 3; q++) {
-                    const int tau = c * kQ + kPos * tg + q - 3;
-                    if (tau < 0 || tau > last) xr[0][q] = xr[1][q] = 0.0f;
+                    xr[0][q] = __uint_as_float(xraw[q] << 16);
+                    xr[1][q] = __uint_as_float(xraw[q] & 0xffff0000u);
                 }
-                if (c == 0 && a.dir > 0 && a.tail_in && tg == 0 && a.K > 1) {
-                    // requested together from clamped rows (a tap beyond the conv width has a zero weight)
-                    T cached[3][2];
+                asm volatile("" ::: "memory");
+                if (!SINGLE) issue_x(cn);
+                if (edge_chunk(c)) {
 #pragma unroll
-                    for (int q = 0; q < 3; q++) {   // 3 - q tokens before the block
-                        const T* tp = (const T*)a.tail_in + ((size_t)b * (a.K - 1) + max(a.K - 1 - (3 - q), 0)) * a.tail_ch + ch0 + 2 * cp;
-                        cached[q][0] = tp[0];
-                        cached[q][1] = tp[1];
+                    for (int q = 0; q < kPos + 3; q++) {
+                        const int tau = c * kQ + kPos * tg + q - 3;
+                        if (tau < 0 || tau > last) xr[0][q] = xr[1][q] = 0.0f;
                     }
+                    if (c == 0 && a.dir > 0 && a.tail_in && tg == 0 && a.K > 1) {
+                        // requested together from clamped rows (a tap beyond the conv width has a zero weight)
+                        T cached[3][2];
 #pragma unroll
-                    for (int q = 0; q < 3; q++) {
-                        if (3 - q <= a.K - 1) {
-                            xr[0][q] = IoBF16::cvt(cached[q][0]);
-                            xr[1][q] = IoBF16::cvt(cached[q][1]);
+                        for (int q = 0; q < 3; q++) {   // 3 - q tokens before the block
+                            const T* tp = (const T*)a.tail_in + ((size_t)b * (a.K - 1) + max(a.K - 1 - (3 - q), 0)) * a.tail_ch + ch0 + 2 * cp;
+                            cached[q][0] = tp[0];
+                            cached[q][1] = tp[1];
+                        }
+#pragma unroll
+                        for (int q = 0; q < 3; q++) {
+                            if (3 - q <= a.K - 1) {
+                                xr[0][q] = IoBF16::cvt(cached[q][0]);
+                                xr[1][q] = IoBF16::cvt(cached[q][1]);
+                            }
                         }
                     }
                 }
-            }
-            float wq[kPos];
+                float wq[kPos];
 #pragma unroll
-            for (int q = 0; q < kPos; q += 4) {
-                const float4 w = *reinterpret_cast<const float4*>(&pw_wgt[kPos * tg + q]);
-                wq[q] = w.x; wq[q + 1] = w.y; wq[q + 2] = w.z; wq[q + 3] = w.w;
-            }
-#pragma unroll
-            for (int h2 = 0; h2 < 2; h2++) {
-                typedef __attribute__((__vector_size__(kPos * sizeof(__bf16)))) __bf16 bf16run;
-                bf16run vx, vw;
-#pragma unroll
-                for (int q = 0; q < kPos; q++) {
-                    float pre = cbias[h2];
-                    pre = fmaf(w4[h2][0], xr[h2][q], pre);
-                    pre = fmaf(w4[h2][1], xr[h2][q + 1], pre);
-                    pre = fmaf(w4[h2][2], xr[h2][q + 2], pre);
-                    pre = fmaf(w4[h2][3], xr[h2][q + 3], pre);
-                    const float xc = silu(pre);
-                    vx[q] = (__bf16)xc;
-                    vw[q] = (__bf16)(xc * wq[q]);
+                for (int q = 0; q < kPos; q += 4) {
+                    const float4 w = *reinterpret_cast<const float4*>(&pw_wgt[kPos * tg + q]);
+                    wq[q] = w.x; wq[q + 1] = w.y; wq[q + 2] = w.z; wq[q + 3] = w.w;
                 }
-                *reinterpret_cast<bf16run*>(&sXc(buf)[(2 * cp + h2) * kRowT + kPos * tg]) = vx;
-                *reinterpret_cast<bf16run*>(&sXw(buf)[(2 * cp + h2) * kRowT + kPos * tg]) = vw;
-            }
 #pragma unroll
-            for (int i = 0; i < kCopy; i++) {
-                *reinterpret_cast<bf16x8*>(&sC(buf)[c_dst[i]]) = ctile[i];
-                *reinterpret_cast<bf16x8*>(&sBT(buf)[b_dst[i]]) = btile[i];
+                for (int h2 = 0; h2 < 2; h2++) {
+                    typedef __attribute__((__vector_size__(kPos * sizeof(__bf16)))) __bf16 bf16run;
+                    bf16run vx, vw;
+#pragma unroll
+                    for (int q = 0; q < kPos; q++) {
+                        float pre = cbias[h2];
+                        pre = fmaf(w4[h2][0], xr[h2][q], pre);
+                        pre = fmaf(w4[h2][1], xr[h2][q + 1], pre);
+                        pre = fmaf(w4[h2][2], xr[h2][q + 2], pre);
+                        pre = fmaf(w4[h2][3], xr[h2][q + 3], pre);
+                        const float xc = silu(pre);
+                        vx[q] = (__bf16)xc;
+                        vw[q] = (__bf16)(xc * wq[q]);
+                    }
+                    *reinterpret_cast<bf16run*>(&sXc(buf)[(2 * cp + h2) * kRowT + kPos * tg]) = vx;
+                    *reinterpret_cast<bf16run*>(&sXw(buf)[(2 * cp + h2) * kRowT + kPos * tg]) = vw;
+                }
             }
-            asm volatile("" ::: "memory");
-            if (!SINGLE) issue_tiles(cn);
+            if (do_score) {
+#pragma unroll
+                for (int i = 0; i < kCopy; i++) {
+                    *reinterpret_cast<bf16x8*>(&sC(buf)[c_dst[i]]) = ctile[i];
+                    *reinterpret_cast<bf16x8*>(&sBT(buf)[b_dst[i]]) = btile[i];
+                }
+                asm volatile("" ::: "memory");
+                if (!SINGLE) issue_tiles(cn);
+            }
             __builtin_amdgcn_wave_barrier();   // the next chunk's scan results overwrite pw_* only after these reads
         };
         issue_dt(0);
-        issue_score(0);
-        issue_x(0);
-        issue_tiles(0);
+        if (do_score) {
+            issue_score(0);
+            issue_tiles(0);
+        }
+        if (do_conv) issue_x(0);
         finish(0, 0, min(1, a.nchunk - 1));
         lds_barrier();
         for (int c = 0; c < a.nchunk; c++) {
