@@ -159,8 +159,10 @@ int bimamba_block_fwd(const bimamba_desc* desc, const bimamba_params* pf, const 
 /* Bytes of device scratch the two calls above need for this descriptor (0 on an invalid descriptor).  Pure host code. */
 size_t bimamba_workspace_bytes(const bimamba_desc* desc, int block_variant);
 
-/* Number of time segments the library would use for this descriptor (>= 1; 1 on the chunked matrix-core path;
- * 0 on an invalid descriptor).  Pure host code. */
+/* Number of pieces the library would cut the time axis into for this descriptor, each piece scanned by its own
+ * workgroups and joined through a carry pass (>= 1; 0 on an invalid descriptor): the time segments of the
+ * lane-per-chain kernels, or the time parts of the chunked matrix-core kernels, which are 1 unless a call has so
+ * few (batch, head) pairs that they would leave half of the chip empty.  Pure host code. */
 int bimamba_time_chunks(const bimamba_desc* desc);
 
 /* Benchmark diagnostics: arm a one-shot probe on the calling host thread.  The next bimamba_fwd or

@@ -144,7 +144,8 @@ struct Plan {
     bool two_bc;  // the two directions consume different prepared B|C buffers
     bool ssd;     // Mamba-2 parameterisation on the chunked matrix-core kernels
     int ssd_chunks;
-    size_t off_bc[2], off_partial, off_carry, off_sumdt, off_crows[2], off_bt[2], off_score[2], total;
+    int ssd_parts, ssd_part_chunks;  // time parts of the matrix-core path (1: every (batch, head) item is one workgroup)
+    size_t off_bc[2], off_partial, off_carry, off_sumdt, off_crows[2], off_bt[2], off_score[2], off_pstate[2], off_pdecay[2], total;
 };
 
 // The chunked matrix-core path covers bf16 I/O with one decay rate per head, d_state 64 or 128 and heads of 32 or
@@ -181,6 +182,21 @@ Plan make_plan(const bimamba_desc* d, bool inputs_shared)
         off += align_up((size_t)2 * d->batch * p.nseg * d->d_inner * sizeof(float), 256);
     }
     p.ssd_chunks = (d->seqlen + kQ - 1) / kQ;
+    // Time parts: a call whose (batch, head) items would leave at least half of the 256 CUs empty deals each item's
+    // chunks to several workgroups (at least 8 chunks each, at most 16 parts); a first, cheaper pass then finds the
+    // state entering each part.
+    p.ssd_parts = 1;
+    p.ssd_part_chunks = p.ssd_chunks;
+    if (p.ssd) {
+        const long long items = (long long)d->n_heads * d->batch;
+        long long parts = items > 0 ? 256 / items : 1;
+        if (parts > p.ssd_chunks / 8) parts = p.ssd_chunks / 8;
+        if (parts > 16) parts = 16;
+        if (parts >= 2) {
+            p.ssd_part_chunks = (int)((p.ssd_chunks + parts - 1) / parts);
+            p.ssd_parts = (p.ssd_chunks + p.ssd_part_chunks - 1) / p.ssd_part_chunks;
+        }
+    }
     if (p.ssd) {
         const size_t rows = align_up((size_t)d->batch * p.ssd_chunks * kQ * d->n_groups * d->d_state * sizeof(__bf16), 256);
         const size_t score = align_up((size_t)d->batch * p.ssd_chunks * d->n_groups * kScoreOp * sizeof(float), 256);
@@ -188,6 +204,14 @@ Plan make_plan(const bimamba_desc* d, bool inputs_shared)
             p.off_crows[s] = off; off += rows;
             p.off_bt[s] = off; off += rows;
             p.off_score[s] = off; off += score;
+        }
+        for (int s = 0; s < 2; s++) {
+            p.off_pstate[s] = p.off_pdecay[s] = off;
+            if (p.ssd_parts > 1) {
+                off += align_up((size_t)p.ssd_parts * d->batch * d->d_inner * d->d_state * sizeof(float), 256);
+                p.off_pdecay[s] = off;
+                off += align_up((size_t)p.ssd_parts * d->batch * d->n_heads * sizeof(float), 256);
+            }
         }
     }
     p.total = off;
@@ -348,6 +372,9 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
             }
             launch_ssd_prep(d->d_state, pp, plan.ssd_chunks, d->batch, st);
             if (probe_start) (void)hipEventRecord(probe_start, st);
+            // pass 0 (time parts only): each part's end state from a zero start, then the states entering the parts;
+            // pass 1: the outputs
+            for (int pass = plan.ssd_parts > 1 ? 0 : 1; pass < 2; pass++) {
             for (int s = 1; s >= 0; s--) {
                 const bimamba_inputs* in = s == 0 ? in_f : in_b;
                 const bimamba_params* p = s == 0 ? pf : pb;
@@ -364,12 +391,27 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
                 sa.tail_in = (s == 0 && block_variant) ? tail_in : nullptr;
                 sa.L = d->seqlen; sa.Dn = d->d_inner; sa.H = d->n_heads; sa.HG = d->n_heads / d->n_groups;
                 sa.G = d->n_groups; sa.K = d->d_conv; sa.tail_ch = tail_ch; sa.nchunk = plan.ssd_chunks;
+                sa.parts = plan.ssd_parts; sa.part_chunks = plan.ssd_part_chunks;
+                sa.part_state = reinterpret_cast<float*>(ws + plan.off_pstate[s]);
+                sa.part_decay = reinterpret_cast<float*>(ws + plan.off_pdecay[s]);
                 sa.dir = s == 0 ? 1 : -1;
-                sa.mode = separate ? kSsdFinalOnly
+                sa.mode = pass == 0 ? kSsdStateOnly : separate ? kSsdFinalOnly
                                    : s == 1 ? (raw ? kSsdPartialRaw : kSsdPartial) : (raw ? kSsdFinalAddRaw : kSsdFinalAdd);
                 sa.out_ch_off = separate ? s * d->d_inner : 0;
                 sa.dt_softplus = d->dt_softplus; sa.d_per_head = d->d_kind == BIMAMBA_D_PER_HEAD;
                 launch_ssd_scan(d->d_state, d->d_inner / d->n_heads, sa, d->batch, st);
+            }
+            if (pass == 0) {
+                SsdCarryArgs ca{};
+                for (int s = 0; s < 2; s++) {
+                    ca.part_state[s] = reinterpret_cast<float*>(ws + plan.off_pstate[s]);
+                    ca.part_decay[s] = reinterpret_cast<const float*>(ws + plan.off_pdecay[s]);
+                }
+                ca.h_in = block_variant ? h_in : nullptr;
+                ca.batch = d->batch; ca.Dn = d->d_inner; ca.P = d->d_inner / d->n_heads; ca.H = d->n_heads;
+                ca.parts = plan.ssd_parts;
+                launch_ssd_carry(d->d_state, ca, st);
+            }
             }
             if (probe_stop) (void)hipEventRecord(probe_stop, st);
         } else {
@@ -461,7 +503,7 @@ int bimamba_time_chunks(const bimamba_desc* desc)
 {
     if (check_desc(desc)) return 0;
     const Plan p = make_plan(desc, true);
-    return p.ssd ? 1 : p.nseg;
+    return p.ssd ? p.ssd_parts : p.nseg;
 }
 
 void bimamba_profile_next_call(void* ev_start, void* ev_stop)

@@ -40,15 +40,17 @@ static int cu_count()
     return cus;
 }
 
-template <int N, int P, bool SINGLE, int GROUPS>
+template <int N, int P, bool SINGLE, int GROUPS, bool PARTS>
 static void scan_variant(const SsdArgs& sa, int batch, hipStream_t st)
 {
     static std::atomic<bool> seen[kMaxDevices];
     constexpr size_t lds = SsdLds<N, P, SINGLE>::bytes();
-    auto kernel = ssd_kernel<N, P, SINGLE, GROUPS>;
+    auto kernel = ssd_kernel<N, P, SINGLE, GROUPS, PARTS>;
     if (first_use_on_current_device(seen))
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL(kernel, dim3((unsigned)sa.H, 1, (unsigned)batch), dim3(4 * P + 256 * GROUPS), lds, st, sa);
+    // blockIdx.y is the time part; the state-only pass has nothing to do for the part scanned last
+    const unsigned parts = !PARTS ? 1u : (unsigned)(sa.mode == kSsdStateOnly ? sa.parts - 1 : sa.parts);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)sa.H, parts, (unsigned)batch), dim3(4 * P + 256 * GROUPS), lds, st, sa);
 }
 
 // Calls of a single chunk (block-diffusion steps) take the instantiation of which two workgroups fit a CU.  Long calls
@@ -58,9 +60,10 @@ static void scan_variant(const SsdArgs& sa, int batch, hipStream_t st)
 template <int N, int P>
 static void scan_one(const SsdArgs& sa, int batch, hipStream_t st)
 {
-    if (sa.nchunk == 1) scan_variant<N, P, true, 1>(sa, batch, st);
-    else if (2LL * sa.H * batch <= cu_count()) scan_variant<N, P, false, 2>(sa, batch, st);
-    else scan_variant<N, P, false, 1>(sa, batch, st);
+    if (sa.nchunk == 1) scan_variant<N, P, true, 1, false>(sa, batch, st);
+    else if (sa.parts > 1) scan_variant<N, P, false, 1, true>(sa, batch, st);
+    else if (2LL * sa.H * batch <= cu_count()) scan_variant<N, P, false, 2, false>(sa, batch, st);
+    else scan_variant<N, P, false, 1, false>(sa, batch, st);
 }
 
 bool ssd_supported(int d_state, int headdim) { return (d_state == 64 || d_state == 128) && (headdim == 32 || headdim == 64); }
@@ -69,6 +72,14 @@ void launch_ssd_prep(int d_state, const SsdPrepPair& pa, int nchunk, int batch, 
 {
     if (d_state == 128) prep_one<128>(pa, nchunk, batch, st);
     else prep_one<64>(pa, nchunk, batch, st);
+}
+
+void launch_ssd_carry(int d_state, const SsdCarryArgs& ca, hipStream_t st)
+{
+    const long long threads = 2LL * ca.batch * ca.Dn * d_state / 4;
+    const dim3 grid((unsigned)((threads + 255) / 256));
+    if (d_state == 128) hipLaunchKernelGGL(ssd_carry_kernel<128>, grid, dim3(256), 0, st, ca);
+    else hipLaunchKernelGGL(ssd_carry_kernel<64>, grid, dim3(256), 0, st, ca);
 }
 
 void launch_ssd_scan(int d_state, int headdim, const SsdArgs& sa, int batch, hipStream_t st)

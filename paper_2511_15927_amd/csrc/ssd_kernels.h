@@ -162,7 +162,9 @@ __global__ __launch_bounds__(256) void ssd_prep_kernel(const SsdPrepPair both)
     }
 }
 
-enum { kSsdFinalOnly = 0, kSsdPartial = 1, kSsdPartialRaw = 2, kSsdFinalAdd = 3, kSsdFinalAddRaw = 4 };
+// Output modes of ssd_kernel.  kSsdStateOnly writes no output: it runs a time part from a zero state and leaves the
+// part's end state and total decay for ssd_carry_kernel (see the time parts below).
+enum { kSsdFinalOnly = 0, kSsdPartial = 1, kSsdPartialRaw = 2, kSsdFinalAdd = 3, kSsdFinalAddRaw = 4, kSsdStateOnly = 5 };
 
 struct SsdArgs {
     TensorArg x, z, dt;
@@ -178,7 +180,44 @@ struct SsdArgs {
     const void* tail_in;  // bf16 [batch][K-1][tail_ch] or null (causal direction only)
     int L, Dn, H, HG, G, K, tail_ch, nchunk;
     int dir, mode, out_ch_off, dt_softplus, d_per_head;
+    // Time parts (calls with too few (batch, head) items to fill the chip): the chunks are dealt to `parts` workgroups
+    // per item, part_chunks each, in scan order (blockIdx.y).  A first launch (kSsdStateOnly, parts - 1 of them) leaves
+    // each part's end state from a zero start and the product of its chunk decays; ssd_carry_kernel turns those into
+    // the state entering each part; the output launch then starts every part from its entry state.
+    int parts, part_chunks;
+    float* part_state;    // [parts][batch][Dn][N]
+    float* part_decay;    // [parts][batch][H]
 };
+
+struct SsdCarryArgs {
+    float* part_state[2];
+    const float* part_decay[2];
+    const float* h_in;    // forward direction's initial state or null
+    int batch, Dn, P, H, parts;
+};
+
+// One thread per (direction, batch, channel, four states): entry state of part p+1 = decay_p * entry_p + end_p.
+template <int N>
+__global__ __launch_bounds__(256) void ssd_carry_kernel(const SsdCarryArgs a)
+{
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long per_dir = (long long)a.batch * a.Dn * N / 4;
+    if (idx >= 2 * per_dir) return;
+    const int s = (int)(idx / per_dir);
+    const long long e = (idx % per_dir) * 4;            // element offset inside one part's [batch][Dn][N]
+    const int ch = (int)((e / N) % a.Dn), b = (int)(e / ((long long)N * a.Dn));
+    float4 h = (s == 0 && a.h_in) ? *reinterpret_cast<const float4*>(a.h_in + e) : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int p = 0; p < a.parts; p++) {
+        float4* slot = reinterpret_cast<float4*>(a.part_state[s] + (size_t)p * per_dir * 4 + e);
+        const bool more = p + 1 < a.parts;
+        const float4 end = more ? *slot : make_float4(0.f, 0.f, 0.f, 0.f);
+        *slot = h;
+        if (more) {
+            const float dk = a.part_decay[s][((size_t)p * a.batch + b) * a.H + ch / a.P];
+            h = make_float4(fmaf(dk, h.x, end.x), fmaf(dk, h.y, end.y), fmaf(dk, h.z, end.z), fmaf(dk, h.w, end.w));
+        }
+    }
+}
 
 // LDS of ssd_kernel: two buffers of per-chunk tiles (filled by the producer waves one chunk ahead of the consumer
 // waves) and two copies of the state in MFMA operand form.  SINGLE (calls of one chunk, i.e. block-diffusion steps):
@@ -229,10 +268,13 @@ __device__ __forceinline__ float wave_inclusive_sum(float v)
 // PG = 2 splits the producers into two groups of four waves: one builds the score operand and stages the tiles, the
 // other runs conv + SiLU (both run the short scan for themselves).  A producer wave's chain of dependent stages per
 // chunk is then about half as long, which is what sets the chunk period of long calls; the CU holds twelve waves.
-template <int N, int P, bool SINGLE = false, int PG = 1>
+// PARTS compiles the time parts in (chunk range and states per blockIdx.y, the state-only mode); without it the kernel
+// walks every chunk of its item and carries none of that bookkeeping through its loops.
+template <int N, int P, bool SINGLE = false, int PG = 1, bool PARTS = false>
 __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(const SsdArgs a_in)
 {
     static_assert(PG == 1 || (PG == 2 && !SINGLE), "one or two producer groups; the single-chunk form keeps one");
+    static_assert(!PARTS || (!SINGLE && PG == 1), "time parts come with one producer group and more than one chunk");
     using Lds = SsdLds<N, P, SINGLE>;
     SsdArgs a = a_in;
     if (SINGLE) a.nchunk = 1;   // known at compile time: the chunk pipeline below folds away
@@ -273,6 +315,16 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
     const int grp = head / a.HG;
     const int ch0 = head * P;
     const size_t Lpad = (size_t)a.nchunk * kQ;
+    // this workgroup's chunks [c_first, c_stop) and the states it starts from / leaves
+    const bool state_only = PARTS && a.mode == kSsdStateOnly;
+    constexpr bool in_parts = PARTS;
+    const int time_part = in_parts ? (int)blockIdx.y : 0;   // (`part` names the parked partial in the consumers)
+    const int c_first = in_parts ? time_part * a.part_chunks : 0;
+    const int c_stop = in_parts ? min(a.nchunk, c_first + a.part_chunks) : a.nchunk;
+    const size_t part_elems = (size_t)gridDim.z * a.Dn * N;
+    const float* const state_in = state_only ? nullptr : in_parts ? a.part_state + time_part * part_elems : a.h_in;
+    float* const state_out = state_only ? a.part_state + time_part * part_elems
+                                        : (time_part == (in_parts ? a.parts : 1) - 1) ? a.h_out : nullptr;
     const int last = a.L - 1;
     auto token_of = [&](int tau) { return a.dir > 0 ? tau : last - tau; };   // scan position -> token index
 
@@ -346,7 +398,7 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
             const __bf16* bsrc = a.b_t + ((((size_t)b * a.nchunk + c) * a.G + grp) * N) * kQ;
 #pragma unroll
             for (int i = 0; i < kCopy; i++) {
-                ctile[i] = *reinterpret_cast<const bf16x8*>(csrc + c_src[i]);
+                if (!state_only) ctile[i] = *reinterpret_cast<const bf16x8*>(csrc + c_src[i]);
                 btile[i] = *reinterpret_cast<const bf16x8*>(bsrc + b_src[i]);
             }
         };
@@ -382,7 +434,7 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
             }
             if (do_conv) pw_wgt[lane] = fast_exp2(l2_end - l2) * dl;
             __builtin_amdgcn_wave_barrier();
-            if (do_score) {
+            if (do_score && !state_only) {
                 // masked score operand: (B_j . C_i) exp(l_i - l_j) Delta_j for j <= i, else 0
                 float sv[kHS][4];
 #pragma unroll
@@ -481,7 +533,7 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
             if (do_score) {
 #pragma unroll
                 for (int i = 0; i < kCopy; i++) {
-                    *reinterpret_cast<bf16x8*>(&sC(buf)[c_dst[i]]) = ctile[i];
+                    if (!state_only) *reinterpret_cast<bf16x8*>(&sC(buf)[c_dst[i]]) = ctile[i];
                     *reinterpret_cast<bf16x8*>(&sBT(buf)[b_dst[i]]) = btile[i];
                 }
                 asm volatile("" ::: "memory");
@@ -489,16 +541,16 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
             }
             __builtin_amdgcn_wave_barrier();   // the next chunk's scan results overwrite pw_* only after these reads
         };
-        issue_dt(0);
+        issue_dt(c_first);
         if (do_score) {
-            issue_score(0);
-            issue_tiles(0);
+            if (!state_only) issue_score(c_first);
+            issue_tiles(c_first);
         }
-        if (do_conv) issue_x(0);
-        finish(0, 0, min(1, a.nchunk - 1));
+        if (do_conv) issue_x(c_first);
+        finish(c_first, 0, min(c_first + 1, c_stop - 1));
         lds_barrier();
-        for (int c = 0; c < a.nchunk; c++) {
-            if (c + 1 < a.nchunk) finish(c + 1, (c + 1) & 1, min(c + 2, a.nchunk - 1));
+        for (int c = c_first; c < c_stop; c++) {
+            if (c + 1 < c_stop) finish(c + 1, (c + 1 - c_first) & 1, min(c + 2, c_stop - 1));
             lds_barrier();
         }
         return;
@@ -510,7 +562,8 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
     // the store's full round trip, so every chunk first consumes its prefetched gate data, then stores).
     auto walk = [&](auto mode_c) {
         constexpr int kMode = decltype(mode_c)::value;
-        constexpr bool need_z = kMode != kSsdPartialRaw;
+        constexpr bool kStateOnly = kMode == kSsdStateOnly;
+        constexpr bool need_z = kMode != kSsdPartialRaw && !kStateOnly;
         constexpr bool need_p = kMode == kSsdFinalAdd || kMode == kSsdFinalAddRaw;
         constexpr bool park = kMode == kSsdPartialRaw || kMode == kSsdPartial;
         const int iblk = wave / kPB, pblk = wave % kPB;
@@ -532,8 +585,8 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
             const int nblk = iblk * kHB + hb;
 #pragma unroll
             for (int r = 0; r < 16; r++) hacc[hb][r] = 0.0f;
-            if (a.h_in) {   // registers 4q .. 4q+3 hold four adjacent states: 16-byte pieces (the host checks alignment)
-                const float* hrow = a.h_in + ((size_t)b * a.Dn + ch0 + po) * N + nblk * 32 + 4 * half;
+            if (state_in) {   // registers 4q .. 4q+3 hold four adjacent states: 16-byte pieces (the host checks alignment)
+                const float* hrow = state_in + ((size_t)b * a.Dn + ch0 + po) * N + nblk * 32 + 4 * half;
 #pragma unroll
                 for (int q = 0; q < 4; q++) {
                     const float4 v = *reinterpret_cast<const float4*>(hrow + 8 * q);
@@ -579,20 +632,21 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
                 }
             }
         };
-        publish_state(0);
-        bool state_nonzero = a.h_in != nullptr;
-        issue_gate(0);
+        if constexpr (!kStateOnly) publish_state(0);
+        bool state_nonzero = state_in != nullptr;
+        float decay_product = 1.0f;   // of the chunks walked (kSsdStateOnly)
+        issue_gate(c_first);
         lds_barrier();
 
-        for (int c = 0; c < a.nchunk; c++) {
-            const int buf = c & 1;
+        for (int c = c_first; c < c_stop; c++) {
+            const int buf = (c - c_first) & 1;
             const float* el = scal + buf * kQ;
             const __bf16* xc_t = sXc(buf);
             // ---- intra-chunk product with the masked, decayed score operand the producers prepared
             f32x16 y1 = {0}, y2 = {0};
 #pragma unroll
             for (int jblk = 0; jblk < 2; jblk++) {
-                if (jblk > iblk) break;
+                if (jblk > iblk || kStateOnly) break;
 #pragma unroll
                 for (int kb = 0; kb < 2; kb++) {
                     const bf16x8 am = *reinterpret_cast<const bf16x8*>(&sM(buf)[(((iblk * 2 + jblk) * 2 + kb) * 64 + lane) * 8]);
@@ -607,7 +661,7 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
                 }
             }
             // ---- inter-chunk product with the state entering the chunk
-            if (state_nonzero) {
+            if (state_nonzero && !kStateOnly) {
                 const __bf16* c_t = sC(buf);
                 const __bf16* h_t = sHT + buf * Lds::kHT;
 #pragma unroll
@@ -628,11 +682,12 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
             }
             // ---- state update of the blocks this wave owns (the state after the last chunk matters only if it is
             // committed)
-            const bool state_needed = c + 1 < a.nchunk || a.h_out != nullptr;
+            const bool state_needed = c + 1 < c_stop || state_out != nullptr;
             if (state_needed) {
                 const __bf16* b_t = sBT(buf);
                 const __bf16* xw_t = sXw(buf);
                 const float decay_q = el[kQ - 1];
+                decay_product *= decay_q;
 #pragma unroll
                 for (int hb = 0; hb < kHB; hb++) {
                     const int nblk = iblk * kHB + hb;
@@ -647,58 +702,61 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
                 }
             }
             // ---- epilogue: inter-chunk term, skip term, gate, combine; all 16 results first, then the stores
-            float res[16];
+            if constexpr (!kStateOnly) {
+                float res[16];
 #pragma unroll
-            for (int q = 0; q < 4; q++) {
-                const float4 e4 = *reinterpret_cast<const float4*>(&el[i0 + 8 * q]);
-                const bf16x4 x4 = *reinterpret_cast<const bf16x4*>(&xc_t[po * kRowT + i0 + 8 * q]);
-                const float ev[4] = {e4.x, e4.y, e4.z, e4.w};
+                for (int q = 0; q < 4; q++) {
+                    const float4 e4 = *reinterpret_cast<const float4*>(&el[i0 + 8 * q]);
+                    const bf16x4 x4 = *reinterpret_cast<const bf16x4*>(&xc_t[po * kRowT + i0 + 8 * q]);
+                    const float ev[4] = {e4.x, e4.y, e4.z, e4.w};
 #pragma unroll
-                for (int e = 0; e < 4; e++) {
-                    const int r = 4 * q + e;
-                    const float y = y1[r] + ev[e] * y2[r] + dval * (float)x4[e];
-                    if constexpr (!need_z) res[r] = y;
-                    else {
-                        const float zg = silu(IoBF16::cvt(zraw[r]));
-                        res[r] = kMode == kSsdFinalAddRaw ? (y + part[r]) * zg : need_p ? y * zg + part[r] : y * zg;
+                    for (int e = 0; e < 4; e++) {
+                        const int r = 4 * q + e;
+                        const float y = y1[r] + ev[e] * y2[r] + dval * (float)x4[e];
+                        if constexpr (!need_z) res[r] = y;
+                        else {
+                            const float zg = silu(IoBF16::cvt(zraw[r]));
+                            res[r] = kMode == kSsdFinalAddRaw ? (y + part[r]) * zg : need_p ? y * zg + part[r] : y * zg;
+                        }
                     }
                 }
-            }
-            {
-                const int tau0 = c * kQ + i0;
-                if (c * kQ + kQ - 1 <= last) {
-                    const long long t0 = token_of(tau0);
-                    float* pp = pbase + t0 * a.Dn;
-                    T* op = obase + t0 * a.out_st;
+                {
+                    const int tau0 = c * kQ + i0;
+                    if (c * kQ + kQ - 1 <= last) {
+                        const long long t0 = token_of(tau0);
+                        float* pp = pbase + t0 * a.Dn;
+                        T* op = obase + t0 * a.out_st;
 #pragma unroll
-                    for (int r = 0; r < 16; r++) {
-                        if constexpr (park) pp[row_k(r) * pstep] = res[r];
-                        else IoBF16::st(op + row_k(r) * ostep, res[r]);
-                    }
-                } else {
+                        for (int r = 0; r < 16; r++) {
+                            if constexpr (park) pp[row_k(r) * pstep] = res[r];
+                            else IoBF16::st(op + row_k(r) * ostep, res[r]);
+                        }
+                    } else {
 #pragma unroll
-                    for (int r = 0; r < 16; r++) {
-                        const int tau = tau0 + row_k(r);
-                        if (tau <= last) {
-                            const long long t = token_of(tau);
-                            if constexpr (park) pbase[t * a.Dn] = res[r];
-                            else IoBF16::st(obase + t * a.out_st, res[r]);
+                        for (int r = 0; r < 16; r++) {
+                            const int tau = tau0 + row_k(r);
+                            if (tau <= last) {
+                                const long long t = token_of(tau);
+                                if constexpr (park) pbase[t * a.Dn] = res[r];
+                                else IoBF16::st(obase + t * a.out_st, res[r]);
+                            }
                         }
                     }
                 }
             }
-            if (c + 1 < a.nchunk) {
+            if (c + 1 < c_stop) {
                 issue_gate(c + 1);
-                publish_state(buf ^ 1);
+                if constexpr (!kStateOnly) publish_state(buf ^ 1);
             }
             state_nonzero = true;
             lds_barrier();
         }
-        if (a.h_out) {
+        if (kStateOnly && wave == 0 && lane == 0) a.part_decay[((size_t)time_part * gridDim.z + b) * a.H + head] = decay_product;
+        if (state_out) {
 #pragma unroll
             for (int hb = 0; hb < kHB; hb++) {
                 const int nblk = iblk * kHB + hb;
-                float* hrow = a.h_out + ((size_t)b * a.Dn + ch0 + po) * N + nblk * 32 + 4 * half;
+                float* hrow = state_out + ((size_t)b * a.Dn + ch0 + po) * N + nblk * 32 + 4 * half;
 #pragma unroll
                 for (int q = 0; q < 4; q++)
                     *reinterpret_cast<float4*>(hrow + 8 * q) =
@@ -711,6 +769,9 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
         case kSsdPartial: walk(std::integral_constant<int, kSsdPartial>{}); break;
         case kSsdPartialRaw: walk(std::integral_constant<int, kSsdPartialRaw>{}); break;
         case kSsdFinalAdd: walk(std::integral_constant<int, kSsdFinalAdd>{}); break;
+        case kSsdStateOnly:
+            if constexpr (PARTS) walk(std::integral_constant<int, kSsdStateOnly>{});
+            break;
         default: walk(std::integral_constant<int, kSsdFinalAddRaw>{}); break;
     }
 }

@@ -160,3 +160,29 @@ def test_ssd_state_not_16_byte_aligned_falls_back(gpu, oracle):
     assert rel_l2(out.float().cpu().numpy(), ref) < gpu.TOL["bf16"]
     assert rel_l2(h_out.cpu().numpy(), h_ref) < 1e-5      # the lane-per-chain kernels keep the state to fp32 accuracy
     assert float(buf_out[0]) == 0.0
+
+
+@pytest.mark.parametrize("L,batch,N,kw", [(1100, 1, 128, {}), (2117, 2, 64, dict(combine=1)),
+                                          (1030, 1, 64, dict(conv_bc=0, dt_softplus=0, d_kind=0))])
+def test_ssd_time_parts(gpu, oracle, L, batch, N, kw):
+    """Few (batch, head) items and many chunks: each item's chunks are dealt to several workgroups (a state-only pass,
+    a carry over the parts, then the output pass).  Ragged last part, both combines, and the block variant: the parts
+    start from the cached state and the committed state is the last part's."""
+    from paper_2511_15927_amd import binding as bd
+    cfg = synth.m2_cfg(batch, L, 256, headdim=64, d_state=N, **kw)
+    assert bd.bimamba_time_chunks(bd.make_desc(cfg)) > 1
+    pf, pb, inp = case(cfg, 1900 + L)
+    ref = oracle.bimamba_fwd(cfg, to_np(pf), to_np(pb), to_np(inp))
+    assert rel_l2(gpu.gpu_fwd(cfg, pf, pb, inp), ref) < gpu.TOL["bf16"]
+    # block variant on top of a prefix
+    m = 5
+    pre = {k: v[:, :m].contiguous() for k, v in inp.items()}
+    blk = {k: v[:, m:].contiguous() for k, v in inp.items()}
+    _, h_pre, tail_pre = oracle.bimamba_block_fwd(dict(cfg, seqlen=m), to_np(pf), to_np(pb), to_np(pre))
+    cb = dict(cfg, seqlen=L - m)
+    assert bd.bimamba_time_chunks(bd.make_desc(cb)) > 1
+    ref_b, h_ref, tail_ref = oracle.bimamba_block_fwd(cb, to_np(pf), to_np(pb), to_np(blk), h_in=h_pre.astype(np.float32), tail_in=tail_pre)
+    out, h, tail = gpu.gpu_block_fwd(cb, pf, pb, blk, h_in=h_pre.astype(np.float32), tail_in=tail_pre)
+    assert rel_l2(out, ref_b) < gpu.TOL["bf16"]
+    assert rel_l2(h, h_ref) < 1e-2
+    assert np.array_equal(tail, tail_ref)
