@@ -100,6 +100,24 @@ def test_workspace_and_chunk_planning():
     assert bd.bimamba_workspace_bytes(d1) % 256 == 0
 
 
+def test_time_parts_of_the_matrix_core_path():
+    # 64 heads: batch 1 leaves 3/4 of the CUs empty -> 4 parts; batch 2 -> 2; batch 4 fills the chip -> 1.
+    parts = {b: bd.bimamba_time_chunks(bd.make_desc(synth.m2_cfg(b, 8192, 4096))) for b in (1, 2, 3, 4, 8)}
+    assert parts == {1: 4, 2: 2, 3: 1, 4: 1, 8: 1}, parts
+    # 8 heads: 16 parts at most, and no part shorter than 8 chunks of 64 tokens
+    assert bd.bimamba_time_chunks(bd.make_desc(synth.m2_cfg(1, 32768, 512))) == 16
+    assert bd.bimamba_time_chunks(bd.make_desc(synth.m2_cfg(1, 2048, 512))) == 4
+    assert bd.bimamba_time_chunks(bd.make_desc(synth.m2_cfg(1, 1023, 512))) == 2
+    assert bd.bimamba_time_chunks(bd.make_desc(synth.m2_cfg(1, 960, 512))) == 1
+    # parts of ceil(chunks / parts) chunks: 17 chunks in 2 parts of 9
+    assert bd.bimamba_time_chunks(bd.make_desc(synth.m2_cfg(1, 17 * 64, 512))) == 2
+    # the part states live in the workspace
+    one = bd.bimamba_workspace_bytes(bd.make_desc(synth.m2_cfg(4, 8192, 4096))) / 4
+    assert bd.bimamba_workspace_bytes(bd.make_desc(synth.m2_cfg(1, 8192, 4096))) > one
+    # the block variant keeps one part (a block is at most a few chunks)
+    assert bd.bimamba_time_chunks(bd.make_desc(synth.m2_cfg(1, 64, 512))) == 1
+
+
 def test_status_strings():
     lib = bd.lib()
     for code in range(0, -7, -1):
