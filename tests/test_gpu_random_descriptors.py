@@ -51,6 +51,9 @@ def draw(rng):
         cfg["time_chunks"] = int(rng.integers(2, 5))
     untied = bool(rng.integers(0, 2))
     random_a = bool(rng.integers(0, 2))
+    if layout == "mamba2_mfma" and rng.integers(0, 3) == 0:
+        # long enough for the chunked kernels to deal a head's chunks to several workgroups (time parts)
+        cfg["seqlen"] = int(rng.choice([1030, 1280, 2117]))
     return layout, cfg, untied, random_a
 
 
