@@ -35,7 +35,8 @@
  *     accumulation and the carried state stay fp32.  They read x two channels at a time and the carried state four
  *     states at a time: setting time_chunks or state_split, or passing an x whose pointer is not 4-byte aligned or
  *     whose strides are odd, or an h_in / h_out that is not 16-byte aligned, selects the lane-per-chain kernels for
- *     the call; the workspace size covers both.
+ *     the call; the workspace size covers both.  A call with few (batch, head) pairs cuts the sequence into time
+ *     parts that run concurrently (see bimamba_time_chunks), unless x has a token stride beyond 2^24 elements.
  *
  * Execution: calls validate their arguments on the host, enqueue kernels on the caller's HIP stream
  * and return without synchronising.  Calls on different streams are independent as long as their

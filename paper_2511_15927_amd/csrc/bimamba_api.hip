@@ -145,6 +145,7 @@ struct Plan {
     bool ssd;     // Mamba-2 parameterisation on the chunked matrix-core kernels
     int ssd_chunks;
     int ssd_parts, ssd_part_chunks;  // time parts of the matrix-core path (1: every (batch, head) item is one workgroup)
+    int ssd_subs, ssd_part_subs, ssd_sub_chunks;  // sub-parts the state pass walks: in all, per part, chunks of each
     size_t off_bc[2], off_partial, off_carry, off_sumdt, off_crows[2], off_bt[2], off_score[2], off_pstate[2], off_pdecay[2], total;
 };
 
@@ -184,17 +185,26 @@ Plan make_plan(const bimamba_desc* d, bool inputs_shared)
     p.ssd_chunks = (d->seqlen + kQ - 1) / kQ;
     // Time parts: a call whose (batch, head) items would leave at least half of the 256 CUs empty deals each item's
     // chunks to several workgroups (at least 8 chunks each, at most 16 parts); a first, cheaper pass then finds the
-    // state entering each part.
-    p.ssd_parts = 1;
-    p.ssd_part_chunks = p.ssd_chunks;
+    // state entering each part.  That pass runs light workgroups, four to a CU, so it cuts the parts further into
+    // sub-parts (at least 4 chunks each) until both directions together bring about that many.
+    p.ssd_parts = p.ssd_subs = p.ssd_part_subs = 1;
+    p.ssd_part_chunks = p.ssd_sub_chunks = p.ssd_chunks;
     if (p.ssd) {
         const long long items = (long long)d->n_heads * d->batch;
         long long parts = items > 0 ? 256 / items : 1;
         if (parts > p.ssd_chunks / 8) parts = p.ssd_chunks / 8;
         if (parts > 16) parts = 16;
         if (parts >= 2) {
-            p.ssd_part_chunks = (int)((p.ssd_chunks + parts - 1) / parts);
+            const int part_chunks = (int)((p.ssd_chunks + parts - 1) / parts);
+            const long long subs_wanted = (4 * 256 + 2 * items - 1) / (2 * items);
+            long long k = (subs_wanted + parts - 1) / parts;
+            if (k > part_chunks / 4) k = part_chunks / 4;
+            if (k < 1) k = 1;
+            p.ssd_part_subs = (int)k;
+            p.ssd_sub_chunks = (int)((part_chunks + k - 1) / k);
+            p.ssd_part_chunks = p.ssd_part_subs * p.ssd_sub_chunks;
             p.ssd_parts = (p.ssd_chunks + p.ssd_part_chunks - 1) / p.ssd_part_chunks;
+            p.ssd_subs = (p.ssd_chunks + p.ssd_sub_chunks - 1) / p.ssd_sub_chunks;
         }
     }
     if (p.ssd) {
@@ -208,9 +218,9 @@ Plan make_plan(const bimamba_desc* d, bool inputs_shared)
         for (int s = 0; s < 2; s++) {
             p.off_pstate[s] = p.off_pdecay[s] = off;
             if (p.ssd_parts > 1) {
-                off += align_up((size_t)p.ssd_parts * d->batch * d->d_inner * d->d_state * sizeof(float), 256);
+                off += align_up((size_t)p.ssd_subs * d->batch * d->d_inner * d->d_state * sizeof(float), 256);
                 p.off_pdecay[s] = off;
-                off += align_up((size_t)p.ssd_parts * d->batch * d->n_heads * sizeof(float), 256);
+                off += align_up((size_t)p.ssd_subs * d->batch * d->n_heads * sizeof(float), 256);
             }
         }
     }
@@ -320,6 +330,13 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
     // the chunked kernels read x two channels at a time and the carried state four states at a time
     if (plan.ssd && !(pairs_readable(in_f->x) && pairs_readable(in_b->x) && is_aligned(h_in, 16) && is_aligned(h_out, 16)))
         plan.ssd = false;
+    // the state pass of the time parts addresses the 67 token rows of a chunk with 32-bit byte offsets
+    constexpr int64_t kMaxPartsTokenStride = 1 << 24;
+    if (plan.ssd && plan.ssd_parts > 1 &&
+        (in_f->x.stride_token > kMaxPartsTokenStride || in_b->x.stride_token > kMaxPartsTokenStride)) {
+        plan.ssd_parts = plan.ssd_subs = plan.ssd_part_subs = 1;
+        plan.ssd_part_chunks = plan.ssd_sub_chunks = plan.ssd_chunks;
+    }
     if (plan.total > 0) {
         if (!workspace) return BIMAMBA_ERR_NULL_POINTER;
         if (!is_aligned(workspace, 16)) return BIMAMBA_ERR_MISALIGNED;
@@ -372,10 +389,7 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
             }
             launch_ssd_prep(d->d_state, pp, plan.ssd_chunks, d->batch, st);
             if (probe_start) (void)hipEventRecord(probe_start, st);
-            // pass 0 (time parts only): each part's end state from a zero start, then the states entering the parts;
-            // pass 1: the outputs
-            for (int pass = plan.ssd_parts > 1 ? 0 : 1; pass < 2; pass++) {
-            for (int s = 1; s >= 0; s--) {
+            auto scan_args = [&](int s) {
                 const bimamba_inputs* in = s == 0 ? in_f : in_b;
                 const bimamba_params* p = s == 0 ? pf : pb;
                 SsdArgs sa{};
@@ -392,27 +406,32 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
                 sa.L = d->seqlen; sa.Dn = d->d_inner; sa.H = d->n_heads; sa.HG = d->n_heads / d->n_groups;
                 sa.G = d->n_groups; sa.K = d->d_conv; sa.tail_ch = tail_ch; sa.nchunk = plan.ssd_chunks;
                 sa.parts = plan.ssd_parts; sa.part_chunks = plan.ssd_part_chunks;
+                sa.part_subs = plan.ssd_part_subs; sa.sub_chunks = plan.ssd_sub_chunks;
                 sa.part_state = reinterpret_cast<float*>(ws + plan.off_pstate[s]);
                 sa.part_decay = reinterpret_cast<float*>(ws + plan.off_pdecay[s]);
                 sa.dir = s == 0 ? 1 : -1;
-                sa.mode = pass == 0 ? kSsdStateOnly : separate ? kSsdFinalOnly
+                sa.mode = separate ? kSsdFinalOnly
                                    : s == 1 ? (raw ? kSsdPartialRaw : kSsdPartial) : (raw ? kSsdFinalAddRaw : kSsdFinalAdd);
                 sa.out_ch_off = separate ? s * d->d_inner : 0;
                 sa.dt_softplus = d->dt_softplus; sa.d_per_head = d->d_kind == BIMAMBA_D_PER_HEAD;
-                launch_ssd_scan(d->d_state, d->d_inner / d->n_heads, sa, d->batch, st);
-            }
-            if (pass == 0) {
+                return sa;
+            };
+            if (plan.ssd_parts > 1) {
+                // time parts: every sub-part's end state from a zero start, then the states entering them
+                SsdStatePair sp;
                 SsdCarryArgs ca{};
                 for (int s = 0; s < 2; s++) {
-                    ca.part_state[s] = reinterpret_cast<float*>(ws + plan.off_pstate[s]);
-                    ca.part_decay[s] = reinterpret_cast<const float*>(ws + plan.off_pdecay[s]);
+                    sp.dir[s] = scan_args(s);
+                    ca.part_state[s] = sp.dir[s].part_state;
+                    ca.part_decay[s] = sp.dir[s].part_decay;
                 }
+                launch_ssd_state(d->d_state, d->d_inner / d->n_heads, sp, plan.ssd_subs, d->batch, st);
                 ca.h_in = block_variant ? h_in : nullptr;
                 ca.batch = d->batch; ca.Dn = d->d_inner; ca.P = d->d_inner / d->n_heads; ca.H = d->n_heads;
-                ca.parts = plan.ssd_parts;
+                ca.parts = plan.ssd_subs;
                 launch_ssd_carry(d->d_state, ca, st);
             }
-            }
+            for (int s = 1; s >= 0; s--) launch_ssd_scan(d->d_state, d->d_inner / d->n_heads, scan_args(s), d->batch, st);
             if (probe_stop) (void)hipEventRecord(probe_stop, st);
         } else {
         // 2. scan (summary + carry when the sequence is cut into segments) and combine

@@ -48,8 +48,7 @@ static void scan_variant(const SsdArgs& sa, int batch, hipStream_t st)
     auto kernel = ssd_kernel<N, P, SINGLE, GROUPS, PARTS>;
     if (first_use_on_current_device(seen))
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    // blockIdx.y is the time part; the state-only pass has nothing to do for the part scanned last
-    const unsigned parts = !PARTS ? 1u : (unsigned)(sa.mode == kSsdStateOnly ? sa.parts - 1 : sa.parts);
+    const unsigned parts = !PARTS ? 1u : (unsigned)sa.parts;   // blockIdx.y is the time part
     hipLaunchKernelGGL(kernel, dim3((unsigned)sa.H, parts, (unsigned)batch), dim3(4 * P + 256 * GROUPS), lds, st, sa);
 }
 
@@ -80,6 +79,17 @@ void launch_ssd_carry(int d_state, const SsdCarryArgs& ca, hipStream_t st)
     const dim3 grid((unsigned)((threads + 255) / 256));
     if (d_state == 128) hipLaunchKernelGGL(ssd_carry_kernel<128>, grid, dim3(256), 0, st, ca);
     else hipLaunchKernelGGL(ssd_carry_kernel<64>, grid, dim3(256), 0, st, ca);
+}
+
+// Both directions in one launch; nothing to do for the sub-part scanned last (no part starts after it).
+void launch_ssd_state(int d_state, int headdim, const SsdStatePair& sp, int subs, int batch, hipStream_t st)
+{
+    if (subs < 2) return;
+    const dim3 grid((unsigned)sp.dir[0].H, (unsigned)(subs - 1), (unsigned)(2 * batch));
+    if (d_state == 128 && headdim == 64) hipLaunchKernelGGL((ssd_state_kernel<128, 64>), grid, dim3(256), 0, st, sp);
+    else if (d_state == 128 && headdim == 32) hipLaunchKernelGGL((ssd_state_kernel<128, 32>), grid, dim3(256), 0, st, sp);
+    else if (d_state == 64 && headdim == 64) hipLaunchKernelGGL((ssd_state_kernel<64, 64>), grid, dim3(256), 0, st, sp);
+    else if (d_state == 64 && headdim == 32) hipLaunchKernelGGL((ssd_state_kernel<64, 32>), grid, dim3(256), 0, st, sp);
 }
 
 void launch_ssd_scan(int d_state, int headdim, const SsdArgs& sa, int batch, hipStream_t st)

@@ -162,9 +162,8 @@ __global__ __launch_bounds__(256) void ssd_prep_kernel(const SsdPrepPair both)
     }
 }
 
-// Output modes of ssd_kernel.  kSsdStateOnly writes no output: it runs a time part from a zero state and leaves the
-// part's end state and total decay for ssd_carry_kernel (see the time parts below).
-enum { kSsdFinalOnly = 0, kSsdPartial = 1, kSsdPartialRaw = 2, kSsdFinalAdd = 3, kSsdFinalAddRaw = 4, kSsdStateOnly = 5 };
+// Output modes of ssd_kernel.
+enum { kSsdFinalOnly = 0, kSsdPartial = 1, kSsdPartialRaw = 2, kSsdFinalAdd = 3, kSsdFinalAddRaw = 4 };
 
 struct SsdArgs {
     TensorArg x, z, dt;
@@ -181,22 +180,23 @@ struct SsdArgs {
     int L, Dn, H, HG, G, K, tail_ch, nchunk;
     int dir, mode, out_ch_off, dt_softplus, d_per_head;
     // Time parts (calls with too few (batch, head) items to fill the chip): the chunks are dealt to `parts` workgroups
-    // per item, part_chunks each, in scan order (blockIdx.y).  A first launch (kSsdStateOnly, parts - 1 of them) leaves
-    // each part's end state from a zero start and the product of its chunk decays; ssd_carry_kernel turns those into
-    // the state entering each part; the output launch then starts every part from its entry state.
-    int parts, part_chunks;
-    float* part_state;    // [parts][batch][Dn][N]
-    float* part_decay;    // [parts][batch][H]
+    // per item, part_chunks each, in scan order (blockIdx.y).  A part is part_subs sub-parts of sub_chunks chunks;
+    // ssd_state_kernel leaves every sub-part's end state from a zero start and the product of its chunk decays (all
+    // but the scan-last one), ssd_carry_kernel turns those into the state entering each sub-part, and the output launch
+    // starts part p from the entry state of sub-part p * part_subs.
+    int parts, part_chunks, part_subs, sub_chunks;
+    float* part_state;    // [subs][batch][Dn][N]
+    float* part_decay;    // [subs][batch][H]
 };
 
 struct SsdCarryArgs {
     float* part_state[2];
     const float* part_decay[2];
     const float* h_in;    // forward direction's initial state or null
-    int batch, Dn, P, H, parts;
+    int batch, Dn, P, H, parts;   // parts: the number of sub-parts to fold over
 };
 
-// One thread per (direction, batch, channel, four states): entry state of part p+1 = decay_p * entry_p + end_p.
+// One thread per (direction, batch, channel, four states): entry state of sub-part p+1 = decay_p * entry_p + end_p.
 template <int N>
 __global__ __launch_bounds__(256) void ssd_carry_kernel(const SsdCarryArgs a)
 {
@@ -257,6 +257,218 @@ __device__ __forceinline__ float wave_inclusive_sum(float v)
     return v;
 }
 
+struct SsdStatePair {
+    SsdArgs dir[2];   // forward, reverse: one launch walks both
+};
+
+// State pass of the time parts.  grid (H, subs - 1, 2 * batch), block 256, static LDS; blockIdx.z / batch selects the
+// direction and blockIdx.y the sub-part: sub_chunks chunks in scan order, walked from a zero state.  Leaves the
+// sub-part's end state in part_state[sub] and the product of its chunk decays in part_decay[sub] for
+// ssd_carry_kernel.  The end state needs neither the score tile nor C nor the gate, so this is the conv + SiLU of x,
+// the chunk's decay weights and the state-update product only, in a workgroup light enough (four waves, 19 KB of LDS)
+// that three or four of them share a CU; the sub-parts are what gives the chip that many workgroups.  All four
+// waves run the short scan for themselves, convolve a quarter of the chunk's positions each, and own 1/4 of the
+// 32 x 32 blocks of H, whose B^T operand they read straight from the prepared tile in global memory.
+template <int N, int P>
+__global__ __launch_bounds__(256, 4) void ssd_state_kernel(const SsdStatePair both)
+{
+    constexpr int kPB = P / 32, kNB = N / 32, kBlocks = kNB * kPB, kOwn = (kBlocks + 3) / 4;
+    constexpr int kRowT = kQ + kPadK;
+    constexpr int kCP = P / 2;                // channel pairs of the head
+    constexpr int kPos = kQ * kCP / 256;      // chunk positions per thread in the conv (8 or 4)
+    using T = unsigned short;
+    __shared__ __attribute__((aligned(16))) __bf16 s_xw[2][P * kRowT];   // conv output times end-of-chunk weight, transposed
+    __shared__ __attribute__((aligned(16))) float s_wgt[4][kQ];          // wave-private: end-of-chunk weight of each position
+
+    // (no division here: the compiler divides on the vector ALU and would then treat every argument read through
+    // the quotient as varying across the wave)
+    const int batch = gridDim.z >> 1;
+    const int reverse = (int)blockIdx.z >= batch ? 1 : 0;
+    const SsdArgs& a = both.dir[reverse];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int head = blockIdx.x, b = (int)blockIdx.z - reverse * batch, sub = blockIdx.y;
+    const int grp = head / a.HG, ch0 = head * P;
+    // (the host never hands this pass the sequence's last sub-part, so every chunk here is a full one)
+    const int c_first = sub * a.sub_chunks, c_stop = min(a.L / kQ, c_first + a.sub_chunks);
+    const int last = a.L - 1;
+    auto token_of = [&](int tau) { return a.dir > 0 ? tau : last - tau; };
+
+    const int cp = tid % kCP, tg = tid / kCP;   // conv role: channels 2cp, 2cp+1; positions kPos*tg .. of each chunk
+    const float a2 = a.A[head] * kLog2e;
+    const float dtb = (a.dt_softplus && a.dt_bias) ? a.dt_bias[head] : 0.0f;
+    float w4[2][4], cbias[2];
+#pragma unroll
+    for (int h2 = 0; h2 < 2; h2++) {
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+            w4[h2][3 - i] = i < a.K ? a.conv_w[(size_t)(ch0 + 2 * cp + h2) * a.K + (a.K - 1 - i)] : 0.0f;
+        cbias[h2] = a.conv_b ? a.conv_b[ch0 + 2 * cp + h2] : 0.0f;
+    }
+    const T* xb = (const T*)a.x.p + (size_t)b * a.x.sb + ch0 + 2 * cp;
+    const T* dtp = (const T*)a.dt.p + (size_t)b * a.dt.sb + head;
+    float* const wgt = s_wgt[wave];
+
+    // matrix role: blocks kOwn * wave + o of the kNB x kPB blocks of H, channel block fastest, so that the blocks of a
+    // wave share their rows of B^T (kSameB: one operand load serves both)
+    constexpr bool kSameB = kOwn == 2 && kPB == 2;
+    constexpr int kLoadB = kSameB ? 1 : kOwn;
+    const int cl = lane & 31, half = lane >> 5;
+    f32x16 hacc[kOwn];
+#pragma unroll
+    for (int o = 0; o < kOwn; o++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) hacc[o][r] = 0.0f;
+
+    // channel pair at positions kPos*tg - 3 .. kPos*tg + kPos - 1 and Delta of position `lane`, as requested for the
+    // chunk after the one being worked on
+    unsigned xnext[kPos + 3];
+    T dtraw;
+    auto issue_dt = [&](int c) { dtraw = dtp[(long long)token_of(min(c * kQ + lane, last)) * a.dt.st]; };
+    // A chunk inside the sequence is read through a raw buffer range anchored at the chunk's lowest token row: the
+    // row of register q is a wave-uniform offset, the thread's rows and channel pair a 32-bit offset that never
+    // changes (no per-row vector address arithmetic, no address registers).  The host keeps 67 rows within 2^32 bytes.
+    const unsigned st_bytes = (unsigned)a.x.st * (unsigned)sizeof(T);
+    const unsigned x_lane_off = (unsigned)(a.dir > 0 ? kPos * tg : kQ - kPos * (tg + 1)) * st_bytes + 4u * cp;
+    const T* const x_head = (const T*)a.x.p + (size_t)b * a.x.sb + ch0;
+    auto issue_x_inside = [&](int c) {   // chunks 1 .. L / kQ - 1
+        {
+            const Rsrc rows = raw_range(x_head + (long long)(a.dir > 0 ? c * kQ - 3 : last - (c * kQ + kQ - 1)) * a.x.st);
+            // register q holds scan position q of the thread, so the rows run backwards in the reverse direction.
+            // (The offsets are formed in scalar registers for every chunk anew: carried across the loop, the compiler
+            // keeps them in vector registers and loops over the lanes to read them back for each load.)
+            int row_step = __builtin_amdgcn_readfirstlane(a.dir * (int)st_bytes);
+            asm volatile("" : "+s"(row_step));
+            const int row_0 = ((1 - a.dir) >> 1) * (kPos + 2) * (a.dir * row_step);
+#pragma unroll
+            for (int q = 0; q < kPos + 3; q++)
+                xnext[q] = __builtin_amdgcn_raw_buffer_load_b32(rows, x_lane_off, row_0 + q * row_step, 0);
+        }
+    };
+    auto issue_x_first = [&]() {   // chunk 0: positions before the sequence are clamped here and zeroed in the conv
+        const int tau0 = kPos * tg - 3;
+#pragma unroll
+        for (int q = 0; q < kPos + 3; q++)
+            xnext[q] = *reinterpret_cast<const unsigned*>(xb + (long long)token_of(min(max(tau0 + q, 0), last)) * a.x.st);
+    };
+    if (c_first >= c_stop) return;   // (never: see above)
+    issue_dt(c_first);
+    if (c_first == 0) issue_x_first(); else issue_x_inside(c_first);
+    float decay_product = 1.0f;
+    // The walk is bound by the latency of its loads (a row piece of 128 bytes per token, each from another DRAM page),
+    // not by its arithmetic: what chunk c + 1 needs is requested at the top of chunk c, a whole chunk of work ahead,
+    // and on every path alike (the walk's last chunk re-requests a valid chunk), so that the waits below count the
+    // same loads in flight whichever way the loop was entered.
+    const int c_inside = a.L / kQ - 1;   // the last chunk that is certainly a full one
+    for (int c = c_first; c < c_stop; c++) {
+        const int buf = (c - c_first) & 1;
+        const int cn = max(1, min(c + 1, c_inside));
+        // take over what was requested for this chunk
+        unsigned xraw[kPos + 3];
+#pragma unroll
+        for (int q = 0; q < kPos + 3; q++) xraw[q] = xnext[q];
+        float dl = IoBF16::cvt(dtraw);
+        issue_dt(cn);
+        // this wave's B^T operands straight from the prepared tile (rows of kQ positions), used after the barrier.
+        bf16x8 ab[kLoadB][4];
+        {
+            const __bf16* bsrc = a.b_t + ((((size_t)b * a.nchunk + c) * a.G + grp) * N) * kQ;
+#pragma unroll
+            for (int o = 0; o < kLoadB; o++) {
+                const int id = kOwn * wave + o, nblk = id / kPB;
+                if (kBlocks % 4 == 0 || id < kBlocks) {
+#pragma unroll
+                    for (int kb = 0; kb < 4; kb++)
+                        ab[o][kb] = *reinterpret_cast<const bf16x8*>(bsrc + (nblk * 32 + cl) * kQ + 16 * kb + 8 * half);
+                }
+            }
+        }
+        issue_x_inside(cn);
+        // Delta, inclusive cumulative log2-decay, end-of-chunk weight of position `lane`
+        if (a.dt_softplus) dl = softplus(dl + dtb);
+        if (c * kQ + lane > last) dl = 0.0f;
+        const float l2 = wave_inclusive_sum(dl * a2);
+        const float l2_end = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(l2), 63));
+        wgt[lane] = fast_exp2(l2_end - l2) * dl;
+        const float decay_q = fast_exp2(l2_end);
+        __builtin_amdgcn_wave_barrier();
+        // conv + SiLU of two channels at kPos positions, weighted
+        if (c == 0) {
+#pragma unroll
+            for (int q = 0; q < 3; q++)
+                if (kPos * tg + q - 3 < 0) xraw[q] = 0u;
+            if (a.dir > 0 && a.tail_in && tg == 0 && a.K > 1) {
+                unsigned cached[3];
+#pragma unroll
+                for (int q = 0; q < 3; q++) {   // 3 - q tokens before the block (a tap beyond the conv width has a zero weight)
+                    const T* tp = (const T*)a.tail_in + ((size_t)b * (a.K - 1) + max(a.K - 1 - (3 - q), 0)) * a.tail_ch + ch0 + 2 * cp;
+                    cached[q] = (unsigned)tp[0] | ((unsigned)tp[1] << 16);
+                }
+                // (consumed here, so that no load is pending on xraw where the two paths join: the conv must not
+                // wait for the younger B^T loads)
+#pragma unroll
+                for (int q = 0; q < 3; q++) asm volatile("" : "+v"(cached[q]));
+#pragma unroll
+                for (int q = 0; q < 3; q++)
+                    if (3 - q <= a.K - 1) xraw[q] = cached[q];
+            }
+        }
+        float wq[kPos];
+#pragma unroll
+        for (int q = 0; q < kPos; q += 4) {
+            const float4 w = *reinterpret_cast<const float4*>(&wgt[kPos * tg + q]);
+            wq[q] = w.x; wq[q + 1] = w.y; wq[q + 2] = w.z; wq[q + 3] = w.w;
+        }
+#pragma unroll
+        for (int h2 = 0; h2 < 2; h2++) {
+            typedef __attribute__((__vector_size__(kPos * sizeof(__bf16)))) __bf16 bf16run;
+            float xr[kPos + 3];
+#pragma unroll
+            for (int q = 0; q < kPos + 3; q++) xr[q] = __uint_as_float(h2 == 0 ? xraw[q] << 16 : xraw[q] & 0xffff0000u);
+            bf16run vw;
+#pragma unroll
+            for (int q = 0; q < kPos; q++) {
+                float pre = cbias[h2];
+                pre = fmaf(w4[h2][0], xr[q], pre);
+                pre = fmaf(w4[h2][1], xr[q + 1], pre);
+                pre = fmaf(w4[h2][2], xr[q + 2], pre);
+                pre = fmaf(w4[h2][3], xr[q + 3], pre);
+                vw[q] = (__bf16)(silu(pre) * wq[q]);
+            }
+            *reinterpret_cast<bf16run*>(&s_xw[buf][(2 * cp + h2) * kRowT + kPos * tg]) = vw;
+        }
+        lds_barrier();   // one per chunk: the other buffer is rewritten only after every wave has passed this one
+        decay_product *= decay_q;
+#pragma unroll
+        for (int o = 0; o < kOwn; o++) {
+            const int id = kOwn * wave + o, pblk = id % kPB;
+            if (kBlocks % 4 == 0 || id < kBlocks) {
+#pragma unroll
+                for (int r = 0; r < 16; r++) hacc[o][r] *= decay_q;
+#pragma unroll
+                for (int kb = 0; kb < 4; kb++) {
+                    const bf16x8 bw = *reinterpret_cast<const bf16x8*>(&s_xw[buf][(pblk * 32 + cl) * kRowT + 16 * kb + 8 * half]);
+                    hacc[o] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ab[kSameB ? 0 : o][kb], bw, hacc[o], 0, 0, 0);
+                }
+            }
+        }
+    }
+    if (tid == 0) a.part_decay[((size_t)sub * batch + b) * a.H + head] = decay_product;
+    float* const state_out = a.part_state + (size_t)sub * batch * a.Dn * N;
+#pragma unroll
+    for (int o = 0; o < kOwn; o++) {
+        const int id = kOwn * wave + o, nblk = id / kPB, pblk = id % kPB;
+        if (kBlocks % 4 == 0 || id < kBlocks) {
+            // registers 4q .. 4q+3 hold four adjacent states of channel pblk*32 + cl
+            float* hrow = state_out + ((size_t)b * a.Dn + ch0 + pblk * 32 + cl) * N + nblk * 32 + 4 * half;
+#pragma unroll
+            for (int q = 0; q < 4; q++)
+                *reinterpret_cast<float4*>(hrow + 8 * q) =
+                    make_float4(hacc[o][4 * q], hacc[o][4 * q + 1], hacc[o][4 * q + 2], hacc[o][4 * q + 3]);
+        }
+    }
+}
+
 // grid (H, 1, batch), block 4*P + 256, dynamic LDS SsdLds<N, P>::bytes().  x is read as pairs of channels: its pointer
 // must be 4-byte aligned and its strides even (the host checks).
 // The first P/16 waves are consumers: wave w owns output rows iblk*32.. and channels pblk*32.. of every chunk and N/64
@@ -268,8 +480,8 @@ __device__ __forceinline__ float wave_inclusive_sum(float v)
 // PG = 2 splits the producers into two groups of four waves: one builds the score operand and stages the tiles, the
 // other runs conv + SiLU (both run the short scan for themselves).  A producer wave's chain of dependent stages per
 // chunk is then about half as long, which is what sets the chunk period of long calls; the CU holds twelve waves.
-// PARTS compiles the time parts in (chunk range and states per blockIdx.y, the state-only mode); without it the kernel
-// walks every chunk of its item and carries none of that bookkeeping through its loops.
+// PARTS compiles the time parts in (chunk range and entry state per blockIdx.y); without it the kernel walks every
+// chunk of its item and carries none of that bookkeeping through its loops.
 template <int N, int P, bool SINGLE = false, int PG = 1, bool PARTS = false>
 __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(const SsdArgs a_in)
 {
@@ -316,15 +528,13 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
     const int ch0 = head * P;
     const size_t Lpad = (size_t)a.nchunk * kQ;
     // this workgroup's chunks [c_first, c_stop) and the states it starts from / leaves
-    const bool state_only = PARTS && a.mode == kSsdStateOnly;
     constexpr bool in_parts = PARTS;
     const int time_part = in_parts ? (int)blockIdx.y : 0;   // (`part` names the parked partial in the consumers)
     const int c_first = in_parts ? time_part * a.part_chunks : 0;
     const int c_stop = in_parts ? min(a.nchunk, c_first + a.part_chunks) : a.nchunk;
     const size_t part_elems = (size_t)gridDim.z * a.Dn * N;
-    const float* const state_in = state_only ? nullptr : in_parts ? a.part_state + time_part * part_elems : a.h_in;
-    float* const state_out = state_only ? a.part_state + time_part * part_elems
-                                        : (time_part == (in_parts ? a.parts : 1) - 1) ? a.h_out : nullptr;
+    const float* const state_in = in_parts ? a.part_state + (size_t)time_part * a.part_subs * part_elems : a.h_in;
+    float* const state_out = (time_part == (in_parts ? a.parts : 1) - 1) ? a.h_out : nullptr;
     const int last = a.L - 1;
     auto token_of = [&](int tau) { return a.dir > 0 ? tau : last - tau; };   // scan position -> token index
 
@@ -398,7 +608,7 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
             const __bf16* bsrc = a.b_t + ((((size_t)b * a.nchunk + c) * a.G + grp) * N) * kQ;
 #pragma unroll
             for (int i = 0; i < kCopy; i++) {
-                if (!state_only) ctile[i] = *reinterpret_cast<const bf16x8*>(csrc + c_src[i]);
+                ctile[i] = *reinterpret_cast<const bf16x8*>(csrc + c_src[i]);
                 btile[i] = *reinterpret_cast<const bf16x8*>(bsrc + b_src[i]);
             }
         };
@@ -434,7 +644,7 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
             }
             if (do_conv) pw_wgt[lane] = fast_exp2(l2_end - l2) * dl;
             __builtin_amdgcn_wave_barrier();
-            if (do_score && !state_only) {
+            if (do_score) {
                 // masked score operand: (B_j . C_i) exp(l_i - l_j) Delta_j for j <= i, else 0
                 float sv[kHS][4];
 #pragma unroll
@@ -533,7 +743,7 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
             if (do_score) {
 #pragma unroll
                 for (int i = 0; i < kCopy; i++) {
-                    if (!state_only) *reinterpret_cast<bf16x8*>(&sC(buf)[c_dst[i]]) = ctile[i];
+                    *reinterpret_cast<bf16x8*>(&sC(buf)[c_dst[i]]) = ctile[i];
                     *reinterpret_cast<bf16x8*>(&sBT(buf)[b_dst[i]]) = btile[i];
                 }
                 asm volatile("" ::: "memory");
@@ -543,7 +753,7 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
         };
         issue_dt(c_first);
         if (do_score) {
-            if (!state_only) issue_score(c_first);
+            issue_score(c_first);
             issue_tiles(c_first);
         }
         if (do_conv) issue_x(c_first);
@@ -562,8 +772,7 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
     // the store's full round trip, so every chunk first consumes its prefetched gate data, then stores).
     auto walk = [&](auto mode_c) {
         constexpr int kMode = decltype(mode_c)::value;
-        constexpr bool kStateOnly = kMode == kSsdStateOnly;
-        constexpr bool need_z = kMode != kSsdPartialRaw && !kStateOnly;
+        constexpr bool need_z = kMode != kSsdPartialRaw;
         constexpr bool need_p = kMode == kSsdFinalAdd || kMode == kSsdFinalAddRaw;
         constexpr bool park = kMode == kSsdPartialRaw || kMode == kSsdPartial;
         const int iblk = wave / kPB, pblk = wave % kPB;
@@ -632,9 +841,8 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
                 }
             }
         };
-        if constexpr (!kStateOnly) publish_state(0);
+        publish_state(0);
         bool state_nonzero = state_in != nullptr;
-        float decay_product = 1.0f;   // of the chunks walked (kSsdStateOnly)
         issue_gate(c_first);
         lds_barrier();
 
@@ -646,7 +854,7 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
             f32x16 y1 = {0}, y2 = {0};
 #pragma unroll
             for (int jblk = 0; jblk < 2; jblk++) {
-                if (jblk > iblk || kStateOnly) break;
+                if (jblk > iblk) break;
 #pragma unroll
                 for (int kb = 0; kb < 2; kb++) {
                     const bf16x8 am = *reinterpret_cast<const bf16x8*>(&sM(buf)[(((iblk * 2 + jblk) * 2 + kb) * 64 + lane) * 8]);
@@ -661,7 +869,7 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
                 }
             }
             // ---- inter-chunk product with the state entering the chunk
-            if (state_nonzero && !kStateOnly) {
+            if (state_nonzero) {
                 const __bf16* c_t = sC(buf);
                 const __bf16* h_t = sHT + buf * Lds::kHT;
 #pragma unroll
@@ -687,7 +895,6 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
                 const __bf16* b_t = sBT(buf);
                 const __bf16* xw_t = sXw(buf);
                 const float decay_q = el[kQ - 1];
-                decay_product *= decay_q;
 #pragma unroll
                 for (int hb = 0; hb < kHB; hb++) {
                     const int nblk = iblk * kHB + hb;
@@ -702,7 +909,7 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
                 }
             }
             // ---- epilogue: inter-chunk term, skip term, gate, combine; all 16 results first, then the stores
-            if constexpr (!kStateOnly) {
+            {
                 float res[16];
 #pragma unroll
                 for (int q = 0; q < 4; q++) {
@@ -746,12 +953,11 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
             }
             if (c + 1 < c_stop) {
                 issue_gate(c + 1);
-                if constexpr (!kStateOnly) publish_state(buf ^ 1);
+                publish_state(buf ^ 1);
             }
             state_nonzero = true;
             lds_barrier();
         }
-        if (kStateOnly && wave == 0 && lane == 0) a.part_decay[((size_t)time_part * gridDim.z + b) * a.H + head] = decay_product;
         if (state_out) {
 #pragma unroll
             for (int hb = 0; hb < kHB; hb++) {
@@ -769,9 +975,6 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
         case kSsdPartial: walk(std::integral_constant<int, kSsdPartial>{}); break;
         case kSsdPartialRaw: walk(std::integral_constant<int, kSsdPartialRaw>{}); break;
         case kSsdFinalAdd: walk(std::integral_constant<int, kSsdFinalAdd>{}); break;
-        case kSsdStateOnly:
-            if constexpr (PARTS) walk(std::integral_constant<int, kSsdStateOnly>{});
-            break;
         default: walk(std::integral_constant<int, kSsdFinalAddRaw>{}); break;
     }
 }
