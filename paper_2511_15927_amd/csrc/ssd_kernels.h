@@ -280,8 +280,7 @@ __global__ __launch_bounds__(256, 4) void ssd_state_kernel(const SsdStatePair bo
     __shared__ __attribute__((aligned(16))) __bf16 s_xw[2][P * kRowT];   // conv output times end-of-chunk weight, transposed
     __shared__ __attribute__((aligned(16))) float s_wgt[4][kQ];          // wave-private: end-of-chunk weight of each position
 
-    // (no division here: the compiler divides on the vector ALU and would then treat every argument read through
-    // the quotient as varying across the wave)
+    // (a compare, not a division by the batch size: integer division runs on the vector ALU)
     const int batch = gridDim.z >> 1;
     const int reverse = (int)blockIdx.z >= batch ? 1 : 0;
     const SsdArgs& a = both.dir[reverse];
