@@ -186,3 +186,28 @@ def test_ssd_time_parts(gpu, oracle, L, batch, N, kw):
     assert rel_l2(out, ref_b) < gpu.TOL["bf16"]
     assert rel_l2(h, h_ref) < 1e-2
     assert np.array_equal(tail, tail_ref)
+
+
+@pytest.mark.parametrize("token_stride", [1 << 24, (1 << 24) + 2])
+def test_ssd_time_parts_with_a_wide_x_stride(gpu, oracle, token_stride):
+    """x as a view with a token stride of 2^24 elements, the widest for which the state pass of the time parts may
+    address a chunk's rows with 32-bit offsets, and just beyond it, where the call runs without parts."""
+    from paper_2511_15927_amd import binding as bd
+    L = 1030
+    cfg = synth.m2_cfg(1, L, 256, headdim=64, d_state=64)
+    assert bd.bimamba_time_chunks(bd.make_desc(cfg)) > 1
+    pf, pb, inp = case(cfg, 4242)
+    ref = oracle.bimamba_fwd(cfg, to_np(pf), to_np(pb), to_np(inp))
+    desc = bd.make_desc(cfg)
+    dpf, dpb, dinp = bd.to_device(pf), bd.to_device(pb), bd.to_device(inp, cfg)
+    big = torch.empty((L - 1) * token_stride + 256, dtype=torch.bfloat16, device="cuda")
+    wide = big.as_strided((1, L, 256), (0, token_stride, 1))
+    wide.copy_(dinp["x"])
+    dinp["x"] = wide
+    out, ws = bd.alloc_out(cfg), bd.alloc_workspace(desc)
+    bd.bimamba_fwd(desc, bd.make_params(dpf), bd.make_params(dpb), bd.make_inputs(dinp), None, bd.make_tensor(out), ws)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    del big, wide, dinp
+    torch.cuda.empty_cache()
+    assert rel_l2(got, ref) < gpu.TOL["bf16"]
