@@ -431,7 +431,13 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
                 ca.parts = plan.ssd_subs;
                 launch_ssd_carry(d->d_state, ca, st);
             }
-            for (int s = 1; s >= 0; s--) launch_ssd_scan(d->d_state, d->d_inner / d->n_heads, scan_args(s), d->batch, st);
+            if (plan.ssd_chunks == 1) {
+                SsdStatePair sp;
+                for (int s = 0; s < 2; s++) sp.dir[s] = scan_args(s);
+                launch_ssd_duo(d->d_state, d->d_inner / d->n_heads, sp, d->batch, st);
+            } else {
+                for (int s = 1; s >= 0; s--) launch_ssd_scan(d->d_state, d->d_inner / d->n_heads, scan_args(s), d->batch, st);
+            }
             if (probe_stop) (void)hipEventRecord(probe_stop, st);
         } else {
         // 2. scan (summary + carry when the sequence is cut into segments) and combine

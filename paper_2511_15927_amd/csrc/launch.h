@@ -29,5 +29,6 @@ bool ssd_supported(int d_state, int headdim);
 void launch_ssd_prep(int d_state, const SsdPrepPair& pa, int nchunk, int batch, hipStream_t st);
 void launch_ssd_scan(int d_state, int headdim, const SsdArgs& sa, int batch, hipStream_t st);
 void launch_ssd_carry(int d_state, const SsdCarryArgs& ca, hipStream_t st);
+void launch_ssd_duo(int d_state, int headdim, const SsdStatePair& sp, int batch, hipStream_t st);
 void launch_ssd_state(int d_state, int headdim, const SsdStatePair& sp, int subs, int batch, hipStream_t st);
 }  // namespace bm

@@ -52,15 +52,13 @@ static void scan_variant(const SsdArgs& sa, int batch, hipStream_t st)
     hipLaunchKernelGGL(kernel, dim3((unsigned)sa.H, parts, (unsigned)batch), dim3(4 * P + 256 * GROUPS), lds, st, sa);
 }
 
-// Calls of a single chunk (block-diffusion steps) take the instantiation of which two workgroups fit a CU.  Long calls
-// that leave at least half of the CUs empty (batch 1 or 2) split the producers into two groups, which shortens the
-// per-chunk chain of each workgroup (-4 to -9 %); with the chip full the extra waves only compete for issue slots
-// (+4 to +7 %), so those keep one group.
+// Long calls that leave at least half of the CUs empty (batch 1 or 2) split the producers into two groups, which
+// shortens the per-chunk chain of each workgroup (-4 to -9 %); with the chip full the extra waves only compete for
+// issue slots (+4 to +7 %), so those keep one group.  (Calls of a single chunk go to launch_ssd_duo.)
 template <int N, int P>
 static void scan_one(const SsdArgs& sa, int batch, hipStream_t st)
 {
-    if (sa.nchunk == 1) scan_variant<N, P, true, 1, false>(sa, batch, st);
-    else if (sa.parts > 1) scan_variant<N, P, false, 1, true>(sa, batch, st);
+    if (sa.parts > 1) scan_variant<N, P, false, 1, true>(sa, batch, st);
     else if (2LL * sa.H * batch <= cu_count()) scan_variant<N, P, false, 2, false>(sa, batch, st);
     else scan_variant<N, P, false, 1, false>(sa, batch, st);
 }
@@ -79,6 +77,26 @@ void launch_ssd_carry(int d_state, const SsdCarryArgs& ca, hipStream_t st)
     const dim3 grid((unsigned)((threads + 255) / 256));
     if (d_state == 128) hipLaunchKernelGGL(ssd_carry_kernel<128>, grid, dim3(256), 0, st, ca);
     else hipLaunchKernelGGL(ssd_carry_kernel<64>, grid, dim3(256), 0, st, ca);
+}
+
+template <int N, int P>
+static void duo_one(const SsdStatePair& sp, int batch, hipStream_t st)
+{
+    static std::atomic<bool> seen[kMaxDevices];
+    constexpr size_t lds = SsdDuoLds<N, P>::bytes();
+    auto kernel = ssd_duo_kernel<N, P>;
+    if (first_use_on_current_device(seen))
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)sp.dir[0].H, 1, (unsigned)batch), dim3(4 * P + 256), lds, st, sp);
+}
+
+// A call of one chunk: both directions of every (batch, head) item in one workgroup.
+void launch_ssd_duo(int d_state, int headdim, const SsdStatePair& sp, int batch, hipStream_t st)
+{
+    if (d_state == 128 && headdim == 64) duo_one<128, 64>(sp, batch, st);
+    else if (d_state == 128 && headdim == 32) duo_one<128, 32>(sp, batch, st);
+    else if (d_state == 64 && headdim == 64) duo_one<64, 64>(sp, batch, st);
+    else if (d_state == 64 && headdim == 32) duo_one<64, 32>(sp, batch, st);
 }
 
 // Both directions in one launch; nothing to do for the sub-part scanned last (no part starts after it).

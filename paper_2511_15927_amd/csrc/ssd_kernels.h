@@ -481,11 +481,29 @@ __global__ __launch_bounds__(256, 4) void ssd_state_kernel(const SsdStatePair bo
 // chunk is then about half as long, which is what sets the chunk period of long calls; the CU holds twelve waves.
 // PARTS compiles the time parts in (chunk range and entry state per blockIdx.y); without it the kernel walks every
 // chunk of its item and carries none of that bookkeeping through its loops.
-template <int N, int P, bool SINGLE = false, int PG = 1, bool PARTS = false>
-__global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(const SsdArgs a_in)
+// DUO (single-chunk calls only): both directions of a (batch, head) item in one workgroup, see ssd_duo_kernel.
+// kDuoFirst is the direction that would park its result in global memory: it leaves it in LDS, one row per token.
+// kDuoSecond is the direction that would read the parked result back: it takes it from `parked`, which its caller
+// filled from LDS (register r: token i0 + row_k(r) of the thread's channel).
+enum { kDuoNone = 0, kDuoFirst = 1, kDuoSecond = 2 };
+
+// Where the first direction of a pair leaves its [kQ][P] fp32 result for the second: over the state operand copy
+// when that is large enough (the first direction starts from a zero state and never reads it), else behind the
+// scan tables.
+template <int N, int P>
+struct SsdDuoLds {
+    using Lds = SsdLds<N, P, true>;
+    static constexpr size_t kParkBytes = (size_t)kQ * P * sizeof(float);
+    static constexpr bool kParkOverState = (size_t)Lds::kHT * sizeof(__bf16) >= kParkBytes;
+    static constexpr size_t bytes() { return Lds::bytes() + (kParkOverState ? 0 : kParkBytes); }
+};
+
+template <int N, int P, bool SINGLE, int PG, bool PARTS, int DUO>
+__device__ __forceinline__ void ssd_walk(const SsdArgs& a_in, float (&parked)[16])
 {
     static_assert(PG == 1 || (PG == 2 && !SINGLE), "one or two producer groups; the single-chunk form keeps one");
     static_assert(!PARTS || (!SINGLE && PG == 1), "time parts come with one producer group and more than one chunk");
+    static_assert(DUO == kDuoNone || SINGLE, "both directions in one workgroup: single-chunk calls only");
     using Lds = SsdLds<N, P, SINGLE>;
     SsdArgs a = a_in;
     if (SINGLE) a.nchunk = 1;   // known at compile time: the chunk pipeline below folds away
@@ -502,6 +520,8 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
     __bf16* const tiles = reinterpret_cast<__bf16*>(ssd_lds);
     __bf16* const sHT = tiles + Lds::kBufs * Lds::kTileElems;
     float* const scal = reinterpret_cast<float*>(sHT + Lds::kBufs * Lds::kHT);   // [kBufs][kQ]: exp(l_i), decay from the chunk start
+    float* const park = SsdDuoLds<N, P>::kParkOverState ? reinterpret_cast<float*>(sHT)
+                                                        : scal + (Lds::kBufs + 3 * Lds::kScanTables) * kQ;   // DUO only
     auto sC = [&](int buf) { return tiles + buf * Lds::kTileElems; };
     auto sBT = [&](int buf) { return tiles + buf * Lds::kTileElems + Lds::kC; };
     auto sXc = [&](int buf) { return tiles + buf * Lds::kTileElems + Lds::kC + Lds::kBT; };
@@ -772,8 +792,9 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
     auto walk = [&](auto mode_c) {
         constexpr int kMode = decltype(mode_c)::value;
         constexpr bool need_z = kMode != kSsdPartialRaw;
-        constexpr bool need_p = kMode == kSsdFinalAdd || kMode == kSsdFinalAddRaw;
-        constexpr bool park = kMode == kSsdPartialRaw || kMode == kSsdPartial;
+        constexpr bool adds_parked = kMode == kSsdFinalAdd || kMode == kSsdFinalAddRaw;
+        constexpr bool need_p = adds_parked && DUO != kDuoSecond;   // read back from global memory
+        constexpr bool parks = kMode == kSsdPartialRaw || kMode == kSsdPartial;
         const int iblk = wave / kPB, pblk = wave % kPB;
         const int cl = lane & 31, half = lane >> 5;
         const int po = pblk * 32 + cl;             // this lane's channel within the head
@@ -820,6 +841,10 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
         // chunk clamps every position instead.
         T zraw[16];
         float part[16];
+        if constexpr (DUO == kDuoSecond && adds_parked) {
+#pragma unroll
+            for (int r = 0; r < 16; r++) part[r] = parked[r];
+        }
         auto issue_gate = [&](int c) {
             const int tau0 = c * kQ + i0;
             if (c * kQ + kQ - 1 <= last) {
@@ -922,7 +947,7 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
                         if constexpr (!need_z) res[r] = y;
                         else {
                             const float zg = silu(IoBF16::cvt(zraw[r]));
-                            res[r] = kMode == kSsdFinalAddRaw ? (y + part[r]) * zg : need_p ? y * zg + part[r] : y * zg;
+                            res[r] = kMode == kSsdFinalAddRaw ? (y + part[r]) * zg : adds_parked ? y * zg + part[r] : y * zg;
                         }
                     }
                 }
@@ -934,7 +959,8 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
                         T* op = obase + t0 * a.out_st;
 #pragma unroll
                         for (int r = 0; r < 16; r++) {
-                            if constexpr (park) pp[row_k(r) * pstep] = res[r];
+                            if constexpr (parks && DUO == kDuoFirst) park[((int)t0 + row_k(r) * a.dir) * P + po] = res[r];
+                            else if constexpr (parks) pp[row_k(r) * pstep] = res[r];
                             else IoBF16::st(op + row_k(r) * ostep, res[r]);
                         }
                     } else {
@@ -943,7 +969,8 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
                             const int tau = tau0 + row_k(r);
                             if (tau <= last) {
                                 const long long t = token_of(tau);
-                                if constexpr (park) pbase[t * a.Dn] = res[r];
+                                if constexpr (parks && DUO == kDuoFirst) park[(int)t * P + po] = res[r];
+                                else if constexpr (parks) pbase[t * a.Dn] = res[r];
                                 else IoBF16::st(obase + t * a.out_st, res[r]);
                             }
                         }
@@ -969,13 +996,69 @@ __global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(c
             }
         }
     };
-    switch (a.mode) {
-        case kSsdFinalOnly: walk(std::integral_constant<int, kSsdFinalOnly>{}); break;
-        case kSsdPartial: walk(std::integral_constant<int, kSsdPartial>{}); break;
-        case kSsdPartialRaw: walk(std::integral_constant<int, kSsdPartialRaw>{}); break;
-        case kSsdFinalAdd: walk(std::integral_constant<int, kSsdFinalAdd>{}); break;
-        default: walk(std::integral_constant<int, kSsdFinalAddRaw>{}); break;
+    if constexpr (DUO == kDuoFirst) {   // the direction that parks (or stores its own half of a two-part output)
+        switch (a.mode) {
+            case kSsdFinalOnly: walk(std::integral_constant<int, kSsdFinalOnly>{}); break;
+            case kSsdPartial: walk(std::integral_constant<int, kSsdPartial>{}); break;
+            default: walk(std::integral_constant<int, kSsdPartialRaw>{}); break;
+        }
+    } else if constexpr (DUO == kDuoSecond) {
+        switch (a.mode) {
+            case kSsdFinalOnly: walk(std::integral_constant<int, kSsdFinalOnly>{}); break;
+            case kSsdFinalAdd: walk(std::integral_constant<int, kSsdFinalAdd>{}); break;
+            default: walk(std::integral_constant<int, kSsdFinalAddRaw>{}); break;
+        }
+    } else {
+        switch (a.mode) {
+            case kSsdFinalOnly: walk(std::integral_constant<int, kSsdFinalOnly>{}); break;
+            case kSsdPartial: walk(std::integral_constant<int, kSsdPartial>{}); break;
+            case kSsdPartialRaw: walk(std::integral_constant<int, kSsdPartialRaw>{}); break;
+            case kSsdFinalAdd: walk(std::integral_constant<int, kSsdFinalAdd>{}); break;
+            default: walk(std::integral_constant<int, kSsdFinalAddRaw>{}); break;
+        }
     }
+}
+
+template <int N, int P, bool SINGLE = false, int PG = 1, bool PARTS = false>
+__global__ __launch_bounds__(4 * P + 256 * PG, SINGLE ? 4 : 1) void ssd_kernel(const SsdArgs a)
+{
+    float none[16];
+    ssd_walk<N, P, SINGLE, PG, PARTS, kDuoNone>(a, none);
+}
+
+// Single-chunk calls (block-diffusion steps), both directions of a (batch, head) item in one workgroup: the reverse
+// direction runs first and leaves its result in LDS instead of parking it in global memory, the forward direction
+// picks it up, so the call is one scan launch instead of two, x's rows are fetched from HBM once and the partial
+// never leaves the chip.  grid (H, 1, batch), block 4*P + 256, dynamic LDS SsdDuoLds<N, P>::bytes().  Between the
+// directions every consumer thread takes the 16 parked values of its (token, channel) places into registers, then a
+// barrier lets the forward direction overwrite the tiles and the state operand copy.
+template <int N, int P>
+__global__ __launch_bounds__(4 * P + 256, 4) void ssd_duo_kernel(const SsdStatePair both)
+{
+    using Lds = SsdLds<N, P, true>;
+    float parked[16];
+#pragma unroll
+    for (int r = 0; r < 16; r++) parked[r] = 0.0f;
+    ssd_walk<N, P, true, 1, false, kDuoFirst>(both.dir[1], parked);
+    const int tid = threadIdx.x;
+    if (tid < 4 * P && both.dir[1].mode != kSsdFinalOnly) {   // consumer waves, same places as in ssd_walk
+        extern __shared__ __attribute__((aligned(16))) unsigned char ssd_lds[];
+        __bf16* const sHT = reinterpret_cast<__bf16*>(ssd_lds) + Lds::kTileElems;
+        const float* const park = SsdDuoLds<N, P>::kParkOverState
+                                      ? reinterpret_cast<const float*>(sHT)
+                                      : reinterpret_cast<const float*>(sHT + Lds::kHT) + (1 + 3) * kQ;
+        const int wave = tid >> 6, lane = tid & 63;
+        const int iblk = wave / (P / 32), pblk = wave % (P / 32);
+        const int po = pblk * 32 + (lane & 31), i0 = iblk * 32 + 4 * (lane >> 5);
+        const int last = both.dir[0].L - 1;
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+            const int t = i0 + 8 * (r / 4) + (r % 4);
+            parked[r] = t <= last ? park[t * P + po] : 0.0f;
+        }
+    }
+    lds_barrier();
+    ssd_walk<N, P, true, 1, false, kDuoSecond>(both.dir[0], parked);
 }
 
 }  // namespace bm
