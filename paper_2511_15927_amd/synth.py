@@ -49,6 +49,7 @@ CONFIGS = {
     "cfg2_m2": m2_cfg(1, 32768, 4096),
     "cfg3_prefix": mixer_cfg(16, 4096, 4096),
     "cfg3_block": mixer_cfg(16, 32, 4096),
+    "cfg3_block_m2": m2_cfg(16, 32, 4096),
     "headline": mixer_cfg(8, 8192, 4096),
     "headline_b1": mixer_cfg(1, 8192, 4096),
     "headline_m2": m2_cfg(8, 8192, 4096),
