@@ -15,15 +15,15 @@ static bool first_use_on_current_device(std::atomic<bool>* seen)
     return !seen[dev].exchange(true);
 }
 
-template <int N>
-static void prep_one(const SsdPrepPair& pa, int nchunk, int batch, hipStream_t st)
+template <int N, int THREADS>
+static void prep_variant(const SsdPrepPair& pa, int nchunk, int batch, hipStream_t st)
 {
     static std::atomic<bool> seen[kMaxDevices];
+    constexpr size_t lds = ssd_prep_lds_bytes<N, THREADS>();
+    auto kernel = ssd_prep_kernel<N, THREADS>;
     if (first_use_on_current_device(seen))
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&ssd_prep_kernel<N>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)(ssd_prep_lds_bytes<N>()));
-    const size_t lds = ssd_prep_lds_bytes<N>();
-    hipLaunchKernelGGL((ssd_prep_kernel<N>), dim3((unsigned)nchunk, (unsigned)pa.dir[0].G, 2u * (unsigned)batch), dim3(256), lds, st, pa);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)nchunk, (unsigned)pa.dir[0].G, 2u * (unsigned)batch), dim3(THREADS), lds, st, pa);
 }
 
 static int cu_count()
@@ -65,10 +65,17 @@ static void scan_one(const SsdArgs& sa, int batch, hipStream_t st)
 
 bool ssd_supported(int d_state, int headdim) { return (d_state == 64 || d_state == 128) && (headdim == 32 || headdim == 64); }
 
+// Launches that give a CU at most one workgroup take the sixteen-wave form: their duration is one workgroup's chain.
 void launch_ssd_prep(int d_state, const SsdPrepPair& pa, int nchunk, int batch, hipStream_t st)
 {
-    if (d_state == 128) prep_one<128>(pa, nchunk, batch, st);
-    else prep_one<64>(pa, nchunk, batch, st);
+    const bool wide = 2LL * nchunk * pa.dir[0].G * batch <= cu_count();
+    if (d_state == 128) {
+        if (wide) prep_variant<128, 1024>(pa, nchunk, batch, st);
+        else prep_variant<128, 256>(pa, nchunk, batch, st);
+    } else {
+        if (wide) prep_variant<64, 1024>(pa, nchunk, batch, st);
+        else prep_variant<64, 256>(pa, nchunk, batch, st);
+    }
 }
 
 void launch_ssd_carry(int d_state, const SsdCarryArgs& ca, hipStream_t st)

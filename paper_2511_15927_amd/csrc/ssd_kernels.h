@@ -45,16 +45,22 @@ struct SsdPrepPair {
     SsdPrepArgs dir[2];   // forward, reverse: one launch prepares both
 };
 
-template <int N>
-constexpr size_t ssd_prep_lds_bytes() { return 2 * (size_t)kQ * (N + 1) * sizeof(float); }
-
-// grid (nchunk, G, 2 * batch), block 256, dynamic LDS ssd_prep_lds_bytes<N>(); blockIdx.z / batch selects the
-// direction.  Reads the raw B and C rows of one chunk
-// (plus the conv halo), applies the short conv + SiLU along the scan direction when they pass through it, and
-// keeps the fp32 result in LDS for the three outputs.
-template <int N>
-__global__ __launch_bounds__(256) void ssd_prep_kernel(const SsdPrepPair both)
+// (the wide form adds the partial score accumulators of the waves that share a block: [12][64][16] floats)
+template <int N, int THREADS>
+constexpr size_t ssd_prep_lds_bytes()
 {
+    return 2 * (size_t)kQ * (N + 1) * sizeof(float) + (THREADS > 256 ? 12 * 64 * 16 * sizeof(float) : 0);
+}
+
+// grid (nchunk, G, 2 * batch), block THREADS (256 or 1024), dynamic LDS ssd_prep_lds_bytes<N, THREADS>();
+// blockIdx.z / batch selects the direction.  Reads the raw B and C rows of one chunk
+// (plus the conv halo), applies the short conv + SiLU along the scan direction when they pass through it, and
+// keeps the fp32 result in LDS for the three outputs.  The wide form is for launches of few workgroups (block
+// calls, short sequences), whose duration is one workgroup's chain of phases: sixteen waves shorten every phase.
+template <int N, int THREADS = 256>
+__global__ __launch_bounds__(THREADS) void ssd_prep_kernel(const SsdPrepPair both)
+{
+    static_assert(THREADS == 256 || THREADS == 1024, "four or sixteen waves");
     using T = unsigned short;
     const int batch = gridDim.z / 2;
     const SsdPrepArgs& a = both.dir[blockIdx.z / batch];
@@ -64,7 +70,7 @@ __global__ __launch_bounds__(256) void ssd_prep_kernel(const SsdPrepPair both)
     const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z % batch, tid = threadIdx.x;
     const int nchunk = gridDim.x;
     {
-        constexpr int kCols = 2 * N, kParts = 256 / kCols, kLen = kQ / kParts;
+        constexpr int kCols = 2 * N, kParts = THREADS / kCols, kLen = kQ / kParts;
         const int col = tid % kCols, seg = tid / kCols;   // one column of B|C, positions seg*kLen .. of the chunk
         const int which = col / N, n = col % N;
         const TensorArg& src = which ? a.C : a.B;
@@ -116,7 +122,7 @@ __global__ __launch_bounds__(256) void ssd_prep_kernel(const SsdPrepPair both)
     __syncthreads();
     const size_t Lpad = (size_t)nchunk * kQ;
     // bf16 C rows and the transposed bf16 B tile, written as 16-byte pieces (8 states of a row, 8 positions of a state)
-    for (int idx = tid; idx < kQ * N / 8; idx += 256) {
+    for (int idx = tid; idx < kQ * N / 8; idx += THREADS) {
         const int j = idx / (N / 8), n8 = idx % (N / 8);
         const int n2 = idx / (kQ / 8), j8 = idx % (kQ / 8);
         bf16x8 cv, bv;
@@ -135,11 +141,15 @@ __global__ __launch_bounds__(256) void ssd_prep_kernel(const SsdPrepPair both)
     // i%32 = l%32: exactly the order in which the scan kernel feeds the tile to its MFMA as operand A,
     // [block pair (0,0), (1,0), (1,1)][k-block r/8][lane][r%8].
     const int wave = tid / 64, lane = tid % 64;
-    if (wave < 3) {
-        const int iblk = wave > 0, jblk = wave > 1;
+    // The wide form deals a block's N / 16 contraction steps to four waves and adds their accumulators through LDS.
+    constexpr int kSplit = THREADS > 256 ? 4 : 1;
+    constexpr int kSteps = N / 16 / kSplit;
+    const int blk = wave / kSplit, kpart = wave % kSplit;
+    f32x16 acc = {0};
+    if (blk < 3) {
+        const int iblk = blk > 0, jblk = blk > 1;
         const int rj = jblk * 32 + lane % 32, ri = iblk * 32 + lane % 32, koff = 8 * (lane / 32);
-        f32x16 acc = {0};
-        for (int ks = 0; ks < N / 16; ks++) {
+        for (int ks = kpart * kSteps; ks < (kpart + 1) * kSteps; ks++) {
             bf16x8 ah, al, bh, bl;
 #pragma unroll
             for (int e = 0; e < 8; e++) {
@@ -153,7 +163,28 @@ __global__ __launch_bounds__(256) void ssd_prep_kernel(const SsdPrepPair both)
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, acc, 0, 0, 0);
         }
-        float* dst = a.score_op + (((size_t)b * nchunk + c) * a.G + g) * kScoreOp + ((size_t)(wave * 2) * 64 + lane) * 8;
+    }
+    if constexpr (kSplit > 1) {
+        float* const sums = reinterpret_cast<float*>(sC + kQ);   // [12][64][16]
+        if (blk < 3 && kpart > 0) {
+#pragma unroll
+            for (int q = 0; q < 4; q++)
+                *reinterpret_cast<float4*>(&sums[((size_t)wave * 64 + lane) * 16 + 4 * q]) =
+                    make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+        }
+        __syncthreads();
+        if (blk < 3 && kpart == 0) {
+            for (int o = 1; o < kSplit; o++) {
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const float4 v = *reinterpret_cast<const float4*>(&sums[((size_t)(wave + o) * 64 + lane) * 16 + 4 * q]);
+                    acc[4 * q] += v.x; acc[4 * q + 1] += v.y; acc[4 * q + 2] += v.z; acc[4 * q + 3] += v.w;
+                }
+            }
+        }
+    }
+    if (blk < 3 && kpart == 0) {
+        float* dst = a.score_op + (((size_t)b * nchunk + c) * a.G + g) * kScoreOp + ((size_t)(blk * 2) * 64 + lane) * 8;
 #pragma unroll
         for (int kb = 0; kb < 2; kb++) {
             *reinterpret_cast<float4*>(dst + kb * 64 * 8) = make_float4(acc[8 * kb], acc[8 * kb + 1], acc[8 * kb + 2], acc[8 * kb + 3]);
