@@ -10,6 +10,11 @@
 // rounded to bf16.  ssd_prep_kernel builds, once per (direction, batch, chunk, group) and shared by all heads, the
 // score tile C B^T, the bf16 C rows and the transposed bf16 B tile.
 //
+// Kernels in this file: ssd_prep_kernel (above); ssd_kernel, the chunk walk of one direction (ssd_walk), with
+// variants for two producer groups and for time parts; ssd_state_kernel and ssd_carry_kernel, which find the state
+// entering each time part when a call has too few (batch, head) items to fill the chip; ssd_duo_kernel, both
+// directions of a single-chunk call (a block-diffusion step) in one workgroup.
+//
 // Lane layouts of the 32x32x16 MFMA (checked on hardware): operand A lane l holds row l%32, k = 8*(l/32)..+7;
 // operand B lane l holds column l%32, same k; accumulator register r of lane l is row 8*(r/4) + 4*(l/32) + r%4,
 // column l%32.  A contraction index may be enumerated in any order as long as both operands agree, which lets an
