@@ -1,6 +1,6 @@
 """Timing report over all benchmark configurations (tokens/s, algorithmic GB/s, fraction of HBM peak).
 
-    python -m paper_2511_15927_amd.report --out gpurun_out/report.json [--quick]
+    python -m paper_2511_15927_amd.report --out report.json [--quick]
 
 Timing only: inputs are drawn on the GPU with the recipe's distributions (parity of every configuration is the
 tests' job).  Covers the 1.3B-scale layer, the long sequence, the headline shape at batch 1 and 8 with structured and
