@@ -211,3 +211,36 @@ def test_ssd_time_parts_with_a_wide_x_stride(gpu, oracle, token_stride):
     del big, wide, dinp
     torch.cuda.empty_cache()
     assert rel_l2(got, ref) < gpu.TOL["bf16"]
+
+
+@pytest.mark.parametrize("name,batch", [("cfg2_m2", 1), ("headline_m2", 1), ("headline_m2", 2)])
+def test_ssd_time_parts_at_benchmark_size_sampled(gpu, oracle, name, batch):
+    """The time-part path (state pass over sub-parts, carry, concurrent output pass) at the benchmark's own sizes, in the
+    launch configuration the benchmark times; the oracle runs on sampled channels."""
+    from paper_2511_15927_amd import binding as bd
+    cfg = dict(synth.CONFIGS[name], batch=batch)
+    assert bd.bimamba_time_chunks(bd.make_desc(cfg)) > 1
+    pf, pb, inp = case(cfg, 1700 + batch)
+    sel = sorted(np.random.default_rng(5).choice(cfg["d_inner"], size=24, replace=False).tolist())
+    ref = oracle.bimamba_fwd(cfg, to_np(pf), to_np(pb), to_np(inp), sel=sel)
+    got = gpu.gpu_fwd(cfg, pf, pb, inp)[..., sel]
+    assert rel_l2(got, ref) < gpu.TOL["bf16"], name
+
+
+def test_ssd_block_call_at_benchmark_size_sampled(gpu, oracle):
+    """A block-diffusion step at the benchmark's size (batch 16, 32 tokens, 64 heads x 64, N 128) from a cached state and
+    conv tail: one scan launch runs both directions of every (batch, head) item; sampled channels against the oracle,
+    the committed state of those channels and the whole committed tail."""
+    cfg = synth.CONFIGS["cfg3_block_m2"]
+    pf, pb, inp = case(cfg, 1800)
+    Bt, Dn, N, K = cfg["batch"], cfg["d_inner"], cfg["d_state"], cfg["d_conv"]
+    tail_ch = synth.conv_channels(cfg)
+    g = torch.Generator().manual_seed(1801)
+    h0 = (0.2 * torch.randn(Bt, Dn, N, generator=g)).float()
+    tail0 = synth.round_io(torch.randn(Bt, K - 1, tail_ch, generator=g), cfg["io"])
+    sel = sorted(np.random.default_rng(6).choice(Dn, size=48, replace=False).tolist())
+    ref, h_ref, t_ref = oracle.bimamba_block_fwd(cfg, to_np(pf), to_np(pb), to_np(inp), h_in=h0.numpy(), tail_in=tail0.numpy(), sel=sel)
+    out, h, tail = gpu.gpu_block_fwd(cfg, pf, pb, inp, h_in=h0, tail_in=tail0)
+    assert rel_l2(out[..., sel], ref) < gpu.TOL["bf16"]
+    assert rel_l2(h[:, sel, :], h_ref[:, sel, :]) < 1e-2
+    assert np.array_equal(tail, t_ref)
