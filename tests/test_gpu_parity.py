@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import rel_l2, to_np
+from helpers import assert_close, rel_l2, to_np
 from paper_2511_15927_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -34,9 +34,7 @@ def check_fwd(gpu, oracle, cfg, seed, random_a=False, untied=False, sel=None, **
     ref = oracle.bimamba_fwd(c, to_np(pf), to_np(pb), to_np(inp), None if inp_b is None else to_np(inp_b), sel=sel)
     if sel is not None:
         got = got[..., sel]
-    err = rel_l2(got, ref)
-    assert err < gpu.TOL[c["io"]], (err, c)
-    return err
+    return assert_close(got, ref, gpu.TOL[c["io"]], c)
 
 
 def test_cfg0_tiny_fp32(gpu, oracle):
@@ -133,7 +131,7 @@ def test_strided_views_of_one_projection(gpu, oracle):
     bd.bimamba_fwd(desc, bd.make_params(dpf), bd.make_params(dpb), bd.make_inputs(views), None, bd.make_tensor(out), ws)
     torch.cuda.synchronize()
     ref = oracle.bimamba_fwd(cfg, to_np(pf), to_np(pb), to_np(inp))
-    assert rel_l2(out.float().cpu().numpy(), ref) < gpu.TOL["bf16"]
+    assert_close(out.float().cpu().numpy(), ref, gpu.TOL["bf16"])
     assert torch.all(out_big[:, :, :4] == 0) and torch.all(out_big[:, :, 4 + Dn:] == 0)
 
 
@@ -202,7 +200,7 @@ def test_cfg4_stack_teacher_forced_per_layer(gpu, oracle):
         forced = dict(np_in, x=x_gpu.float().cpu().numpy())
         ref = oracle.bimamba_fwd(cfg, to_np(pf), to_np(pb), forced, sel=sel)
         got = out.float().cpu().numpy().astype(np.float64)[:, :, sel]
-        assert rel_l2(got, ref) < gpu.TOL["bf16"], layer
+        assert_close(got, ref, gpu.TOL["bf16"], layer)
         x_gpu = out
 
 
@@ -221,11 +219,11 @@ def test_decay_progression_detected_path(gpu, oracle, N, split):
             step = -(0.125 * sign) * (1 + hidx % 3)
             p["A"] = (start[:, None] + n[None, :] * step[:, None]).contiguous()
         ref = oracle.bimamba_fwd(cfg, to_np(pf), to_np(pb), to_np(inp))
-        assert rel_l2(gpu.gpu_fwd(cfg, pf, pb, inp), ref) < gpu.TOL["bf16"]
+        assert_close(gpu.gpu_fwd(cfg, pf, pb, inp), ref, gpu.TOL["bf16"])
         pf2 = dict(pf, A=pf["A"].clone())
         pf2["A"][5, N - 1] *= 1.0 + 2.0 ** -20                  # no longer a progression: the general path must run
         ref2 = oracle.bimamba_fwd(cfg, to_np(pf2), to_np(pb), to_np(inp))
-        assert rel_l2(gpu.gpu_fwd(cfg, pf2, pb, inp), ref2) < gpu.TOL["bf16"]
+        assert_close(gpu.gpu_fwd(cfg, pf2, pb, inp), ref2, gpu.TOL["bf16"])
 
 
 def test_large_batch_shallow_tile(gpu, oracle):
@@ -247,7 +245,7 @@ def test_odd_number_of_channel_tiles(gpu, oracle, Dn, split):
     pf, pb, inp = case(cfg, 1750 + Dn)
     ref, h_ref, _ = oracle.bimamba_block_fwd(cfg, to_np(pf), to_np(pb), to_np(inp), want_tail=False)
     got, h_got, _ = gpu.gpu_block_fwd(cfg, pf, pb, inp)
-    assert rel_l2(got, ref) < gpu.TOL["f32"]
+    assert_close(got, ref, gpu.TOL["f32"])
     assert rel_l2(h_got, h_ref) < 1e-5
 
 
