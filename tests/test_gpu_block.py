@@ -229,3 +229,21 @@ def test_block_step_replayed_from_a_hip_graph(gpu, layout):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(out, want[0]) and torch.equal(h_out, want[1]) and torch.equal(tail_out, want[2]), rep
+
+
+@pytest.mark.parametrize("layout", ["selective", "mamba2"])
+def test_first_call_in_a_process_captured_into_a_graph(layout):
+    """A kernel variant's first launch in a process triggers the library's one-time queries for it; here that first
+    launch happens under stream capture (a fresh child process whose first library call is the captured one).  The
+    capture must succeed and every replay must match the oracle and an eager call."""
+    import json
+    import os
+    import subprocess
+    import sys
+    child = os.path.join(os.path.dirname(os.path.abspath(__file__)), "capture_first_use_child.py")
+    r = subprocess.run([sys.executable, child, layout], stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=300)
+    assert r.returncode == 0, r.stderr[-2000:]
+    res = json.loads(r.stdout.strip().splitlines()[-1])
+    assert res["eager_equals_replay"], res
+    for rep in res["replays"]:
+        assert rep["out"] < 2e-2 and rep["h"] < (1e-5 if layout == "selective" else 1e-2) and rep["tail_equal"], res
