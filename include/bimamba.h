@@ -64,7 +64,8 @@ enum bimamba_status {
     BIMAMBA_ERR_UNSUPPORTED = -3,         /* dtype / d_state / d_conv / grouping / token stride outside the compiled set */
     BIMAMBA_ERR_MISALIGNED = -4,          /* pointer not aligned to its element size (or 16 bytes for the workspace) */
     BIMAMBA_ERR_WORKSPACE_TOO_SMALL = -5, /* workspace_bytes < bimamba_workspace_bytes() */
-    BIMAMBA_ERR_HIP = -6                  /* a kernel launch failed (hipGetLastError) */
+    BIMAMBA_ERR_HIP = -6,                 /* a kernel launch failed (hipGetLastError) */
+    BIMAMBA_ERR_SCRATCH_EXCEEDED = -7     /* bimamba_block_fwd_static: the call needs more than BIMAMBA_STATIC_SCRATCH_BYTES */
 };
 
 enum bimamba_dtype { BIMAMBA_F32 = 0, BIMAMBA_BF16 = 1 };
@@ -156,6 +157,23 @@ int bimamba_block_fwd(const bimamba_desc* desc, const bimamba_params* pf, const 
                       const bimamba_inputs* in_f, const bimamba_inputs* in_b,
                       const float* h_in, const void* tail_in, float* h_out, void* tail_out,
                       const bimamba_tensor* out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * bimamba_block_fwd for callers that cannot allocate device memory or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical results, but
+ * the scratch is a fixed buffer of BIMAMBA_STATIC_SCRATCH_BYTES inside the library's device image (one copy per GPU,
+ * held until the process ends); the call allocates and frees nothing.  A descriptor whose
+ * bimamba_workspace_bytes(desc, 1) exceeds that size is rejected with BIMAMBA_ERR_SCRATCH_EXCEEDED before anything
+ * is launched (batch 16, d_inner 4096 fits blocks of up to 128 tokens in either layout).  All calls on one GPU share
+ * the buffer, whatever their stream: two such calls that may overlap in time on the same GPU race; order them on one
+ * stream or with events.  Nothing in the buffer has to survive from one call to the next, and nothing in it has to be
+ * cleared: every call writes what it reads.
+ */
+#define BIMAMBA_STATIC_SCRATCH_BYTES (64u << 20)
+int bimamba_block_fwd_static(const bimamba_desc* desc, const bimamba_params* pf, const bimamba_params* pb,
+                             const bimamba_inputs* in_f, const bimamba_inputs* in_b,
+                             const float* h_in, const void* tail_in, float* h_out, void* tail_out,
+                             const bimamba_tensor* out, void* hip_stream);
 
 /* Bytes of device scratch the two calls above need for this descriptor (0 on an invalid descriptor).  Pure host code. */
 size_t bimamba_workspace_bytes(const bimamba_desc* desc, int block_variant);

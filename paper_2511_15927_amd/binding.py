@@ -17,9 +17,11 @@ D_PER_CHANNEL, D_PER_HEAD = 0, 1
 COMBINE_ADD, COMBINE_SEPARATE = 0, 1
 
 STATUS = {0: "BIMAMBA_OK", -1: "BIMAMBA_ERR_NULL_POINTER", -2: "BIMAMBA_ERR_BAD_SHAPE", -3: "BIMAMBA_ERR_UNSUPPORTED",
-          -4: "BIMAMBA_ERR_MISALIGNED", -5: "BIMAMBA_ERR_WORKSPACE_TOO_SMALL", -6: "BIMAMBA_ERR_HIP"}
+          -4: "BIMAMBA_ERR_MISALIGNED", -5: "BIMAMBA_ERR_WORKSPACE_TOO_SMALL", -6: "BIMAMBA_ERR_HIP",
+          -7: "BIMAMBA_ERR_SCRATCH_EXCEEDED"}
+STATIC_SCRATCH_BYTES = 64 << 20
 
-EXPORTS = ("bimamba_fwd", "bimamba_block_fwd", "bimamba_workspace_bytes", "bimamba_time_chunks",
+EXPORTS = ("bimamba_fwd", "bimamba_block_fwd", "bimamba_block_fwd_static", "bimamba_workspace_bytes", "bimamba_time_chunks",
            "bimamba_profile_next_call", "bimamba_status_string", "bimamba_version")
 
 
@@ -66,6 +68,10 @@ def lib():
         L.bimamba_block_fwd.argtypes = [C.POINTER(Desc), C.POINTER(Params), C.POINTER(Params), C.POINTER(Inputs),
                                         C.POINTER(Inputs), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.POINTER(Tensor), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.bimamba_block_fwd_static.restype = C.c_int
+        L.bimamba_block_fwd_static.argtypes = [C.POINTER(Desc), C.POINTER(Params), C.POINTER(Params), C.POINTER(Inputs),
+                                               C.POINTER(Inputs), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                               C.POINTER(Tensor), C.c_void_p]
         L.bimamba_workspace_bytes.restype = C.c_size_t
         L.bimamba_workspace_bytes.argtypes = [C.POINTER(Desc), C.c_int]
         L.bimamba_time_chunks.restype = C.c_int
@@ -165,6 +171,16 @@ def bimamba_block_fwd(desc, pf, pb, in_f, in_b, h_in, tail_in, h_out, tail_out, 
                                  _ptr(tail_out), C.byref(out), ws_ptr, ws_bytes, _stream_ptr(stream))
     if check and rc != 0:
         raise BimambaError(rc, "bimamba_block_fwd")
+    return rc
+
+
+def bimamba_block_fwd_static(desc, pf, pb, in_f, in_b, h_in, tail_in, h_out, tail_out, out, stream=None, check=True):
+    """bimamba_block_fwd on the library's own fixed scratch buffer: no workspace argument, nothing allocated."""
+    rc = lib().bimamba_block_fwd_static(C.byref(desc), C.byref(pf), C.byref(pb), C.byref(in_f),
+                                        None if in_b is None else C.byref(in_b), _ptr(h_in), _ptr(tail_in), _ptr(h_out),
+                                        _ptr(tail_out), C.byref(out), _stream_ptr(stream))
+    if check and rc != 0:
+        raise BimambaError(rc, "bimamba_block_fwd_static")
     return rc
 
 

@@ -6,6 +6,13 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
+// Device memory of bimamba_block_fwd_static, the entry point for callers that cannot allocate: one copy per GPU, held
+// until the process ends.  In host code this name only identifies the symbol; the address a kernel can use is asked
+// from the runtime once per device (static_scratch below).
+static __device__ __align__(256) unsigned char scratch[BIMAMBA_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using namespace bm;
@@ -495,6 +502,23 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
     return hipGetLastError() == hipSuccess ? BIMAMBA_OK : BIMAMBA_ERR_HIP;
 }
 
+constexpr int kMaxScratchDevices = 64;
+std::atomic<void*> g_scratch_addr[kMaxScratchDevices];   // per device: each GPU holds its own copy of the array
+
+// The current device's copy of `scratch`, asked once per device with that device current.
+int static_scratch(void** addr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxScratchDevices) return BIMAMBA_ERR_HIP;
+    void* p = g_scratch_addr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return BIMAMBA_ERR_HIP;
+        g_scratch_addr[dev].store(p, std::memory_order_release);
+    }
+    *addr = p;
+    return BIMAMBA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -513,6 +537,20 @@ int bimamba_block_fwd(const bimamba_desc* desc, const bimamba_params* pf, const 
                       void* hip_stream)
 {
     return run(desc, pf, pb, in_f, in_b, h_in, tail_in, h_out, tail_out, out, workspace, workspace_bytes, hip_stream,
+               true);
+}
+
+int bimamba_block_fwd_static(const bimamba_desc* desc, const bimamba_params* pf, const bimamba_params* pb,
+                             const bimamba_inputs* in_f, const bimamba_inputs* in_b, const float* h_in,
+                             const void* tail_in, float* h_out, void* tail_out, const bimamba_tensor* out,
+                             void* hip_stream)
+{
+    int rc = check_desc(desc);
+    if (rc) return rc;
+    if (make_plan(desc, false).total > (size_t)BIMAMBA_STATIC_SCRATCH_BYTES) return BIMAMBA_ERR_SCRATCH_EXCEEDED;
+    void* ws = nullptr;
+    if ((rc = static_scratch(&ws))) return rc;
+    return run(desc, pf, pb, in_f, in_b, h_in, tail_in, h_out, tail_out, out, ws, BIMAMBA_STATIC_SCRATCH_BYTES, hip_stream,
                true);
 }
 
@@ -547,6 +585,7 @@ const char* bimamba_status_string(int status)
         case BIMAMBA_ERR_MISALIGNED: return "misaligned pointer";
         case BIMAMBA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case BIMAMBA_ERR_HIP: return "HIP launch error";
+        case BIMAMBA_ERR_SCRATCH_EXCEEDED: return "the call needs more scratch than the library's static buffer holds";
         default: return "unknown status";
     }
 }
