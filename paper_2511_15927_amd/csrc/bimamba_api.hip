@@ -7,6 +7,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <cstdlib>
 
 // Device memory of bimamba_block_fwd_static, the entry point for callers that cannot allocate: one copy per GPU, held
 // until the process ends.  In host code this name only identifies the symbol; the address a kernel can use is asked
@@ -421,6 +422,12 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
                                    : s == 1 ? (raw ? kSsdPartialRaw : kSsdPartial) : (raw ? kSsdFinalAddRaw : kSsdFinalAdd);
                 sa.out_ch_off = separate ? s * d->d_inner : 0;
                 sa.dt_softplus = d->dt_softplus; sa.d_per_head = d->d_kind == BIMAMBA_D_PER_HEAD;
+                // calls of several chunks that need no time parts walk sixteen waves wide (the row offsets of a chunk's
+                // gate / output rows are 32-bit there) unless BIMAMBA_NO_WIDE is set
+                constexpr int64_t kMaxWideStride = 1 << 24;
+                sa.wide = plan.ssd_parts == 1 && plan.ssd_chunks >= 2 && in_f->z.stride_token <= kMaxWideStride &&
+                          in_b->z.stride_token <= kMaxWideStride && out->stride_token <= kMaxWideStride &&
+                          !getenv("BIMAMBA_NO_WIDE");
                 return sa;
             };
             if (plan.ssd_parts > 1) {

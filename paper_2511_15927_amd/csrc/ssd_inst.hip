@@ -1,5 +1,6 @@
 // Instantiations and launchers of the chunked Mamba-2 kernels (d_state in {64, 128}, head width in {32, 64}).
 #include "ssd_kernels.h"
+#include "ssd_wide.h"
 #include "launch.h"
 
 #include <atomic>
@@ -52,13 +53,25 @@ static void scan_variant(const SsdArgs& sa, int batch, hipStream_t st)
     hipLaunchKernelGGL(kernel, dim3((unsigned)sa.H, parts, (unsigned)batch), dim3(4 * P + 256 * GROUPS), lds, st, sa);
 }
 
+template <int N, int P>
+static void wide_variant(const SsdArgs& sa, int batch, hipStream_t st)
+{
+    static std::atomic<bool> seen[kMaxDevices];
+    constexpr size_t lds = SsdLds<N, P, false>::bytes();
+    auto kernel = ssd_wide_kernel<N, P>;
+    if (first_use_on_current_device(seen))
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)sa.H, 1, (unsigned)batch), dim3(SsdWide<N, P>::kThreads), lds, st, sa);
+}
+
 // Long calls that leave at least half of the CUs empty (batch 1 or 2) split the producers into two groups, which
 // shortens the per-chunk chain of each workgroup (-4 to -9 %); with the chip full the extra waves only compete for
 // issue slots (+4 to +7 %), so those keep one group.  (Calls of a single chunk go to launch_ssd_duo.)
 template <int N, int P>
 static void scan_one(const SsdArgs& sa, int batch, hipStream_t st)
 {
-    if (sa.parts > 1) scan_variant<N, P, false, 1, true>(sa, batch, st);
+    if (sa.wide) wide_variant<N, P>(sa, batch, st);
+    else if (sa.parts > 1) scan_variant<N, P, false, 1, true>(sa, batch, st);
     else if (2LL * sa.H * batch <= cu_count()) scan_variant<N, P, false, 2, false>(sa, batch, st);
     else scan_variant<N, P, false, 1, false>(sa, batch, st);
 }

@@ -215,6 +215,7 @@ struct SsdArgs {
     const void* tail_in;  // bf16 [batch][K-1][tail_ch] or null (causal direction only)
     int L, Dn, H, HG, G, K, tail_ch, nchunk;
     int dir, mode, out_ch_off, dt_softplus, d_per_head;
+    int wide;             // run on ssd_wide_kernel (ssd_wide.h): both directions of a call agree, the parked result is bf16
     // Time parts (calls with too few (batch, head) items to fill the chip): the chunks are dealt to `parts` workgroups
     // per item, part_chunks each, in scan order (blockIdx.y).  A part is part_subs sub-parts of sub_chunks chunks;
     // ssd_state_kernel leaves every sub-part's end state from a zero start and the product of its chunk decays (all
