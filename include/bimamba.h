@@ -12,16 +12,24 @@
  *   h_t[n]    = exp(Delta[t,h] * A_s[h,n]) * h_prev[n] + Delta[t,h] * B_s[t,g,n] * xc_s[t,d]     eq. 4 (t = 0..L-1) / eq. 5 (t = L-1..0)
  *   y_s[t,d]  = sum_n C_s[t,g,n] * h_t[n] + D_s[d] * xc_s[t,d]
  *   g_s[t,d]  = y_s[t,d] * SiLU(z_s[t,d])
- *   out[t,d]  = g_f[t,d] + g_b[t,d]                                                 eq. 6 (BIMAMBA_COMBINE_ADD)
+ *   out[t,d]  = g_f[t,d] + g_b[t,d]                                                 (BIMAMBA_COMBINE_ADD)
  *   out[t,:]  = [g_f[t,:] | g_b[t,:]]                                               (BIMAMBA_COMBINE_SEPARATE, width 2*d_inner)
+ *
+ * Eq. 6 adds the two layers' outputs, i.e. after each direction's own output projection.  COMBINE_ADD is that sum only
+ * when both directions share one output projection; with untied projections (the paper's setting) use COMBINE_SEPARATE
+ * and multiply [g_f | g_b] by the two projection matrices stacked, which realises eq. 6 exactly.
  *
  * With conv_bc = 1 (the Mamba-2 form) B and C pass through the same conv + SiLU as x, using rows
  * d_inner .. d_inner+2*n_groups*d_state-1 of conv_w / conv_b (channel order x | B | C).
  *
- * Memory: every pointer is device memory owned by the caller unless marked "host".  The library
- * allocates nothing, keeps no pointer after a call returns and has no global state (bimamba_profile_next_call
- * excepted).  Activations are
- * token-major with the channel dimension contiguous; batch and token strides are given in elements.
+ * Memory: every pointer is device memory owned by the caller unless marked "host".  The library allocates nothing and
+ * keeps no pointer after a call returns.  What it does keep, per process: per-device caches of launch geometry (the
+ * device's CU count, and per kernel variant its occupancy and static LDS), filled the first time a variant is launched
+ * on a device, when the library also queries that kernel's attributes and raises its dynamic-LDS limit; the one-shot
+ * event pair of bimamba_profile_next_call (per host thread); and the fixed scratch buffer of
+ * bimamba_block_fwd_static.  The first-use queries enqueue nothing and are safe under stream capture (a test captures
+ * a variant's very first launch).  Activations are token-major with the channel dimension contiguous; batch and token
+ * strides are given in elements.
  *
  * Arithmetic: state, decay factors, gate and the sum of eq. 6 are fp32; bf16 I/O is widened on load and rounded
  * to nearest-even once at the final store.  Two kernel families implement the same formulas:
@@ -64,8 +72,10 @@ enum bimamba_status {
     BIMAMBA_ERR_UNSUPPORTED = -3,         /* dtype / d_state / d_conv / grouping / token stride outside the compiled set */
     BIMAMBA_ERR_MISALIGNED = -4,          /* pointer not aligned to its element size (or 16 bytes for the workspace) */
     BIMAMBA_ERR_WORKSPACE_TOO_SMALL = -5, /* workspace_bytes < bimamba_workspace_bytes() */
-    BIMAMBA_ERR_HIP = -6,                 /* a kernel launch failed (hipGetLastError) */
-    BIMAMBA_ERR_SCRATCH_EXCEEDED = -7     /* bimamba_block_fwd_static: the call needs more than BIMAMBA_STATIC_SCRATCH_BYTES */
+    BIMAMBA_ERR_HIP = -6,                 /* a launch of this call failed (errors pending from earlier, unrelated calls are
+                                             neither reported nor cleared) */
+    BIMAMBA_ERR_SCRATCH_EXCEEDED = -7,    /* bimamba_block_fwd_static: the call needs more than BIMAMBA_STATIC_SCRATCH_BYTES */
+    BIMAMBA_ERR_ALIAS = -8                /* out may overlap an input view (checked on the host) */
 };
 
 enum bimamba_dtype { BIMAMBA_F32 = 0, BIMAMBA_BF16 = 1 };
@@ -132,7 +142,9 @@ typedef struct bimamba_inputs {
  * Full-sequence bidirectional mixer path (eqs. 4-6).
  *   desc        host.  pf, pb: host structs of device pointers; pb may equal pf (tied weights).
  *   in_f, in_b  host structs; in_b == NULL or in_b == in_f means both directions read the same activations.
- *   out         [batch, L, d_inner] (ADD) or [batch, L, 2*d_inner] (SEPARATE), io_dtype; must not alias an input.
+ *   out         [batch, L, d_inner] (ADD) or [batch, L, 2*d_inner] (SEPARATE), io_dtype.  It must not overlap any input
+ *               view (BIMAMBA_ERR_ALIAS): byte ranges apart, or, inside one buffer, the same strides (batch stride a
+ *               multiple of the token stride) and column ranges apart modulo the token stride.
  *   workspace   device scratch of at least bimamba_workspace_bytes(desc, 0) bytes, 16-byte aligned (may be NULL if 0).
  *   hip_stream  a hipStream_t (NULL = the default stream).
  */

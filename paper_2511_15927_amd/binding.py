@@ -18,7 +18,7 @@ COMBINE_ADD, COMBINE_SEPARATE = 0, 1
 
 STATUS = {0: "BIMAMBA_OK", -1: "BIMAMBA_ERR_NULL_POINTER", -2: "BIMAMBA_ERR_BAD_SHAPE", -3: "BIMAMBA_ERR_UNSUPPORTED",
           -4: "BIMAMBA_ERR_MISALIGNED", -5: "BIMAMBA_ERR_WORKSPACE_TOO_SMALL", -6: "BIMAMBA_ERR_HIP",
-          -7: "BIMAMBA_ERR_SCRATCH_EXCEEDED"}
+          -7: "BIMAMBA_ERR_SCRATCH_EXCEEDED", -8: "BIMAMBA_ERR_ALIAS"}
 STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = ("bimamba_fwd", "bimamba_block_fwd", "bimamba_block_fwd_static", "bimamba_workspace_bytes", "bimamba_time_chunks",

@@ -20,9 +20,62 @@ using namespace bm;
 
 thread_local hipEvent_t g_probe_start = nullptr, g_probe_stop = nullptr;  // one-shot, see bimamba_profile_next_call
 
-constexpr int kTargetWaves = 2048;  // two waves per SIMD on 256 CUs x 4 SIMDs
+}  // namespace
+
+namespace bm {
+int cu_count()
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int> cached[kMaxDevices];
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) {
+        cus = cached[dev].load(std::memory_order_relaxed);
+        if (cus == 0) {
+            if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+            cached[dev].store(cus, std::memory_order_relaxed);
+        }
+    }
+    return cus;   // no device (a host-only query): plan for the 256-CU chip
+}
+}  // namespace bm
+
+namespace {
+
+// Launch geometry is planned for the SIMDs the device has (four per CU); the thresholds below were measured on MI355X
+// (256 CUs, 1024 SIMDs).
+inline int simds() { return 4 * cu_count(); }
+inline int target_waves() { return 2 * simds(); }   // two waves per SIMD
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Byte range [lo, hi) a tensor view spans (non-negative strides, checked before this is used).
+struct Span {
+    uintptr_t lo, hi;
+};
+Span span_of(const bimamba_tensor& t, int channels, size_t elem, const bimamba_desc* d)
+{
+    const uintptr_t lo = reinterpret_cast<uintptr_t>(t.ptr);
+    const int64_t last = (int64_t)(d->batch - 1) * t.stride_batch + (int64_t)(d->seqlen - 1) * t.stride_token + channels;
+    return Span{lo, lo + (uintptr_t)last * elem};
+}
+
+// Whether writing `out` could touch memory an input view reads.  Views whose byte ranges are apart never do; views
+// that interleave inside one buffer (column slices of one projection output, the usual layout) do not either when
+// they share both strides, rows tile the batch stride, and their column ranges are apart modulo the row pitch.
+bool may_overlap(const bimamba_tensor& out, int out_ch, const bimamba_tensor& in, int in_ch, size_t elem,
+                 const bimamba_desc* d)
+{
+    const Span a = span_of(out, out_ch, elem, d), b = span_of(in, in_ch, elem, d);
+    if (a.hi <= b.lo || b.hi <= a.lo) return false;
+    if (out.stride_token == in.stride_token && out.stride_batch == in.stride_batch && out.stride_token > 0 &&
+        out.stride_batch % out.stride_token == 0) {
+        const int64_t pitch = out.stride_token;
+        const int64_t delta = ((int64_t)a.lo - (int64_t)b.lo) / (int64_t)elem;
+        const int64_t r = ((delta % pitch) + pitch) % pitch;   // out's first column, counted from in's first column
+        if (r >= in_ch && r + out_ch <= pitch) return false;
+    }
+    return true;
+}
 inline bool is_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 __global__ __launch_bounds__(256) void zero_fill_kernel(float* p, long long n)
@@ -88,7 +141,6 @@ long long waves_of(const bimamba_desc* d, int split)
 // chain) and cut the sequence only as far as two waves per SIMD need, in segments of at least 256 tokens.
 constexpr int kWavesForSegments = 16384;
 constexpr int kMinSegmentTokens = 128;
-constexpr int kSimds = 1024;
 
 bool many_states(const bimamba_desc* d) { return d->d_state > 32; }
 
@@ -96,9 +148,9 @@ int segments_for(const bimamba_desc* d, long long waves)
 {
     const int L = d->seqlen;
     if (L <= 0 || waves <= 0) return 1;
-    const int want = many_states(d) ? kTargetWaves : kWavesForSegments;
+    const int want = many_states(d) ? target_waves() : kWavesForSegments;
     long long min_tokens = 256;
-    if (!many_states(d) && waves * (L / 256) < 4 * kSimds) min_tokens = kMinSegmentTokens;
+    if (!many_states(d) && waves * (L / 256) < 4 * simds()) min_tokens = kMinSegmentTokens;
     long long n = (want + waves - 1) / waves;
     const long long max_by_len = L / min_tokens > 0 ? L / min_tokens : 1;
     if (n > max_by_len) n = max_by_len;
@@ -108,12 +160,12 @@ int segments_for(const bimamba_desc* d, long long waves)
 // Two lanes per chain fill the SIMDs well in one round of resident waves.
 bool two_lanes_fit(long long w)
 {
-    const long long per_simd_x100 = 2 * w * 100 / kSimds;
+    const long long per_simd_x100 = 2 * w * 100 / simds();
     return (per_simd_x100 >= 180 && per_simd_x100 <= 200) || (per_simd_x100 >= 235 && per_simd_x100 <= 300);
 }
 
 // One lane per chain needs no help from segments or lane splitting.
-bool enough_chains(const bimamba_desc* d, long long w) { return many_states(d) ? w >= kTargetWaves : 8 * w >= 15 * kSimds; }
+bool enough_chains(const bimamba_desc* d, long long w) { return many_states(d) ? w >= target_waves() : 8 * w >= 15 * simds(); }
 
 int pick_split(const bimamba_desc* d)
 {
@@ -121,9 +173,9 @@ int pick_split(const bimamba_desc* d)
     const long long w = waves_of(d, 1);
     if (enough_chains(d, w)) return 1;
     const bool two = split_supported(d->d_state, 2), four = d->d_state >= 64 && split_supported(d->d_state, 4);
-    if (many_states(d)) return w >= kTargetWaves / 2 && two ? 2 : four ? 4 : two ? 2 : 1;
+    if (many_states(d)) return w >= target_waves() / 2 && two ? 2 : four ? 4 : two ? 2 : 1;
     if (two && two_lanes_fit(w)) return 2;
-    if (d->time_chunks == 0 && w * segments_for(d, w) >= kTargetWaves) return 1;
+    if (d->time_chunks == 0 && w * segments_for(d, w) >= target_waves()) return 1;
     return two ? 2 : 1;
 }
 
@@ -139,7 +191,7 @@ int pick_chunks(const bimamba_desc* d, int split)
         const long long w = waves_of(d, 1);
         const bool whole = d->state_split == 0 && !many_states(d) &&
                            (split == 1 ? enough_chains(d, w) : split == 2 && two_lanes_fit(w));
-        n = waves >= kTargetWaves || whole ? 1 : segments_for(d, waves);
+        n = waves >= target_waves() || whole ? 1 : segments_for(d, waves);
     }
     if (n > L) n = L;
     if (n > 4096) n = 4096;
@@ -199,12 +251,13 @@ Plan make_plan(const bimamba_desc* d, bool inputs_shared)
     p.ssd_part_chunks = p.ssd_sub_chunks = p.ssd_chunks;
     if (p.ssd) {
         const long long items = (long long)d->n_heads * d->batch;
-        long long parts = items > 0 ? 256 / items : 1;
+        const int cus = cu_count();
+        long long parts = items > 0 ? cus / items : 1;
         if (parts > p.ssd_chunks / 8) parts = p.ssd_chunks / 8;
         if (parts > 16) parts = 16;
         if (parts >= 2) {
             const int part_chunks = (int)((p.ssd_chunks + parts - 1) / parts);
-            const long long subs_wanted = (4 * 256 + 2 * items - 1) / (2 * items);
+            const long long subs_wanted = (4LL * cus + 2 * items - 1) / (2 * items);
             long long k = (subs_wanted + parts - 1) / parts;
             if (k > part_chunks / 4) k = part_chunks / 4;
             if (k < 1) k = 1;
@@ -350,6 +403,16 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
         if (!is_aligned(workspace, 16)) return BIMAMBA_ERR_MISALIGNED;
         if (workspace_bytes < plan.total) return BIMAMBA_ERR_WORKSPACE_TOO_SMALL;
     }
+    if (d->batch > 0 && d->seqlen > 0) {
+        const int gn = d->n_groups * d->d_state;
+        for (const bimamba_inputs* in : {in_f, in_b}) {
+            if (may_overlap(*out, out_ch, in->x, d->d_inner, elem, d) || may_overlap(*out, out_ch, in->z, d->d_inner, elem, d) ||
+                may_overlap(*out, out_ch, in->dt, d->n_heads, elem, d) || may_overlap(*out, out_ch, in->B, gn, elem, d) ||
+                may_overlap(*out, out_ch, in->C, gn, elem, d))
+                return BIMAMBA_ERR_ALIAS;
+        }
+    }
+    const hipError_t pending = hipPeekAtLastError();   // an error some earlier, unrelated call left behind is not ours to report or clear
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     const int GN = d->n_groups * d->d_state;
     const int tail_ch = d->d_inner + (d->conv_bc ? 2 * GN : 0);
@@ -506,7 +569,8 @@ int run(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* p
         if (d->io_dtype == BIMAMBA_BF16) hipLaunchKernelGGL(tail_kernel<IoBF16>, grid, dim3(256), 0, st, ta);
         else hipLaunchKernelGGL(tail_kernel<IoF32>, grid, dim3(256), 0, st, ta);
     }
-    return hipGetLastError() == hipSuccess ? BIMAMBA_OK : BIMAMBA_ERR_HIP;
+    const hipError_t now = hipPeekAtLastError();
+    return now == hipSuccess || now == pending ? BIMAMBA_OK : BIMAMBA_ERR_HIP;
 }
 
 constexpr int kMaxScratchDevices = 64;
@@ -592,6 +656,7 @@ const char* bimamba_status_string(int status)
         case BIMAMBA_ERR_MISALIGNED: return "misaligned pointer";
         case BIMAMBA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case BIMAMBA_ERR_HIP: return "HIP launch error";
+        case BIMAMBA_ERR_ALIAS: return "the output overlaps an input";
         case BIMAMBA_ERR_SCRATCH_EXCEEDED: return "the call needs more scratch than the library's static buffer holds";
         default: return "unknown status";
     }

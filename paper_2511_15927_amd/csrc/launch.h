@@ -3,6 +3,10 @@
 #include "kernels.h"
 
 namespace bm {
+// Compute units of the current device (256 when no device answers), asked once per device; defined in bimamba_api.hip
+// and used by the host-side plan and by every launcher, so that all of them size a launch for the same chip.
+int cu_count();
+
 #define BM_DECLARE_SCAN(n, s)                                                                                      \
     void launch_scan_n##n##_s##s(int a_scalar_per_head, int io_bf16, const SweepArgs& sa, const CarryArgs& ca,     \
                                  int batch, int short_call, hipStream_t st, hipEvent_t ev_start,                   \

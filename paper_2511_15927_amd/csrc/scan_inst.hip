@@ -54,21 +54,6 @@ struct KernelFit {
     }
 };
 
-static int cu_count()
-{
-    static std::atomic<int> cached[kMaxDevices];
-    const int dev = current_device();
-    int cus = 256;
-    if (dev >= 0) {
-        cus = cached[dev].load(std::memory_order_relaxed);
-        if (cus == 0) {
-            if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
-            cached[dev].store(cus, std::memory_order_relaxed);
-        }
-    }
-    return cus;
-}
-
 static long long workgroups_per_cu(const dim3& grid)
 {
     const long long cus = cu_count();

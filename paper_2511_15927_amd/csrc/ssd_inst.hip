@@ -27,20 +27,6 @@ static void prep_variant(const SsdPrepPair& pa, int nchunk, int batch, hipStream
     hipLaunchKernelGGL(kernel, dim3((unsigned)nchunk, (unsigned)pa.dir[0].G, 2u * (unsigned)batch), dim3(THREADS), lds, st, pa);
 }
 
-static int cu_count()
-{
-    static std::atomic<int> cached[kMaxDevices];
-    int dev = 0, cus = 256;
-    if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) {
-        cus = cached[dev].load(std::memory_order_relaxed);
-        if (cus == 0) {
-            if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
-            cached[dev].store(cus, std::memory_order_relaxed);
-        }
-    }
-    return cus;
-}
-
 template <int N, int P, bool SINGLE, int GROUPS, bool PARTS>
 static void scan_variant(const SsdArgs& sa, int batch, hipStream_t st)
 {

@@ -255,3 +255,33 @@ def test_launch_geometries_of_the_batch_sweep(gpu, oracle, batch, L):
     one lane per chain from 1.5 waves per SIMD, more than one round of workgroups (no turns), sampled channels."""
     cfg = synth.mixer_cfg(batch, L, 4096)
     check_fwd(gpu, oracle, cfg, 1800 + batch, sel=sampled(16, 4096, batch))
+
+
+def test_output_as_a_column_slice_of_the_inputs_buffer(gpu, oracle):
+    """out may live in the same buffer as the inputs as long as its columns stay apart from theirs (same strides): the
+    host's overlap check accepts it and no input column is disturbed; an out that runs into z is refused."""
+    from paper_2511_15927_amd import binding as bd
+    cfg = synth.mixer_cfg(2, 45, 96, io="bf16")
+    pf, pb, inp = case(cfg, 710)
+    Dn, N = 96, 16
+    widths = dict(z=Dn, x=Dn, B=N, C=N, dt=Dn, out=Dn)
+    pitch = sum(widths.values()) + 8
+    big = torch.zeros(2, 45, pitch, dtype=torch.bfloat16, device="cuda")
+    views, off = {}, 0
+    for k in ("z", "x", "B", "C", "dt", "out"):
+        views[k] = big[:, :, off:off + widths[k]]
+        if k != "out":
+            views[k].copy_(inp[k].reshape(2, 45, -1).to(torch.bfloat16))
+        off += widths[k]
+    before = big.clone()
+    desc = bd.make_desc(cfg)
+    dpf, dpb, ws = bd.to_device(pf), bd.to_device(pb), bd.alloc_workspace(desc)
+    args = (desc, bd.make_params(dpf), bd.make_params(dpb), bd.make_inputs(views), None)
+    bd.bimamba_fwd(*args, bd.make_tensor(views["out"]), ws)
+    torch.cuda.synchronize()
+    ref = oracle.bimamba_fwd(cfg, to_np(pf), to_np(pb), to_np(inp))
+    assert_close(views["out"].float().cpu().numpy(), ref, gpu.TOL["bf16"])
+    keep = [c for c in range(pitch) if not (off - Dn <= c < off)]
+    assert torch.equal(big[:, :, keep], before[:, :, keep])
+    clash = big[:, :, Dn // 2:Dn // 2 + Dn]                       # straddles z and x
+    assert bd.bimamba_fwd(*args, bd.make_tensor(clash), ws, check=False) == -8
