@@ -12,8 +12,9 @@ import os
 
 import numpy as np
 
-from .build import LIB
+from .build import LIB, LIB_UBSAN
 from .build import build as build_lib
+from .build import build_sanitized
 
 _lib = None
 
@@ -35,9 +36,12 @@ class Inputs(C.Structure):
 def lib():
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB):
+        path = LIB
+        if os.environ.get("BIMAMBA_ORACLE_UBSAN"):     # the pins under the undefined-behaviour sanitizer (tests only)
+            path = build_sanitized()[0]
+        elif not os.path.exists(LIB):
             build_lib()
-        _lib = C.CDLL(LIB)
+        _lib = C.CDLL(path)
         _lib.orc_bimamba_fwd.restype = C.c_int
         _lib.orc_bimamba_block_fwd.restype = C.c_int
         _lib.orc_one_direction.restype = C.c_int
