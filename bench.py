@@ -31,42 +31,135 @@ def parse():
     ap.add_argument("--no-general-a", action="store_true",
                     help="skip the structure-free-A comparison leg (profiling runs: it launches the same kernel)")
     ap.add_argument("--cpu-batches", type=int, default=2, help="batch elements the oracle is timed on")
+    ap.add_argument("--layers", type=int, default=24, help="cfg3_block*: mixer layers in the decode loop")
+    ap.add_argument("--denoise-steps", type=int, default=8, help="cfg3_block*: denoising steps per block")
+    ap.add_argument("--block", type=int, default=32, help="cfg3_block*: block length G (32, 64 or 128)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run three 1 GiB device-to-device copies (a known-size reference for HBM counters)")
     return ap.parse_args()
 
 
-def read_counters(kernel_key):
-    """Counters of the dominant kernel from the committed rocprofv3 --pmc summary, if there is one."""
+def read_profile(kernel_key):
+    """The committed rocprofv3 --pmc summary of this workload's dominant kernel (profiles/<key>_pmc.txt, written by
+    paper_2511_15927_amd.profile_summary): counters as floats, plus the kernel name and the file the values come from.
+    These are STORED values of an earlier run of this same command, not measurements of the present run."""
     path = os.path.join(ROOT, "profiles", kernel_key + "_pmc.txt")
-    vals = {}
+    vals, kernel = {}, None
     try:
         for line in open(path):
-            if "=" in line and not line.lstrip().startswith("#"):
+            if line.startswith("# kernel:"):
+                kernel = line.split(":", 1)[1].strip()
+            elif "=" in line and not line.lstrip().startswith("#"):
                 k, v = line.split("=", 1)
                 vals[k.strip()] = float(v.strip())
     except Exception:
-        return {}
-    return vals
+        return {}, None, None
+    return vals, kernel, os.path.relpath(path, ROOT)
 
 
-def read_traffic(kernel_key):
-    """HBM bytes per launch of the dominant kernel (fetch + write, each scaled by the copy calibration)."""
-    c = read_counters(kernel_key)
+def traffic_of(c, launches):
+    """HBM bytes per step of the dominant kernel (fetch + write, each scaled by the copy calibration)."""
     try:
-        return c["FETCH_BYTES_PER_LAUNCH"] + c["WRITE_BYTES_PER_LAUNCH"]
+        return launches * (c["FETCH_BYTES_PER_LAUNCH"] + c["WRITE_BYTES_PER_LAUNCH"])
     except KeyError:
         return None
 
 
-def read_valu_busy(kernel_key, waves_per_simd):
+def valu_busy_of(c, simds):
     """Fraction of SIMD time with a vector-ALU instruction executing: per-wave VALU-active cycles over per-wave
-    resident cycles, times the waves that share a SIMD."""
-    c = read_counters(kernel_key)
+    resident cycles, times the waves that share a SIMD (the launch's waves over the chip's SIMDs when they are all
+    resident at once, which holds for the profiled launches)."""
     try:
-        return min(1.0, waves_per_simd * c["SQ_ACTIVE_INST_VALU"] / c["SQ_WAVE_CYCLES"])
+        waves_per_simd = c["SQ_WAVES"] / simds
+        return min(1.0, waves_per_simd * c["SQ_ACTIVE_INST_VALU"] / c["SQ_WAVE_CYCLES"]), waves_per_simd
     except (KeyError, ZeroDivisionError):
-        return None
+        return None, None
+
+
+def copy_ceiling_gbps(torch):
+    """Read + write rate of a plain 1 GiB device-to-device copy, measured now (the achievable HBM ceiling on this machine)."""
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    return 5 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
+def decode_loop_bench(args, torch, bd, shapes, synth):
+    """Block-diffusion decode loop (Sec. 4.3): one step of this benchmark is one block of G tokens taken through
+    --denoise-steps steps x --layers mixer layers (that many bimamba_block_fwd calls, the last step committing every
+    layer's cache), replayed from a HIP graph captured once."""
+    from paper_2511_15927_amd.decode import BlockDecodeLoop
+    cfg = dict(synth.CONFIGS[args.workload], seqlen=args.block)
+    seed = synth.config_seed(3)
+    params = [(synth.make_params(cfg, seed + l, 0), synth.make_params(cfg, seed + l, 1)) for l in range(args.layers)]
+    loop = BlockDecodeLoop(cfg, params, args.denoise_steps)
+    for s in range(args.denoise_steps):
+        loop.set_step_inputs(s, synth.make_inputs(cfg, seed + 100 + s))
+    g = torch.Generator().manual_seed(seed)
+    for h in loop.h:
+        h.copy_(0.2 * torch.randn(h.shape, generator=g))
+    loop.capture()
+    calls = args.layers * args.denoise_steps
+
+    def timed(fn, n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    for _ in range(args.warmup):
+        loop.run_block()
+    block_s = timed(loop.run_block, args.steps)
+    eager_s = timed(loop.run_block_eager, max(1, args.steps // 4))
+    tokens_per_call = cfg["batch"] * cfg["seqlen"]
+    per_call = block_s / calls
+    flops = shapes.algorithmic_flops(cfg)
+    scalar_a = cfg["a_kind"] == 1
+    ach = (shapes.ssd_matrix_flops(cfg) if scalar_a else flops) / per_call / 1e12
+    peak = PEAK_BF16_MFMA_TFLOPS if scalar_a else PEAK_FP32_VECTOR_TFLOPS
+    nbytes = shapes.algorithmic_bytes(cfg) + cfg["batch"] * cfg["d_inner"] * cfg["d_state"] * 4   # + the cached state, read once
+    result = {
+        "metric": "bidirectional-scan tokens/s/GPU at d_inner=4096,L=8K; HBM GB/s vs peak",
+        "value": tokens_per_call / per_call, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": block_s * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "what_a_step_is": "one block: %d denoising steps x %d layers = %d block calls, "
+                   "graph replay; value counts the tokens each call scans (batch x G)" % (args.denoise_steps, args.layers, calls),
+                   "batch": cfg["batch"], "block_tokens": cfg["seqlen"], "d_inner": cfg["d_inner"], "d_state": cfg["d_state"],
+                   "n_heads": cfg["n_heads"], "io_dtype": cfg["io"], "state_dtype": "f32", "layers": args.layers,
+                   "denoise_steps": args.denoise_steps},
+        "per_call_us": {"graph_replay": per_call * 1e6, "eager": eager_s / calls * 1e6},
+        "generated_tokens_per_s": tokens_per_call / block_s,
+        "roofline": {"bound": "mfma" if scalar_a else "alu", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
+                     "frac": ach / peak, "traffic": None,
+                     "kernel": "one block call (all its launches), mean over a graph replay of %d calls" % calls,
+                     "kernel_ms": per_call * 1e3},
+        "hbm": {"achieved": nbytes / per_call / 1e9, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                "frac": nbytes / per_call / 1e9 / PEAK_HBM_GBPS, "algorithmic_bytes": nbytes},
+    }
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle as orc
+        npy = lambda d: {k: (None if v is None else v.numpy()) for k, v in d.items()}
+        inp = synth.make_inputs(cfg, seed + 100)
+        pf, pb = params[0]
+        t0 = time.perf_counter()
+        reps = 3
+        for _ in range(reps):
+            orc.bimamba_block_fwd(cfg, npy(pf), npy(pb), npy(inp), h_in=np.zeros((cfg["batch"], cfg["d_inner"], cfg["d_state"])))
+        cpu_s = (time.perf_counter() - t0) / reps
+        result["cpu_baseline"] = {"value": tokens_per_call / cpu_s, "unit": "tokens/s", "cores": orc.num_threads(),
+                                  "kind": "oracle", "seconds": cpu_s, "sample": "one block call of layer 0, whole batch, fp64"}
+    print(json.dumps(result))
 
 
 def main():
@@ -91,6 +184,8 @@ def main():
                           "bytes_written_per_copy": src.numel() * 4}))
         return
     bd.lib()  # fail loudly if the HIP library is not built
+    if args.workload.startswith("cfg3_block"):
+        return decode_loop_bench(args, torch, bd, shapes, synth)
     cfg = dict(synth.CONFIGS[args.workload])
     seed = synth.config_seed(9)
     t0 = time.time()
@@ -164,12 +259,17 @@ def main():
         ach = mflops / (kernel_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                     "frac": ach / PEAK_BF16_MFMA_TFLOPS, "algorithmic_flops": mflops}
-    traffic = read_traffic("sweep_" + args.workload)
-    if ssd and traffic is not None:
-        traffic *= 2.0   # the summary holds the mean of one launch; the probed interval holds both directions' launches
-    # both headline launches keep two waves on every SIMD (2048 waves, or 512 workgroups of 8 waves on 256 CUs)
+    counters, profile_kernel, profile_file = read_profile("sweep_" + args.workload)
+    # the chunked path runs one launch per direction, both inside the probed interval; the summary holds one launch's mean
+    traffic = traffic_of(counters, 2 if ssd else 1)
+    simds = 4 * torch.cuda.get_device_properties(0).multi_processor_count
+    valu_busy, waves_per_simd = valu_busy_of(counters, simds)
+    ceiling = copy_ceiling_gbps(torch)
     roofline.update({"traffic": traffic, "kernel": kernel, "kernel_ms": kernel_ms,
-                     "valu_busy_from_profile": read_valu_busy("sweep_" + args.workload, 2.0)})
+                     "traffic_source": {"stored_profile": profile_file, "profiled_kernel": profile_kernel,
+                                        "note": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this command, "
+                                                "scaled by the 1 GiB copy calibration in the same file"},
+                     "valu_busy_from_profile": valu_busy, "waves_per_simd_from_profile": waves_per_simd})
     result = {
         "metric": "bidirectional-scan tokens/s/GPU at d_inner=4096,L=8K; HBM GB/s vs peak",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -183,7 +283,7 @@ def main():
                    "combine": "add", "time_chunks": bd.bimamba_time_chunks(desc)},
         "roofline": roofline,
         "hbm": {"achieved": ach_gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach_gbps / PEAK_HBM_GBPS,
-                "algorithmic_bytes": nbytes},
+                "algorithmic_bytes": nbytes, "copy_ceiling_measured": ceiling, "frac_of_copy_ceiling": ach_gbps / ceiling},
         "general_A": general,
         "input_generation_s": gen_s,
     }
@@ -200,10 +300,24 @@ def main():
         cpu_s = time.perf_counter() - t0
         got = out[:nb].float().cpu().numpy().astype(np.float64)
         err = max(float(np.linalg.norm(got[b] - ref[b]) / np.linalg.norm(ref[b])) for b in range(nb))
-        result["cpu_baseline"] = {"value": nb * cfg["seqlen"] / cpu_s, "unit": "tokens/s", "cores": orc.num_threads(),
+        # the same oracle on one thread, on a sample sized to a few seconds: the first 256 channels of batch element 0
+        threads = orc.num_threads()
+        one_sel = list(range(min(256, cfg["d_inner"])))
+        one_in = {k: v[:1].contiguous() for k, v in inp.items()}
+        orc.set_num_threads(1)
+        t0 = time.perf_counter()
+        orc.bimamba_fwd(dict(cfg, batch=1), npy(pf), npy(pb), npy(one_in), sel=one_sel)
+        one_s = time.perf_counter() - t0
+        orc.set_num_threads(threads)
+        one_rate = cfg["seqlen"] * (len(one_sel) / cfg["d_inner"]) / one_s
+        result["cpu_baseline"] = {"value": nb * cfg["seqlen"] / cpu_s, "unit": "tokens/s", "cores": threads,
                                   "kind": "oracle", "seconds": cpu_s,
                                   "sample": "batch elements 0..%d of %d, all %d tokens and %d channels, fp64" % (
-                                      nb - 1, cfg["batch"], cfg["seqlen"], cfg["d_inner"])}
+                                      nb - 1, cfg["batch"], cfg["seqlen"], cfg["d_inner"]),
+                                  "single_thread": {"value": one_rate, "unit": "tokens/s", "cores": 1, "seconds": one_s,
+                                                    "sample": "batch element 0, all %d tokens, %d of %d channels "
+                                                              "(rate scaled by the channel fraction)" % (
+                                                                  cfg["seqlen"], len(one_sel), cfg["d_inner"])}}
         result["rel_l2_vs_oracle"] = err
     print(json.dumps(result))
 
