@@ -66,12 +66,12 @@ def traffic_of(c, launches):
 
 
 def valu_busy_of(c, simds):
-    """Fraction of SIMD time with a vector-ALU instruction executing: per-wave VALU-active cycles over per-wave
-    resident cycles, times the waves that share a SIMD (the launch's waves over the chip's SIMDs when they are all
-    resident at once, which holds for the profiled launches)."""
+    """Fraction of SIMD time with a vector-ALU instruction executing, from the stored counters: VALU-active wave cycles
+    (counted in units of four cycles) over SIMDs x the dispatch's duration at the nominal 2.4 GHz clock.  Also the
+    time-averaged number of waves resident per SIMD (wave cycles over the same denominator)."""
     try:
-        waves_per_simd = c["SQ_WAVES"] / simds
-        return min(1.0, waves_per_simd * c["SQ_ACTIVE_INST_VALU"] / c["SQ_WAVE_CYCLES"]), waves_per_simd
+        denom = simds * c["DURATION_NS_UNDER_PMC"] * 2.4
+        return min(1.0, 4.0 * c["SQ_ACTIVE_INST_VALU"] / denom), 4.0 * c["SQ_WAVE_CYCLES"] / denom
     except (KeyError, ZeroDivisionError):
         return None, None
 
@@ -269,7 +269,7 @@ def main():
                      "traffic_source": {"stored_profile": profile_file, "profiled_kernel": profile_kernel,
                                         "note": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this command, "
                                                 "scaled by the 1 GiB copy calibration in the same file"},
-                     "valu_busy_from_profile": valu_busy, "waves_per_simd_from_profile": waves_per_simd})
+                     "valu_busy_from_profile": valu_busy, "resident_waves_per_simd_from_profile": waves_per_simd})
     result = {
         "metric": "bidirectional-scan tokens/s/GPU at d_inner=4096,L=8K; HBM GB/s vs peak",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

@@ -71,17 +71,30 @@ def summarise_stats(directory, warmup, steps, command=None):
     return "\n".join(lines) + "\n"
 
 
+_counters_per_dispatch = {}
+
+
 def counter_means(directory, kernel_filter=None):
     """{(kernel, counter): (mean per dispatch, dispatches)}; also the launch geometry of each kernel."""
     agg = collections.defaultdict(lambda: [0.0, 0])
     geom = {}
-    for r in _rows(directory, "_counter_collection.csv"):
+    rows = list(_rows(directory, "_counter_collection.csv"))
+    per = collections.defaultdict(set)
+    for r in rows:
+        per[r["Kernel_Name"]].add(r["Counter_Name"])
+    _counters_per_dispatch.clear()
+    _counters_per_dispatch.update({k: len(v) for k, v in per.items()})
+    for r in rows:
         k = r["Kernel_Name"]
         if kernel_filter and kernel_filter not in k:
             continue
         a = agg[(k, r["Counter_Name"])]
         a[0] += float(r["Counter_Value"])
         a[1] += 1
+        if "Start_Timestamp" in r:   # the dispatch's own duration (under counter collection: an upper bound)
+            t = agg[(k, "DURATION_NS_UNDER_PMC")]
+            t[0] += (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / max(1, _counters_per_dispatch.get(k, 1))
+            t[1] += 1.0 / max(1, _counters_per_dispatch.get(k, 1))
         if k not in geom and "Grid_Size" in r:
             geom[k] = (int(r["Grid_Size"]), int(r["Workgroup_Size"]))
     return {k: (v[0] / v[1], v[1]) for k, v in agg.items()}, geom
