@@ -44,17 +44,23 @@ def read_profile(kernel_key):
     paper_2511_15927_amd.profile_summary): counters as floats, plus the kernel name and the file the values come from.
     These are STORED values of an earlier run of this same command, not measurements of the present run."""
     path = os.path.join(ROOT, "profiles", kernel_key + "_pmc.txt")
-    vals, kernel = {}, None
+    sections, kernel, shared = {}, None, {}
     try:
         for line in open(path):
             if line.startswith("# kernel:"):
                 kernel = line.split(":", 1)[1].strip()
+                sections[kernel] = {}
             elif "=" in line and not line.lstrip().startswith("#"):
                 k, v = line.split("=", 1)
-                vals[k.strip()] = float(v.strip())
+                (sections[kernel] if kernel else shared)[k.strip()] = float(v.strip())
     except Exception:
         return {}, None, None
-    return vals, kernel, os.path.relpath(path, ROOT)
+    ours = {k: v for k, v in sections.items() if "bm::" in k}
+    if not ours:
+        return {}, None, None
+    # the dominant kernel of the step: the one with the longest dispatch
+    kernel = max(ours, key=lambda k: ours[k].get("DURATION_NS_UNDER_PMC", 0.0))
+    return dict(shared, **ours[kernel]), kernel, os.path.relpath(path, ROOT)
 
 
 def traffic_of(c, launches):
@@ -254,7 +260,9 @@ def main():
                 "frac": ach_tflops / PEAK_FP32_VECTOR_TFLOPS, "algorithmic_flops": flops}
     if ssd:
         # the chunked matrix-core kernels: one launch per direction, both inside the probed interval
-        kernel = "ssd_kernel<N=%d,P=%d> (two launches, one per direction)" % (cfg["d_state"], cfg["d_inner"] // cfg["n_heads"])
+        # one time part and several chunks: the sixteen-wave form; otherwise the eight-wave form (+ state and carry kernels)
+        form = "ssd_wide_kernel" if bd.bimamba_time_chunks(desc) == 1 and cfg["seqlen"] > 64 else "ssd_kernel"
+        kernel = "%s<N=%d,P=%d> (two launches, one per direction)" % (form, cfg["d_state"], cfg["d_inner"] // cfg["n_heads"])
         mflops = shapes.ssd_matrix_flops(cfg)
         ach = mflops / (kernel_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
