@@ -53,17 +53,20 @@ def timed(fn, steps, warmup):
     return e0.elapsed_time(e1) / steps
 
 
-def time_fwd(name, cfg, steps=10, warmup=3, general_a=False):
+def time_fwd(name, cfg, steps=10, warmup=3, general_a=False, untied=False):
     desc = bd.make_desc(cfg)
     dpf, dpb = gpu_params(cfg, general_a=general_a)
     inp = gpu_inputs(cfg)
+    inp_b = gpu_inputs(cfg, seed=2) if untied else None   # untied directions: the reverse layer has its own x, z, dt, B, C
     out, ws = bd.alloc_out(cfg), bd.alloc_workspace(desc)
-    args = (desc, bd.make_params(dpf), bd.make_params(dpb), bd.make_inputs(inp), None, bd.make_tensor(out), ws)
+    args = (desc, bd.make_params(dpf), bd.make_params(dpb), bd.make_inputs(inp),
+            None if inp_b is None else bd.make_inputs(inp_b), bd.make_tensor(out), ws)
     ms = timed(lambda: bd.bimamba_fwd(*args), steps, warmup)
     tokens = cfg["batch"] * cfg["seqlen"]
-    gbps = shapes.algorithmic_bytes(cfg) / (ms * 1e-3) / 1e9
+    gbps = shapes.algorithmic_bytes(cfg, shared_inputs=not untied) / (ms * 1e-3) / 1e9
     row = dict(name=name, batch=cfg["batch"], seq_len=cfg["seqlen"], d_inner=cfg["d_inner"], d_state=cfg["d_state"],
                layout="mamba2" if cfg["a_kind"] == 1 else "selective", io=cfg["io"], A="general" if general_a else "recipe",
+               inputs="per direction" if untied else "shared", combine="separate" if cfg["combine"] == 1 else "add",
                time_chunks=bd.bimamba_time_chunks(desc), ms=ms, tokens_per_s=tokens / (ms * 1e-3),
                algorithmic_GBps=gbps, hbm_frac=gbps / PEAK_HBM_GBPS,
                alu_TFLOPs=shapes.algorithmic_flops(cfg) / (ms * 1e-3) / 1e12)
@@ -222,7 +225,8 @@ def main():
         rows.append(time_fwd("headline_b8", C["headline"]))
         rows.append(time_fwd("headline_b8_generalA", C["headline"], general_a=True))
         rows.append(time_fwd("headline_b1", C["headline_b1"]))
-        rows.append(time_fwd("headline_b8_untied_separate", dict(C["headline"], combine=1)))
+        rows.append(time_fwd("headline_b8_shared_separate", dict(C["headline"], combine=1)))
+        rows.append(time_fwd("headline_b8_untied_separate", dict(C["headline"], combine=1), untied=True))
     if "m2" in want:
         rows.append(time_fwd("cfg0_m2", C["cfg0_m2"]))
         m2 = dict(C["cfg1_m2"]) if not a.quick else dict(C["cfg1_m2"], batch=1)
