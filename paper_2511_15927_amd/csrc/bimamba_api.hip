@@ -127,18 +127,19 @@ long long waves_of(const bimamba_desc* d, int split)
 
 // Launch geometry of the lane-per-chain kernels, from measurements on MI355X (1024 SIMDs) with w = the number of waves
 // that one lane per chain gives (2 * batch * d_inner / 64), up to 32 states:
+//   first       two lanes per chain (each holds half the states), whole sequence, when the 2w waves fill the rounds of
+//               resident waves well (two_lanes_fit below).
 //   w >= 1920   one lane per chain, whole sequence: close to two waves per SIMD already.
-//   else        two lanes per chain (each holds half the states), whole sequence, when the 2w waves fill the SIMDs
-//               well in one round of resident waves: 1.8 to 2, or 2.35 to 3 per SIMD (the kernel's registers allow
-//               three at once).  Doubling the waves this way repeats the per-channel work but needs no second pass.
-//               Otherwise one lane per chain and the sequence cut into time segments until about 16 waves per SIMD
-//               exist: the segment summaries cost a second, cheaper pass, but every SIMD then holds enough waves
-//               to issue back to back and to hide the loads, whatever the batch.  Segments stay at 256 tokens or
-//               more when that still gives four waves per SIMD, at 128 or more otherwise.
+//   else        one lane per chain and the sequence cut into time segments until about 16 waves per SIMD exist: the
+//               segment summaries cost a second, cheaper pass, but every SIMD then holds enough waves to issue back
+//               to back and to hide the loads, whatever the batch.  Segments stay at 256 tokens or more when that
+//               still gives four waves per SIMD, at 128 or more otherwise.
 //               If even that leaves fewer than two waves per SIMD (short sequences), two lanes per chain.
-// Four lanes per chain repeat too much per-token work to pay off below 64 states.  With 64 or 128 states a lane cannot
-// hold a whole chain without starving the SIMD of registers, so those shapes split the states first (four lanes per
-// chain) and cut the sequence only as far as two waves per SIMD need, in segments of at least 256 tokens.
+// Four lanes per chain cost as many vector instructions per channel and token as two (measured with the tokens dealt:
+// 2.36 ms against 1.83 at the headline shape, and twice the HBM fetch because four tiles share a 128-byte line) and
+// are not picked below 64 states.  With 64 or 128 states a lane cannot hold a whole chain without starving the SIMD of
+// registers, so those shapes split the states first (four lanes per chain) and cut the sequence only as far as two
+// waves per SIMD need, in segments of at least 256 tokens.
 constexpr int kWavesForSegments = 16384;
 constexpr int kMinSegmentTokens = 128;
 
@@ -157,10 +158,17 @@ int segments_for(const bimamba_desc* d, long long waves)
     return (int)(n < 1 ? 1 : n);
 }
 
-// Two lanes per chain fill the SIMDs well in one round of resident waves.
-bool two_lanes_fit(long long w)
+// Two lanes per chain, whole sequence.  Up to 16 states the pair deals its tokens (see run_tiles_dealt) and a SIMD
+// holds two such waves at once, so the launch runs in rounds of 2 waves per SIMD: it pays when the last round is
+// nearly full (1.7 to 2, or 3.4 to 4 waves per SIMD) or exactly half full (3).  Measured at d_inner 4096, L 8192
+// against the best of the other geometries: batch 7-8 -8 to -17 %, batch 12 -10 %, batch 14-16 -3 to -8 %.
+// With 32 states the plain walk keeps three waves on a SIMD: 1.8 to 2, or 2.35 to 3 per SIMD.
+bool two_lanes_fit(const bimamba_desc* d, long long w)
 {
     const long long per_simd_x100 = 2 * w * 100 / simds();
+    if (d->d_state <= 16)
+        return (per_simd_x100 >= 170 && per_simd_x100 <= 200) || (per_simd_x100 >= 290 && per_simd_x100 <= 300) ||
+               (per_simd_x100 >= 340 && per_simd_x100 <= 400);
     return (per_simd_x100 >= 180 && per_simd_x100 <= 200) || (per_simd_x100 >= 235 && per_simd_x100 <= 300);
 }
 
@@ -171,10 +179,10 @@ int pick_split(const bimamba_desc* d)
 {
     if (d->state_split > 0) return d->state_split;
     const long long w = waves_of(d, 1);
-    if (enough_chains(d, w)) return 1;
     const bool two = split_supported(d->d_state, 2), four = d->d_state >= 64 && split_supported(d->d_state, 4);
+    if (!many_states(d) && two && d->time_chunks <= 1 && two_lanes_fit(d, w)) return 2;
+    if (enough_chains(d, w)) return 1;
     if (many_states(d)) return w >= target_waves() / 2 && two ? 2 : four ? 4 : two ? 2 : 1;
-    if (two && two_lanes_fit(w)) return 2;
     if (d->time_chunks == 0 && w * segments_for(d, w) >= target_waves()) return 1;
     return two ? 2 : 1;
 }
@@ -190,7 +198,7 @@ int pick_chunks(const bimamba_desc* d, int split)
         const long long waves = waves_of(d, split);
         const long long w = waves_of(d, 1);
         const bool whole = d->state_split == 0 && !many_states(d) &&
-                           (split == 1 ? enough_chains(d, w) : split == 2 && two_lanes_fit(w));
+                           (split == 1 ? enough_chains(d, w) : split == 2 && two_lanes_fit(d, w));
         n = waves >= target_waves() || whole ? 1 : segments_for(d, waves);
     }
     if (n > L) n = L;

@@ -10,6 +10,10 @@
 // the first half of its walk each wave parks its output as an fp32 partial, in the second half it adds the partial
 // the other wave parked there and performs the single rounding to the I/O dtype.
 //
+// With up to 16 states split over several lanes, those lanes also deal the tokens among themselves: lane j of a chain
+// owns token j of every group of S tokens and does that token's per-channel work (loads, conv, SiLUs, gate, store)
+// alone, the others reading what they need of it through lane-permute operands (run_tiles_dealt).
+//
 // B_t and C_t come from an fp32 copy made by prep_bc_kernel.  With S = 1 they are wave-uniform and are fetched one
 // token ahead with scalar loads; with S > 1 each lane needs its own slice, so a tile of rows is staged through LDS
 // (private to the wave, no barrier) and read back one token ahead.
@@ -103,6 +107,14 @@ struct IoBF16 {
         __builtin_amdgcn_raw_buffer_store_b16(round(v), r, lane_off, row_off, 0);
     }
 };
+
+// A result in the I/O dtype (one rounding to nearest even for bf16).
+template <typename IO>
+__device__ __forceinline__ typename IO::T io_value(float v)
+{
+    if constexpr (sizeof(typename IO::T) == 2) return IO::round(v);
+    else return v;
+}
 
 __device__ __forceinline__ float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
 __device__ __forceinline__ float silu(float v) { return v * __builtin_amdgcn_rcpf(1.0f + fast_exp2(-kLog2e * v)); }
@@ -437,9 +449,308 @@ __device__ __forceinline__ void take_turn(const SweepArgs& a)
     else __builtin_amdgcn_s_setprio(3);
 }
 
-// Tokens [0, count) of the chain's walk from its current position, tile by tile with the next tile's loads in flight
-// and the next token's B|C slice requested before the current token is computed.  lds: this wave's private staging
-// area of 2 * TILE * 2N floats (S > 1 only).
+// ---- Dealt tokens (S = 2 or 4 lanes per chain) -----------------------------------------------------------------
+// The S lanes of a chain split its states, and they also split the per-channel work of S consecutive tokens (a
+// group): lane j of the chain OWNS token j of every group.  Only the owner loads that token's x, Delta, z and partial,
+// converts them, evaluates the conv, both SiLUs and the softplus, forms u = Delta * xc and the decay ratio, and later
+// finishes and stores the token's result.  What the other lanes need of a token (Delta, u, the ratio) they read from
+// the owner's registers through the quad-permute operand of the consuming instruction.  Per lane and token that leaves
+// the 4 * N/S state instructions, one exponential and the reduction; everything else is paid once per group instead
+// of once per token, and a wave issues one load or store instruction per group and tensor instead of one per token.
+//
+// The conv window of token i reaches back to tokens i-1 .. i-3, which other lanes own: token i-k sits in lane
+// (j - k) mod S, in the same group when k <= j and ceil((k - j) / S) groups back otherwise.  Each lane keeps its own raw
+// x of the last few groups and holds, per (k, groups back), either the tap weight or zero, so the window is a fixed
+// sequence of multiply-adds on lane-rotated values with no selects.  (A zero weight multiplies a token the window does
+// not contain; with finite inputs that adds nothing.)
+template <int S>
+__host__ __device__ constexpr int dealt_groups_back(int j, int k) { return k <= j ? 0 : (k - j + S - 1) / S; }
+template <int S>
+__host__ __device__ constexpr bool dealt_term_exists(int k, int d)
+{
+    for (int j = 0; j < S; j++)
+        if (dealt_groups_back<S>(j, k) == d) return true;
+    return false;
+}
+
+// The value lane (own - k) mod S of the caller's chain holds.  k is a constant wherever this is called from an
+// unrolled loop, so one move remains.
+template <int S>
+__device__ __forceinline__ float chain_lane_back(float v, int k)
+{
+    static_assert(S == 2 || S == 4, "chains are lane pairs or quads");
+    const int i = __float_as_int(v);
+    k &= S - 1;
+    if (k == 0) return v;
+    if (S == 2) return __int_as_float(__builtin_amdgcn_update_dpp(0, i, 0xB1, 0xF, 0xF, true));      // [1,0,3,2]
+    if (k == 1) return __int_as_float(__builtin_amdgcn_update_dpp(0, i, 0x93, 0xF, 0xF, true));      // [3,0,1,2]
+    if (k == 2) return __int_as_float(__builtin_amdgcn_update_dpp(0, i, 0x4E, 0xF, 0xF, true));      // [2,3,0,1]
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, i, 0x39, 0xF, 0xF, true));                  // [1,2,3,0]
+}
+
+// The value lane j of the caller's chain holds (j constant after unrolling).
+template <int S>
+__device__ __forceinline__ float chain_lane_pick(float v, int j)
+{
+    if (S == 2) return j == 0 ? chain_lane_value<2, 0>(v) : chain_lane_value<2, 1>(v);
+    if (j == 0) return chain_lane_value<4, 0>(v);
+    if (j == 1) return chain_lane_value<4, 1>(v);
+    if (j == 2) return chain_lane_value<4, 2>(v);
+    return chain_lane_value<4, 3>(v);
+}
+
+// Addressing of the dealt walk.  Per tensor, a wave-uniform 64-bit pointer to the lowest-address row of a tile (so
+// that every lane offset is non-negative whatever the direction of the walk) moves by one tile per iteration, and a
+// lane's own (group, token, channel) inside a tile is a 32-bit byte offset fixed for the whole walk: a memory
+// instruction takes both as they are, and the loop is left with one pointer step per tensor and tile.
+template <typename T>
+__device__ __forceinline__ T load_at(const T* tile_row, unsigned lane_bytes)
+{
+    return *reinterpret_cast<const T*>(reinterpret_cast<const char*>(tile_row) + lane_bytes);
+}
+template <typename T>
+__device__ __forceinline__ void store_at(T* tile_row, unsigned lane_bytes, T v)
+{
+    *reinterpret_cast<T*>(reinterpret_cast<char*>(tile_row) + lane_bytes) = v;
+}
+
+// Tokens per dealt tile, and the shapes that deal their tokens: up to 16 states split over two or four lanes (with more
+// states per lane the state updates dominate and the plain walk's smaller register footprint wins).
+template <int N, int S>
+constexpr int kDealtTile = 8;
+template <int N, int S>
+constexpr bool kDealtTokens = S > 1 && N <= 16;
+
+typedef float Float4 __attribute__((ext_vector_type(4)));  // a native vector: copies of structs that hold it stay in registers
+template <typename IO, int G, int NSTAGE>
+struct DealtTile {
+    typename IO::T x[G], z[G], dt[G];
+    float part[G];
+    Float4 bc[NSTAGE];   // the lane's share of the tile's B|C rows on their way to LDS
+};
+
+// Whole tiles of tokens [0, count) of the chain's walk, dealt as described above; returns the number of tokens done
+// (a multiple of the dealt tile).  On entry and on return c.xh holds the raw x of the three tokens before the current
+// position, alike in all lanes of the chain, so the per-token path can take over the remainder.  lds: this wave's
+// private 2 * DT * 2N floats.  Two tile register sets are used in turn (the loop body is the pair), so a tile is
+// computed from the registers its loads arrived in.
+template <int N, int S, int AKIND, typename IO, int MODE>
+__device__ __forceinline__ int run_tiles_dealt(const SweepArgs& a, Chain<N, S, AKIND, IO>& c, int count, bool softplus_dt,
+                                               float* lds, int lane)
+{
+    static_assert((S == 2 || S == 4) && MODE != kModeNoOutput, "dealt tiles: lane pairs or quads, output modes");
+    using T = typename IO::T;
+    constexpr int DT = kDealtTile<N, S>;
+    constexpr int NS = N / S, G = DT / S, D = (3 + S - 1) / S;
+    constexpr int kRowF4 = 2 * N / 4;
+    constexpr int kStage = (DT * kRowF4 + 63) / 64;
+    constexpr bool kGated = MODE != kModePartialRaw;
+    using Tile = DealtTile<IO, G, kStage>;
+    const int total = count / DT * DT;
+    if (total == 0) return 0;
+    const int sub = (int)c.sub;
+
+    // tap weight or zero per (k tokens back, d groups back)
+    float wk[3][D + 1];
+#pragma unroll
+    for (int k = 1; k <= 3; k++)
+#pragma unroll
+        for (int d = 0; d <= D; d++) {
+            float v = 0.0f;
+#pragma unroll
+            for (int j = 0; j < S; j++)
+                if (dealt_groups_back<S>(j, k) == d) v = sub == j ? c.w4[3 - k] : v;
+            wk[k - 1][d] = v;
+        }
+    // own raw x of the last groups: hist[d] is d groups back once a group's value has been shifted in.  Before the
+    // first group, hist[d - 1] is seeded with "group -d": the token before the walk by m + 1 sits in lane
+    // (-1 - m) mod S of group -ceil((m + 1) / S).
+    float hist[D + 1];
+#pragma unroll
+    for (int d = 1; d <= D + 1; d++) {
+        float v = 0.0f;
+#pragma unroll
+        for (int j = 0; j < S; j++) {
+            const int m = d * S - j - 1;
+            if (m >= 0 && m <= 2) v = sub == j ? c.xh[m] : v;
+        }
+        hist[d - 1] = v;
+    }
+    // The lane's own token of group q inside a tile's rows, per tensor: bytes above the tile's lowest-address row,
+    // plus the lane's channel.  Token q * S + sub of the tile lies that many rows up when the walk ascends in memory,
+    // DT - 1 - that many when it descends.
+    auto absll = [](long long v) { return v < 0 ? -v : v; };
+    auto rows_up = [&](long long step, int token) { return step < 0 ? DT - 1 - token : token; };
+    unsigned vx[G], vd[G], vz[G], vo[G], vp[G];
+#pragma unroll
+    for (int q = 0; q < G; q++) {
+        const int t = q * S + sub;
+        vx[q] = c.ch_io + (unsigned)rows_up(c.xs, t) * (unsigned)(absll(c.xs) * (long long)sizeof(T));
+        vd[q] = c.head_io + (unsigned)rows_up(c.dts, t) * (unsigned)(absll(c.dts) * (long long)sizeof(T));
+        vz[q] = c.ch_io + (unsigned)rows_up(c.zs, t) * (unsigned)(absll(c.zs) * (long long)sizeof(T));
+        vo[q] = c.ch_io + (unsigned)rows_up(c.os, t) * (unsigned)(absll(c.os) * (long long)sizeof(T));
+        vp[q] = c.ch_f32 + (unsigned)rows_up(c.ps, t) * (unsigned)(absll(c.ps) * 4LL);
+    }
+    // lane q moves float4 number (j*64 + q) of a tile's B|C rows: token (scan order) idx / kRowF4, column idx % kRowF4
+    unsigned vbc[kStage];
+#pragma unroll
+    for (int j = 0; j < kStage; j++) {
+        const int idx = min(j * 64 + lane, DT * kRowF4 - 1);
+        vbc[j] = (unsigned)rows_up(c.bcs, idx / kRowF4) * (unsigned)(absll(c.bcs) * 4LL) + (unsigned)(idx % kRowF4) * 16u;
+    }
+    auto lowest = [&](auto* row, long long step) { return step < 0 ? row + (DT - 1) * step : row; };
+    // tile pointers: the inputs' run one tile ahead of the outputs' once the first tile has been requested
+    const T* xin = lowest(c.xrow, c.xs);
+    const T* din = lowest(c.dtrow, c.dts);
+    const T* zin = lowest(c.zrow, c.zs);
+    const float* pin = lowest(c.prow, c.ps);
+    const float* bcin = lowest(c.bcrow, c.bcs);
+    T* oout = lowest(c.orow, c.os);
+    float* pout = lowest(c.prow, c.ps);
+    auto load = [&](Tile& r) {
+#pragma unroll
+        for (int q = 0; q < G; q++) {
+            r.x[q] = load_at(xin, vx[q]);
+            r.dt[q] = load_at(din, vd[q]);
+            if (mode_reads_z(MODE)) r.z[q] = load_at(zin, vz[q]);
+            if (mode_reads_partial(MODE)) r.part[q] = load_at(pin, vp[q]);
+        }
+#pragma unroll
+        for (int j = 0; j < kStage; j++)
+            if (DT * kRowF4 % 64 == 0 || j * 64 + lane < DT * kRowF4)
+                r.bc[j] = *reinterpret_cast<const Float4*>(reinterpret_cast<const char*>(bcin) + vbc[j]);
+        xin += DT * c.xs;
+        din += DT * c.dts;
+        if (mode_reads_z(MODE)) zin += DT * c.zs;
+        if (mode_reads_partial(MODE)) pin += DT * c.ps;
+        bcin += DT * c.bcs;
+    };
+    auto stage_store = [&](int which, const Tile& r) {
+#pragma unroll
+        for (int j = 0; j < kStage; j++) {
+            const int idx = j * 64 + lane;
+            if (DT * kRowF4 % 64 == 0 || idx < DT * kRowF4)
+                *reinterpret_cast<Float4*>(lds + which * (DT * 2 * N) + idx * 4) = r.bc[j];
+        }
+        __builtin_amdgcn_wave_barrier();  // other lanes of this wave read these rows next; LDS keeps wave order
+    };
+
+    BcRow<NS> row;
+    int buf = 0, done = 0;
+    // One tile: request the next one into `fill`, compute `cur`, move on.  Returns false after the last tile.
+    auto one_tile = [&](const Tile& cur, Tile& fill) -> bool {
+        const bool more = done + 2 * DT <= total;
+        if (more) {
+            if ((done & (4 * DT - 1)) == 0) take_turn(a);
+            load(fill);
+        }
+        const float* tile_bc = lds + buf * (DT * 2 * N);
+        float delta[G];
+#pragma unroll
+        for (int q = 0; q < G; q++) delta[q] = IO::cvt(cur.dt[q]);
+        if (softplus_dt) {
+#pragma unroll
+            for (int q = 0; q < G; q++) delta[q] = softplus(delta[q] + c.dtb);
+        }
+#pragma unroll
+        for (int q = 0; q < G; q++) {
+            // the owner's share of its token: conv window, SiLUs, input and decay factors
+#pragma unroll
+            for (int d = D; d >= 1; d--) hist[d] = hist[d - 1];
+            hist[0] = IO::cvt(cur.x[q]);
+            float pre = fmaf(c.w4[3], hist[0], c.cb);
+#pragma unroll
+            for (int k = 1; k <= 3; k++)
+#pragma unroll
+                for (int d = 0; d <= D; d++)
+                    if (dealt_term_exists<S>(k, d)) pre = fmaf(chain_lane_back<S>(hist[d], k), wk[k - 1][d], pre);
+            const float xc = silu(pre);
+            const float u = delta[q] * xc;
+            float zg = 0.0f, fac = 0.0f;
+            if (kGated) zg = silu(IO::cvt(cur.z[q]));
+            if (AKIND == kAProgression) fac = fast_exp2(delta[q] * c.d2);        // ratio between neighbouring states
+            else if (AKIND == kAScalar) fac = fast_exp2(delta[q] * c.a2[0]);     // the head's decay
+            float ys[S];
+#pragma unroll
+            for (int jt = 0; jt < S; jt++) {
+                const int i = q * S + jt;
+                BcRow<NS> row_next;
+                if (i + 1 < DT) load_bc_lds<N, S>(tile_bc, i + 1, c.sub, row_next);
+                const float ui = chain_lane_pick<S>(u, jt);
+                float y = 0.0f;
+                if (AKIND == kAPerState) {
+                    const float di = chain_lane_pick<S>(delta[q], jt);
+#pragma unroll
+                    for (int n = 0; n < NS; n++) {
+                        c.h[n] = fmaf(fast_exp2(di * c.a2[n]), c.h[n], ui * row.v[n]);
+                        y = fmaf(row.v[NS + n], c.h[n], y);
+                    }
+                } else if (AKIND == kAProgression) {
+                    const float di = chain_lane_pick<S>(delta[q], jt), ratio = chain_lane_pick<S>(fac, jt);
+                    float an = fast_exp2(di * c.a2[0]);
+#pragma unroll
+                    for (int n = 0; n < NS; n++) {
+                        c.h[n] = fmaf(an, c.h[n], ui * row.v[n]);
+                        y = fmaf(row.v[NS + n], c.h[n], y);
+                        if (n + 1 < NS) an *= ratio;
+                    }
+                } else {
+                    const float an = chain_lane_pick<S>(fac, jt);
+#pragma unroll
+                    for (int n = 0; n < NS; n++) {
+                        c.h[n] = fmaf(an, c.h[n], ui * row.v[n]);
+                        y = fmaf(row.v[NS + n], c.h[n], y);
+                    }
+                }
+                ys[jt] = sum_over_chain_lanes<S>(y);
+                if (i + 1 < DT) row = row_next;
+            }
+            // the owner finishes its token
+            float y = ys[0];
+#pragma unroll
+            for (int jt = 1; jt < S; jt++) y = sub == jt ? ys[jt] : y;
+            y = fmaf(c.dval, xc, y);
+            if (MODE == kModePartialRaw) {
+                store_at(pout, vp[q], y);
+            } else if (MODE == kModeFinalAddRaw) {
+                store_at(oout, vo[q], io_value<IO>((y + cur.part[q]) * zg));
+            } else {
+                const float g = y * zg;
+                if (MODE == kModePartial) store_at(pout, vp[q], g);
+                else store_at(oout, vo[q], io_value<IO>(MODE == kModeFinalAdd ? g + cur.part[q] : g));
+            }
+        }
+        done += DT;
+        if (MODE == kModePartialRaw || MODE == kModePartial) pout += DT * c.ps;
+        else oout += DT * c.os;
+        if (!more) return false;
+        buf ^= 1;
+        stage_store(buf, fill);
+        load_bc_lds<N, S>(lds + buf * (DT * 2 * N), 0, c.sub, row);
+        return true;
+    };
+
+    Tile ta, tb;
+    load(ta);
+    stage_store(0, ta);
+    load_bc_lds<N, S>(lds, 0, c.sub, row);
+    while (true) {
+        if (!one_tile(ta, tb)) break;
+        if (!one_tile(tb, ta)) break;
+    }
+    // hand the conv history back in the per-token form: the token m + 1 back sits in lane (S - 1 - m) mod S, m / S groups back
+#pragma unroll
+    for (int m = 0; m < 3; m++) c.xh[m] = chain_lane_pick<S>(hist[m / S], (S - 1 - m % S));
+    advance_rows(c, done);
+    c.bcrow += done * c.bcs;
+    c.tok += done * c.tstep;
+    return done;
+}
+
+// Tokens of the larger of the two kinds of tile a wave stages B|C rows for (its LDS area holds two of them).
+template <int N, int S, int TILE>
+constexpr int kStagedTile = kDealtTokens<N, S> && kDealtTile<N, S> > TILE ? kDealtTile<N, S> : TILE;
+
 template <int N, int S, int AKIND, typename IO, int MODE, int TILE, int BCSRC = kBcPrepared>
 __device__ __forceinline__ void run_range(const SweepArgs& a, Chain<N, S, AKIND, IO>& c, int count, bool softplus_dt, float* lds,
                                           int lane)
@@ -455,7 +766,9 @@ __device__ __forceinline__ void run_range(const SweepArgs& a, Chain<N, S, AKIND,
     using Tile = RawTile<IO, TILE>;
     if (count <= 0) return;
     int done = 0;
-    if (count >= TILE) {
+    if constexpr (kDealtTokens<N, S> && MODE != kModeNoOutput && BCSRC == kBcPrepared) {
+        done = run_tiles_dealt<N, S, AKIND, IO, MODE>(a, c, count, softplus_dt, lds, lane);
+    } else if (count >= TILE) {
         Tile nxt;
         load_tile<N, S, AKIND, IO, MODE, TILE>(c, 0, nxt);
         BcRow<NS> row;
@@ -735,7 +1048,7 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, c
     constexpr int NS = N / S;
     constexpr int kCpw = 64 / S;  // channels per wave
     const int lane = threadIdx.x & 63;
-    float* lds = lds_all + (BCSRC == kBcStaged ? w * (kShortCallTokens * 2 * N) : S > 1 ? w * (2 * TILE * 2 * N) : 0);
+    float* lds = lds_all + (BCSRC == kBcStaged ? w * (kShortCallTokens * 2 * N) : S > 1 ? w * (2 * kStagedTile<N, S, TILE> * 2 * N) : 0);
     const DirArgs& da = a.dir[s];
     const int b = blockIdx.z, seg = blockIdx.y;
     // Lanes past the last channel shadow channel Dn-1: they load the same inputs, compute the same values and
@@ -891,11 +1204,16 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, c
 template <int N, typename IO>
 constexpr bool kProgressionEligible = (N >= 2 && N <= 32 && sizeof(typename IO::T) == 2);
 
+// Register budget of the sweep where the tokens are dealt: lane quads are picked to put four waves on a SIMD (128
+// registers), lane pairs run two to a SIMD and take what they need.
+template <int N, int S, int KIND>
+constexpr int kSweepMinWaves = KIND == kSweep && kDealtTokens<N, S> ? (S == 4 ? 4 : 2) : 1;
+
 template <int N, int S, int AKIND, typename IO, int KIND, int TILE, int BCSRC = kBcPrepared>
-__global__ __launch_bounds__(256) void sweep_kernel(const SweepArgs a)
+__global__ __launch_bounds__(256, (kSweepMinWaves<N, S, KIND>)) void sweep_kernel(const SweepArgs a)
 {
     __shared__ __attribute__((aligned(16))) float lds_all[BCSRC == kBcStaged ? 4 * kShortCallTokens * 2 * N
-                                                          : S > 1            ? 4 * 2 * TILE * 2 * N
+                                                          : S > 1            ? 4 * 2 * kStagedTile<N, S, TILE> * 2 * N
                                                                              : 4];
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     if constexpr (AKIND == kAPerState && kProgressionEligible<N, IO>) {
