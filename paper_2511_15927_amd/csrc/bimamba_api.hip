@@ -159,16 +159,14 @@ int segments_for(const bimamba_desc* d, long long waves)
 }
 
 // Two lanes per chain, whole sequence.  Up to 16 states the pair deals its tokens (see run_tiles_dealt) and a SIMD
-// holds two such waves at once, so the launch runs in rounds of 2 waves per SIMD: it pays when the last round is
-// nearly full (1.7 to 2, or 3.4 to 4 waves per SIMD) or exactly half full (3).  Measured at d_inner 4096, L 8192
-// against the best of the other geometries: batch 7-8 -8 to -17 %, batch 12 -10 %, batch 14-16 -3 to -8 %.
+// holds three such waves at once: measured at d_inner 4096 (L 8192, batch 5 to 32) and d_inner 2048 (L 1024 to 8192,
+// batch 16 to 64) against the best of the other geometries, it wins from 1.7 to 5 waves per SIMD (batch 7 to 20 at
+// d_inner 4096: -3 to -23 %) and loses outside.
 // With 32 states the plain walk keeps three waves on a SIMD: 1.8 to 2, or 2.35 to 3 per SIMD.
 bool two_lanes_fit(const bimamba_desc* d, long long w)
 {
     const long long per_simd_x100 = 2 * w * 100 / simds();
-    if (d->d_state <= 16)
-        return (per_simd_x100 >= 170 && per_simd_x100 <= 200) || (per_simd_x100 >= 290 && per_simd_x100 <= 300) ||
-               (per_simd_x100 >= 340 && per_simd_x100 <= 400);
+    if (d->d_state <= 16) return per_simd_x100 >= 170 && per_simd_x100 <= 500;
     return (per_simd_x100 >= 180 && per_simd_x100 <= 200) || (per_simd_x100 >= 235 && per_simd_x100 <= 300);
 }
 

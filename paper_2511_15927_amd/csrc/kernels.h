@@ -513,6 +513,10 @@ __device__ __forceinline__ void store_at(T* tile_row, unsigned lane_bytes, T v)
 {
     *reinterpret_cast<T*>(reinterpret_cast<char*>(tile_row) + lane_bytes) = v;
 }
+// A lane offset has to be a 32-bit value of the block that uses it: widened to 64 bits outside the loop (where the
+// compiler would move the widening) it is no longer recognised as the offset operand of a scalar-base access and
+// costs a 64-bit vector add per access.  Passing it through an empty asm once per tile keeps it where it is.
+__device__ __forceinline__ void keep_narrow(unsigned& lane_bytes) { asm volatile("" : "+v"(lane_bytes)); }
 
 // Tokens per dealt tile, and the shapes that deal their tokens: up to 16 states split over two or four lanes (with more
 // states per lane the state updates dominate and the plain walk's smaller register footprint wins).
@@ -618,7 +622,7 @@ __device__ __forceinline__ int run_tiles_dealt(const SweepArgs& a, Chain<N, S, A
 #pragma unroll
         for (int j = 0; j < kStage; j++)
             if (DT * kRowF4 % 64 == 0 || j * 64 + lane < DT * kRowF4)
-                r.bc[j] = *reinterpret_cast<const Float4*>(reinterpret_cast<const char*>(bcin) + vbc[j]);
+                r.bc[j] = load_at(reinterpret_cast<const Float4*>(bcin), vbc[j]);
         xin += DT * c.xs;
         din += DT * c.dts;
         if (mode_reads_z(MODE)) zin += DT * c.zs;
@@ -640,6 +644,16 @@ __device__ __forceinline__ int run_tiles_dealt(const SweepArgs& a, Chain<N, S, A
     // One tile: request the next one into `fill`, compute `cur`, move on.  Returns false after the last tile.
     auto one_tile = [&](const Tile& cur, Tile& fill) -> bool {
         const bool more = done + 2 * DT <= total;
+#pragma unroll
+        for (int q = 0; q < G; q++) {
+            keep_narrow(vx[q]);
+            keep_narrow(vd[q]);
+            keep_narrow(vz[q]);
+            keep_narrow(vo[q]);
+            keep_narrow(vp[q]);
+        }
+#pragma unroll
+        for (int j = 0; j < kStage; j++) keep_narrow(vbc[j]);
         if (more) {
             if ((done & (4 * DT - 1)) == 0) take_turn(a);
             load(fill);
@@ -1204,10 +1218,11 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& a, float* lds_all, c
 template <int N, typename IO>
 constexpr bool kProgressionEligible = (N >= 2 && N <= 32 && sizeof(typename IO::T) == 2);
 
-// Register budget of the sweep where the tokens are dealt: lane quads are picked to put four waves on a SIMD (128
-// registers), lane pairs run two to a SIMD and take what they need.
+// Register budget of the sweep where the tokens are dealt: lane quads are meant to put four waves on a SIMD (128
+// registers), lane pairs three (168; measured at d_inner 4096, L 8192 against a budget of two waves: batch 12
+// 2.93 -> 2.52 ms, batch 8 1.82 -> 1.77 ms).
 template <int N, int S, int KIND>
-constexpr int kSweepMinWaves = KIND == kSweep && kDealtTokens<N, S> ? (S == 4 ? 4 : 2) : 1;
+constexpr int kSweepMinWaves = KIND == kSweep && kDealtTokens<N, S> ? (S == 4 ? 4 : 3) : 1;
 
 template <int N, int S, int AKIND, typename IO, int KIND, int TILE, int BCSRC = kBcPrepared>
 __global__ __launch_bounds__(256, (kSweepMinWaves<N, S, KIND>)) void sweep_kernel(const SweepArgs a)

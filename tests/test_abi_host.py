@@ -90,12 +90,11 @@ def test_workspace_and_chunk_planning():
     assert bd.bimamba_time_chunks(bd.make_desc(synth.CONFIGS["cfg3_block"])) == 1
     assert bd.bimamba_time_chunks(bd.make_desc(synth.mixer_cfg(1, 100, 64, time_chunks=7))) == 7
     assert bd.bimamba_time_chunks(bd.make_desc(synth.mixer_cfg(1, 5, 64, time_chunks=7))) == 5
-    # batch sweep at d_inner 4096 (w = 128 waves per batch element with one lane per chain): whole sequence when two
-    # lanes per chain fill their rounds of two resident waves per SIMD well (batch 7-8, 12, 14-16) or one lane per chain
-    # nearly fills the SIMDs (batch >= 15), else time segments
-    chunks = {b: bd.bimamba_time_chunks(bd.make_desc(synth.mixer_cfg(b, 8192, 4096))) for b in (1, 4, 7, 8, 9, 10, 12, 13, 14, 15, 16, 64)}
-    assert [b for b, n in chunks.items() if n == 1] == [7, 8, 12, 14, 15, 16, 64], chunks
-    assert chunks[1] == 32 and chunks[4] == 32 and chunks[9] == 15 and chunks[10] > 1
+    # batch sweep at d_inner 4096 (w = 128 waves per batch element with one lane per chain): whole sequence with two
+    # lanes per chain from 1.7 to 5 waves per SIMD (batch 7-20), with one lane per chain above, time segments below
+    chunks = {b: bd.bimamba_time_chunks(bd.make_desc(synth.mixer_cfg(b, 8192, 4096))) for b in (1, 4, 6, 7, 8, 12, 16, 20, 21, 24, 64)}
+    assert [b for b, n in chunks.items() if n == 1] == [7, 8, 12, 16, 20, 21, 24, 64], chunks
+    assert chunks[1] == 32 and chunks[4] == 32 and chunks[6] > 1
     sep = bd.make_desc(synth.mixer_cfg(8, 8192, 4096, combine=1))
     assert bd.bimamba_workspace_bytes(sep) < bd.bimamba_workspace_bytes(d1)     # no partial buffer without ADD
     assert bd.bimamba_workspace_bytes(d1) % 256 == 0
