@@ -16,6 +16,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBPS = 8000.0          # MI355X HBM3E
+PEAK_FP32_UNPACKED_TFLOPS = 256 * 4 * 16 * 2 * 2.4e9 / 1e12   # 78.6: one fp32 FMA per lane and clock
 PEAK_FP32_VECTOR_TFLOPS = 157.3  # MI355X fp32 vector (256 CUs x 2.4 GHz x 256 flop/clk)
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16 matrix
 
@@ -78,6 +79,19 @@ def valu_busy_of(c, simds):
     try:
         denom = simds * c["DURATION_NS_UNDER_PMC"] * 2.4
         return min(1.0, 4.0 * c["SQ_ACTIVE_INST_VALU"] / denom), 4.0 * c["SQ_WAVE_CYCLES"] / denom
+    except (KeyError, ZeroDivisionError):
+        return None, None
+
+
+SHADER_ENGINES = 32   # SQ_BUSY_CYCLES is summed over the shader engines (8 XCDs x 4)
+
+
+def sustained_clock_of(c, simds):
+    """The shader clock the dispatch actually ran at under the counters (busy cycles of one shader engine over the
+    dispatch's duration), and the vector-ALU busy fraction in those cycles rather than at the nominal clock."""
+    try:
+        cycles = c["SQ_BUSY_CYCLES"] / SHADER_ENGINES
+        return cycles / c["DURATION_NS_UNDER_PMC"], min(1.0, 4.0 * c["SQ_ACTIVE_INST_VALU"] / (simds * cycles))
     except (KeyError, ZeroDivisionError):
         return None, None
 
@@ -272,12 +286,17 @@ def main():
     traffic = traffic_of(counters, 2 if ssd else 1)
     simds = 4 * torch.cuda.get_device_properties(0).multi_processor_count
     valu_busy, waves_per_simd = valu_busy_of(counters, simds)
+    clock_ghz, valu_busy_own_clock = sustained_clock_of(counters, simds)
     ceiling = copy_ceiling_gbps(torch)
     roofline.update({"traffic": traffic, "kernel": kernel, "kernel_ms": kernel_ms,
                      "traffic_source": {"stored_profile": profile_file, "profiled_kernel": profile_kernel,
                                         "note": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this command, "
                                                 "scaled by the 1 GiB copy calibration in the same file"},
-                     "valu_busy_from_profile": valu_busy, "resident_waves_per_simd_from_profile": waves_per_simd})
+                     "valu_busy_from_profile": valu_busy, "resident_waves_per_simd_from_profile": waves_per_simd,
+                     "sustained_clock_ghz_from_profile": clock_ghz, "valu_busy_at_sustained_clock": valu_busy_own_clock,
+                     # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz: what fp32 code without packed instructions can issue
+                     "frac_of_unpacked_fp32_peak": None if roofline["bound"] != "alu" else
+                     roofline["achieved"] / PEAK_FP32_UNPACKED_TFLOPS})
     result = {
         "metric": "bidirectional-scan tokens/s/GPU at d_inner=4096,L=8K; HBM GB/s vs peak",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

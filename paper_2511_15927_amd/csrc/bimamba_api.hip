@@ -178,7 +178,10 @@ int pick_split(const bimamba_desc* d)
     if (d->state_split > 0) return d->state_split;
     const long long w = waves_of(d, 1);
     const bool two = split_supported(d->d_state, 2), four = d->d_state >= 64 && split_supported(d->d_state, 4);
-    if (!many_states(d) && two && d->time_chunks <= 1 && two_lanes_fit(d, w)) return 2;
+    // (calls of a few dozen tokens that can run as one launch with one lane per chain keep it, see short_call below:
+    // 32-token block steps at batch 16, d_inner 4096 take 23 us that way against 28 us with two lanes and a preparation launch)
+    const bool one_launch_form = d->d_state <= 16 && !d->conv_bc && d->seqlen <= kShortCallTokens && enough_chains(d, w);
+    if (!many_states(d) && two && d->time_chunks <= 1 && !one_launch_form && two_lanes_fit(d, w)) return 2;
     if (enough_chains(d, w)) return 1;
     if (many_states(d)) return w >= target_waves() / 2 && two ? 2 : four ? 4 : two ? 2 : 1;
     if (d->time_chunks == 0 && w * segments_for(d, w) >= target_waves()) return 1;

@@ -1,8 +1,8 @@
 // The chunk walk of ssd_kernels.h for calls that fill the chip, as sixteen short instruction streams instead of eight.
 //
-// A wave issues at most one instruction every six to seven cycles whatever the instruction is, and a SIMD's vector
-// ALU accepts one every two to three, so a workgroup is as fast as its longest per-chunk instruction stream, not as its
-// total work.  ssd_kernel deals a chunk to four consumer and four producer waves; here the same work goes to
+// A wave issues at most one instruction every six to seven cycles whatever the instruction is, while a SIMD's vector
+// ALU accepts a 64-lane instruction every four, so a workgroup is as fast as its longest per-chunk instruction stream,
+// not as its total work.  ssd_kernel deals a chunk to four consumer and four producer waves; here the same work goes to
 //   y waves   (P/16): the intra-chunk product, the inter-chunk product C H and the epilogue of a 32 x 32 output block;
 //   h waves   (N/32): the state update of one row block of H (all channel blocks, so one B^T operand serves them all),
 //                     its decay and the bf16 operand copy of the new state;
