@@ -154,3 +154,53 @@ def one_direction(cfg, params, inputs, direction, h_in=None, tail_in=None, want_
     if rc != 0:
         raise ValueError("oracle: shape outside the definition")
     return g, h_out
+
+
+class InputGrads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("dx", "dz", "ddt", "dB", "dC")]
+
+
+class ParamGrads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("dconv_w", "dconv_b", "dA", "dD", "ddt_bias")]
+
+
+def bimamba_bwd(cfg, params_f, params_b, in_f, in_b=None, dout=None, sel=None):
+    """Gradients of bimamba_fwd given dout (shaped like its output).  Returns (din_f, din_b, dparams_f, dparams_b):
+    din_*: dict of float64 arrays dx, dz [batch, L, n_sel], ddt [batch, L, n_heads], dB, dC [batch, L, groups, d_state];
+    din_b is None when in_b is None (both directions read in_f, whose gradients then hold the sum of both).
+    dparams_*: dict of float64 arrays shaped like the parameters (dconv_b / ddt_bias are returned even where the
+    parameter itself was None, i.e. zero)."""
+    d = _desc(cfg)
+    pf, k1 = _params(params_f)
+    pb, k2 = _params(params_b)
+    i_f, k3 = _inputs(in_f)
+    i_b, k4 = _inputs(in_f if in_b is None else in_b)
+    sp, ns, k5 = _sel(sel)
+    Bt, L, Dn, N, H, G, K = (cfg[k] for k in ("batch", "seqlen", "d_inner", "d_state", "n_heads", "n_groups", "d_conv"))
+    n_sel = ns if sel is not None else Dn
+    conv_ch = Dn + (2 * G * N if cfg.get("conv_bc", 0) else 0)
+    do = _f64(dout)
+    assert do.size == Bt * L * n_sel * (2 if cfg.get("combine", 0) else 1)
+
+    def input_grads():
+        g = dict(dx=np.zeros((Bt, L, n_sel)), dz=np.zeros((Bt, L, n_sel)), ddt=np.zeros((Bt, L, H)),
+                 dB=np.zeros((Bt, L, G, N)), dC=np.zeros((Bt, L, G, N)))
+        return g, InputGrads(*[_ptr(g[k]) for k in ("dx", "dz", "ddt", "dB", "dC")])
+
+    def param_grads():
+        g = dict(dconv_w=np.zeros((conv_ch, K)), dconv_b=np.zeros(conv_ch),
+                 dA=np.zeros((H, N) if cfg.get("a_kind", 0) == 0 else (H,)),
+                 dD=np.zeros(Dn if cfg.get("d_kind", 0) == 0 else H), ddt_bias=np.zeros(H))
+        return g, ParamGrads(*[_ptr(g[k]) for k in ("dconv_w", "dconv_b", "dA", "dD", "ddt_bias")])
+
+    gf, cgf = input_grads()
+    gb, cgb = (gf, cgf) if in_b is None else input_grads()
+    qf, cqf = param_grads()
+    qb, cqb = param_grads()
+    fn = lib().orc_bimamba_bwd
+    fn.restype = C.c_int
+    rc = fn(C.byref(d), C.byref(pf), C.byref(pb), C.byref(i_f), C.byref(i_b), sp, C.c_int(ns), _ptr(do),
+            C.byref(cgf), C.byref(cgb), C.byref(cqf), C.byref(cqb))
+    if rc != 0:
+        raise ValueError("oracle: shape outside the definition")
+    return gf, (None if in_b is None else gb), qf, qb

@@ -17,6 +17,10 @@
  * rounded on the way out.  No blocking, chunking, fusion or reordering: one
  * (batch, channel) row at a time, one token at a time, one state at a time.
  *
+ * Pins of the gradients (tests/test_oracle_bwd_pins.py): central finite differences of orc_bimamba_fwd with
+ * Richardson extrapolation, for every input and parameter element on small shapes; automatic differentiation of the
+ * same definition written with a tensor library's differentiable ops.
+ *
  * Pins (tests/test_oracle_pins.py): L=1 closed form, A=0 weighted cumulative
  * sum, geometric closed form, brute-force y = M x for L<=16, reverse ==
  * flip(forward(flip)), library depthwise convolution, split-anywhere state
@@ -285,6 +289,191 @@ int orc_one_direction(const orc_desc *d, const orc_params *p, const orc_inputs *
         one_direction(d, p, in, b, dir, NULL, Dn, h0, he,
                       tail_in ? tail_in + (long)b * (K - 1) * tail_ch : NULL,
                       g + (long)b * L * Dn, Dn);
+    }
+    return 0;
+}
+
+/*
+ * ---- Gradients (the paper trains these models, App. A.2; it gives no backward algorithm, so this is the chain rule
+ * of the forward definition above, one row, one token, one state at a time, in the reverse of the scan order).
+ *
+ * For one direction and one (batch, channel) row, with t running over the scan order and t- the step before t:
+ *   pre_t = cb + sum_k w_k x_{t - dir*(K-1-k)}      xc_t = silu(pre_t)
+ *   delta_t = dt_t  or  softplus(dt_t + bias)       a_t[n] = exp(delta_t A[n])
+ *   h_t[n] = a_t[n] h_{t-}[n] + delta_t B_t[n] xc_t
+ *   y_t = sum_n C_t[n] h_t[n] + D xc_t              g_t = y_t silu(z_t)
+ * Given dg_t (the upstream gradient of g_t):
+ *   dz_t += dg_t y_t silu'(z_t)                     dy_t = dg_t silu(z_t)
+ *   dh_t[n] = C_t[n] dy_t + a_{t+}[n] dh_{t+}[n]    (t+ the step after t; zero after the last step)
+ *   dC_t[n] += dy_t h_t[n]                          dD += dy_t xc_t
+ *   dA[n] += dh_t[n] h_{t-}[n] a_t[n] delta_t       dB_t[n] += dh_t[n] delta_t xc_t
+ *   ddelta_t = sum_n dh_t[n] (h_{t-}[n] a_t[n] A[n] + B_t[n] xc_t)
+ *   dxc_t = D dy_t + sum_n dh_t[n] delta_t B_t[n]   dpre_t = dxc_t silu'(pre_t)
+ *   ddt_t += ddelta_t (times sigmoid(dt_t + bias) with softplus, which also feeds dbias)
+ *   dcb += dpre_t;  dw_k += dpre_t x_{t - dir*(K-1-k)};  dx_{t - dir*(K-1-k)} += w_k dpre_t
+ * With conv_bc, B_t and C_t are themselves silu(conv(raw)) and their gradients go through the same conv rule.
+ * All outputs are accumulated into (+=): the caller zeroes them and may pass the same arrays for both directions.
+ */
+typedef struct { double *dx, *dz, *ddt, *dB, *dC; } orc_input_grads;   /* dx, dz [batch][L][n_sel]; ddt [batch][L][H]; dB, dC [batch][L][G*N] */
+typedef struct { double *dconv_w, *dconv_b, *dA, *dD, *ddt_bias; } orc_param_grads; /* shaped like the parameters */
+
+static double dsilu(double v) { const double s = 1.0 / (1.0 + exp(-v)); return s * (1.0 + v * (1.0 - s)); }
+static double sigmoid(double v) { return 1.0 / (1.0 + exp(-v)); }
+
+/* gradient of silu(conv(src)) for one channel: dval[t] is the gradient of the conv+SiLU output at t */
+static void conv_silu_1ch_bwd(const float *src, long stride, int L, int K, const float *w, double bias, int dir,
+                              const double *dval, double *dsrc, long dstride, double *dw, double *db)
+{
+    for (int t = 0; t < L; t++) {
+        double acc = bias;
+        for (int k = 0; k < K; k++) {
+            int idx = t - dir * (K - 1 - k);
+            if (idx >= 0 && idx < L) acc += (double)w[k] * (double)src[(long)idx * stride];
+        }
+        const double dpre = dval[t] * dsilu(acc);
+        if (db) *db += dpre;
+        for (int k = 0; k < K; k++) {
+            int idx = t - dir * (K - 1 - k);
+            if (idx >= 0 && idx < L) {
+                dw[k] += dpre * (double)src[(long)idx * stride];
+                dsrc[(long)idx * dstride] += (double)w[k] * dpre;
+            }
+        }
+    }
+}
+
+static void one_direction_bwd(const orc_desc *d, const orc_params *p, const orc_inputs *in, int b, int dir,
+                              const int *sel, int n_sel, const double *dg, long dg_stride,
+                              const orc_input_grads *gi, const orc_param_grads *gp)
+{
+    const int L = d->seqlen, Dn = d->d_inner, N = d->d_state, H = d->n_heads, G = d->n_groups, K = d->d_conv;
+    const int P = Dn / H, HG = H / G, GN = G * N;
+    const float *xb = in->x + (long)b * L * Dn, *zb = in->z + (long)b * L * Dn;
+    const float *dtb = in->dt + (long)b * L * H;
+    const float *Bb = in->B + (long)b * L * GN, *Cb = in->C + (long)b * L * GN;
+    double *Bc = (double *)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1) * GN);
+    double *Cc = (double *)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1) * GN);
+    double *dBc = (double *)calloc((size_t)(L > 0 ? L : 1) * GN, sizeof(double));
+    double *dCc = (double *)calloc((size_t)(L > 0 ? L : 1) * GN, sizeof(double));
+    double *col = (double *)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1));
+    if (d->conv_bc) {
+        for (int j = 0; j < GN; j++)
+            for (int which = 0; which < 2; which++) {
+                int ch = Dn + which * GN + j;
+                conv_silu_1ch((which ? Cb : Bb) + j, GN, L, K, p->conv_w + (long)ch * K,
+                              p->conv_b ? (double)p->conv_b[ch] : 0.0, dir, NULL, col);
+                for (int t = 0; t < L; t++) (which ? Cc : Bc)[(long)t * GN + j] = col[t];
+            }
+    } else {
+        for (long i = 0; i < (long)L * GN; i++) { Bc[i] = (double)Bb[i]; Cc[i] = (double)Cb[i]; }
+    }
+    double *xc = (double *)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1));
+    double *delta = (double *)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1));
+    double *dxc = (double *)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1));
+    double *hall = (double *)malloc(sizeof(double) * (size_t)(L + 1) * N);   /* hall[step+1] = state after scan step `step` */
+    double *dh = (double *)malloc(sizeof(double) * (size_t)N);
+    double *Arow = (double *)malloc(sizeof(double) * (size_t)N);
+    for (int s = 0; s < n_sel; s++) {
+        const int ch = sel ? sel[s] : s;
+        const int head = ch / P, grp = head / HG;
+        const double bias = (d->dt_softplus && p->dt_bias) ? (double)p->dt_bias[head] : 0.0;
+        conv_silu_1ch(xb + ch, Dn, L, K, p->conv_w + (long)ch * K, p->conv_b ? (double)p->conv_b[ch] : 0.0, dir, NULL, xc);
+        for (int t = 0; t < L; t++) {
+            double v = (double)dtb[(long)t * H + head];
+            delta[t] = d->dt_softplus ? softplus(v + bias) : v;
+        }
+        for (int n = 0; n < N; n++) Arow[n] = d->a_kind == 0 ? (double)p->A[(long)head * N + n] : (double)p->A[head];
+        const double Dval = d->d_kind == 0 ? (double)p->D[ch] : (double)p->D[head];
+        /* forward, keeping every state */
+        for (int n = 0; n < N; n++) hall[n] = 0.0;
+        {
+            int t = dir > 0 ? 0 : L - 1;
+            for (int step = 0; step < L; step++, t += dir) {
+                const double *Bt = Bc + (long)t * GN + (long)grp * N;
+                for (int n = 0; n < N; n++)
+                    hall[(long)(step + 1) * N + n] = exp(delta[t] * Arow[n]) * hall[(long)step * N + n] + delta[t] * Bt[n] * xc[t];
+            }
+        }
+        /* backward, last scan step first */
+        for (int n = 0; n < N; n++) dh[n] = 0.0;
+        {
+            int t = dir > 0 ? L - 1 : 0;
+            for (int step = L - 1; step >= 0; step--, t -= dir) {
+                const double *Bt = Bc + (long)t * GN + (long)grp * N, *Ct = Cc + (long)t * GN + (long)grp * N;
+                double *dBt = dBc + (long)t * GN + (long)grp * N, *dCt = dCc + (long)t * GN + (long)grp * N;
+                const double *hcur = hall + (long)(step + 1) * N, *hprev = hall + (long)step * N;
+                const double zv = (double)zb[(long)t * Dn + ch];
+                const double dgt = dg[(long)t * dg_stride + s];
+                double y = Dval * xc[t];
+                for (int n = 0; n < N; n++) y += Ct[n] * hcur[n];
+                gi->dz[((long)b * L + t) * n_sel + s] += dgt * y * dsilu(zv);
+                const double dy = dgt * silu(zv);
+                double ddelta = 0.0, dxct = Dval * dy;
+                if (gp->dD) gp->dD[d->d_kind == 0 ? ch : head] += dy * xc[t];
+                for (int n = 0; n < N; n++) {
+                    const double a = exp(delta[t] * Arow[n]);
+                    dh[n] += Ct[n] * dy;
+                    dCt[n] += dy * hcur[n];
+                    if (gp->dA) gp->dA[d->a_kind == 0 ? (long)head * N + n : head] += dh[n] * hprev[n] * a * delta[t];
+                    dBt[n] += dh[n] * delta[t] * xc[t];
+                    ddelta += dh[n] * (hprev[n] * a * Arow[n] + Bt[n] * xc[t]);
+                    dxct += dh[n] * delta[t] * Bt[n];
+                    dh[n] *= a;
+                }
+                if (d->dt_softplus) {
+                    const double sg = sigmoid((double)dtb[(long)t * H + head] + bias);
+                    gi->ddt[((long)b * L + t) * H + head] += ddelta * sg;
+                    if (gp->ddt_bias) gp->ddt_bias[head] += ddelta * sg;
+                } else {
+                    gi->ddt[((long)b * L + t) * H + head] += ddelta;
+                }
+                dxc[t] = dxct;
+            }
+        }
+        conv_silu_1ch_bwd(xb + ch, Dn, L, K, p->conv_w + (long)ch * K, p->conv_b ? (double)p->conv_b[ch] : 0.0, dir,
+                          dxc, gi->dx + (long)b * L * n_sel + s, n_sel, gp->dconv_w + (long)ch * K,
+                          gp->dconv_b ? gp->dconv_b + ch : NULL);
+    }
+    /* B and C: straight through, or back through their own conv + SiLU */
+    if (d->conv_bc) {
+        for (int j = 0; j < GN; j++)
+            for (int which = 0; which < 2; which++) {
+                int ch = Dn + which * GN + j;
+                for (int t = 0; t < L; t++) col[t] = (which ? dCc : dBc)[(long)t * GN + j];
+                conv_silu_1ch_bwd((which ? Cb : Bb) + j, GN, L, K, p->conv_w + (long)ch * K,
+                                  p->conv_b ? (double)p->conv_b[ch] : 0.0, dir, col,
+                                  (which ? gi->dC : gi->dB) + (long)b * L * GN + j, GN, gp->dconv_w + (long)ch * K,
+                                  gp->dconv_b ? gp->dconv_b + ch : NULL);
+            }
+    } else {
+        for (long i = 0; i < (long)L * GN; i++) {
+            gi->dB[(long)b * L * GN + i] += dBc[i];
+            gi->dC[(long)b * L * GN + i] += dCc[i];
+        }
+    }
+    free(Bc); free(Cc); free(dBc); free(dCc); free(col); free(xc); free(delta); free(dxc); free(hall); free(dh); free(Arow);
+}
+
+/*
+ * Gradients of the full-sequence path (orc_bimamba_fwd) given dout, the gradient of its output:
+ * dout [batch][L][n_sel] (ADD: both directions receive it) or [batch][L][2][n_sel] (SEPARATE: half 0 forward).
+ * gin_f / gin_b and gpf / gpb may point at the same arrays when the directions share inputs or parameters.
+ */
+int orc_bimamba_bwd(const orc_desc *d, const orc_params *pf, const orc_params *pb,
+                    const orc_inputs *in_f, const orc_inputs *in_b, const int *sel, int n_sel, const double *dout,
+                    const orc_input_grads *gin_f, const orc_input_grads *gin_b,
+                    const orc_param_grads *gpf, const orc_param_grads *gpb)
+{
+    if (d->batch < 0 || d->seqlen < 0 || d->d_inner < 1 || d->d_state < 1 || d->n_heads < 1 || d->n_groups < 1) return -1;
+    if (d->d_inner % d->n_heads || d->n_heads % d->n_groups || d->d_conv < 1 || d->d_conv > 8) return -1;
+    if (!sel) n_sel = d->d_inner;
+    const int L = d->seqlen;
+    const long per_b = (long)L * n_sel * (d->combine ? 2 : 1);
+    const long stride = (long)n_sel * (d->combine ? 2 : 1);
+    for (int b = 0; b < d->batch; b++) {
+        const double *dob = dout + (long)b * per_b;
+        one_direction_bwd(d, pf, in_f, b, +1, sel, n_sel, dob, stride, gin_f, gpf);
+        one_direction_bwd(d, pb, in_b, b, -1, sel, n_sel, dob + (d->combine ? n_sel : 0), stride, gin_b, gpb);
     }
     return 0;
 }
