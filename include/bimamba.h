@@ -187,6 +187,50 @@ int bimamba_block_fwd_static(const bimamba_desc* desc, const bimamba_params* pf,
                              const float* h_in, const void* tail_in, float* h_out, void* tail_out,
                              const bimamba_tensor* out, void* hip_stream);
 
+/* Gradients with respect to the activations one direction read.  dx, dz [batch, L, d_inner] and ddt [batch, L, n_heads]
+ * are views in io_dtype like the inputs (written, one rounding each); dB, dC are contiguous fp32
+ * [batch, L, n_groups, d_state] device arrays (sums over the channels of a group are formed in fp32 with atomics; the
+ * library zeroes them first, it does not accumulate into what the caller left there). */
+typedef struct bimamba_input_grads {
+    bimamba_tensor dx, dz, ddt;
+    float* dB;
+    float* dC;
+} bimamba_input_grads;
+
+/* Gradients with respect to one direction's parameters: device pointers, fp32, contiguous, shaped like bimamba_params;
+ * sums over batch and tokens, zeroed by the library first.  dconv_b / ddt_bias may be NULL (not wanted). */
+typedef struct bimamba_param_grads {
+    float* dconv_w;
+    float* dconv_b;
+    float* dA;
+    float* dD;
+    float* ddt_bias;
+} bimamba_param_grads;
+
+/*
+ * Gradients of bimamba_fwd (the paper trains the model, App. A.2; the backward rule is the chain rule of eqs. 4-6 in
+ * the selective form, stated in csrc/bwd_kernels.h).
+ *   desc, pf, pb, in_f, in_b   as for bimamba_fwd (in_b == NULL or == in_f: both directions read the same activations).
+ *   dout        gradient of bimamba_fwd's out: [batch, L, d_inner] (ADD) or [batch, L, 2*d_inner] (SEPARATE), io_dtype.
+ *   din_f       gradients w.r.t. in_f; with shared activations they hold the sum of both directions' contributions
+ *               and din_b must be NULL.  With separate activations din_b is required.
+ *   dpf, dpb    gradients w.r.t. pf and pb.  If pb == pf (tied weights) the caller adds dpb to dpf; the two must still
+ *               be distinct buffers.
+ *   workspace   at least bimamba_bwd_workspace_bytes(desc) bytes, 16-byte aligned.
+ * Supported: the selective-scan layout, i.e. n_heads == d_inner (Delta, A, D per channel), a_kind PER_HEAD_STATE,
+ * d_kind PER_CHANNEL, conv_bc 0, d_state 4, 8 or 16; every other descriptor returns BIMAMBA_ERR_UNSUPPORTED.
+ * Nothing may overlap: the gradient views among themselves, the inputs, dout.  (Not checked.)
+ */
+int bimamba_bwd(const bimamba_desc* desc, const bimamba_params* pf, const bimamba_params* pb,
+                const bimamba_inputs* in_f, const bimamba_inputs* in_b, const bimamba_tensor* dout,
+                const bimamba_input_grads* din_f, const bimamba_input_grads* din_b,
+                const bimamba_param_grads* dpf, const bimamba_param_grads* dpb,
+                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Workspace of bimamba_bwd: fp32 B|C rows, the state entering every chunk of 8 (16 for d_state 4) tokens for both
+ * directions (2 * batch * ceil(L / chunk) * d_inner * d_state floats) and three fp32 planes of 2 * batch * L * d_inner. */
+size_t bimamba_bwd_workspace_bytes(const bimamba_desc* desc);
+
 /* Bytes of device scratch the two calls above need for this descriptor (0 on an invalid descriptor).  Pure host code. */
 size_t bimamba_workspace_bytes(const bimamba_desc* desc, int block_variant);
 

@@ -21,8 +21,9 @@ STATUS = {0: "BIMAMBA_OK", -1: "BIMAMBA_ERR_NULL_POINTER", -2: "BIMAMBA_ERR_BAD_
           -7: "BIMAMBA_ERR_SCRATCH_EXCEEDED", -8: "BIMAMBA_ERR_ALIAS"}
 STATIC_SCRATCH_BYTES = 64 << 20
 
-EXPORTS = ("bimamba_fwd", "bimamba_block_fwd", "bimamba_block_fwd_static", "bimamba_workspace_bytes", "bimamba_time_chunks",
-           "bimamba_profile_next_call", "bimamba_status_string", "bimamba_version")
+EXPORTS = ("bimamba_fwd", "bimamba_block_fwd", "bimamba_block_fwd_static", "bimamba_bwd", "bimamba_workspace_bytes",
+           "bimamba_bwd_workspace_bytes", "bimamba_time_chunks", "bimamba_profile_next_call", "bimamba_status_string",
+           "bimamba_version")
 
 
 class Desc(C.Structure):
@@ -41,6 +42,14 @@ class Tensor(C.Structure):
 
 class Inputs(C.Structure):
     _fields_ = [(n, Tensor) for n in ("x", "z", "dt", "B", "C")]
+
+
+class InputGrads(C.Structure):
+    _fields_ = [("dx", Tensor), ("dz", Tensor), ("ddt", Tensor), ("dB", C.c_void_p), ("dC", C.c_void_p)]
+
+
+class ParamGrads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("dconv_w", "dconv_b", "dA", "dD", "ddt_bias")]
 
 
 class BimambaError(RuntimeError):
@@ -72,6 +81,12 @@ def lib():
         L.bimamba_block_fwd_static.argtypes = [C.POINTER(Desc), C.POINTER(Params), C.POINTER(Params), C.POINTER(Inputs),
                                                C.POINTER(Inputs), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                C.POINTER(Tensor), C.c_void_p]
+        L.bimamba_bwd.restype = C.c_int
+        L.bimamba_bwd.argtypes = [C.POINTER(Desc), C.POINTER(Params), C.POINTER(Params), C.POINTER(Inputs),
+                                  C.POINTER(Inputs), C.POINTER(Tensor), C.POINTER(InputGrads), C.POINTER(InputGrads),
+                                  C.POINTER(ParamGrads), C.POINTER(ParamGrads), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.bimamba_bwd_workspace_bytes.restype = C.c_size_t
+        L.bimamba_bwd_workspace_bytes.argtypes = [C.POINTER(Desc)]
         L.bimamba_workspace_bytes.restype = C.c_size_t
         L.bimamba_workspace_bytes.argtypes = [C.POINTER(Desc), C.c_int]
         L.bimamba_time_chunks.restype = C.c_int
@@ -109,7 +124,7 @@ def make_params(p):
 
 def make_tensor(t):
     """[batch, L, channels] view with unit channel stride (batch/token strides are passed through)."""
-    assert t.dim() == 3 and (t.shape[2] == 1 or t.stride(2) == 1), "channel dimension must be contiguous"
+    assert t.dim() == 3 and (t.numel() == 0 or t.shape[2] == 1 or t.stride(2) == 1), "channel dimension must be contiguous"
     return Tensor(t.data_ptr(), t.stride(0), t.stride(1))
 
 
@@ -158,6 +173,40 @@ def bimamba_fwd(desc, pf, pb, in_f, in_b, out, workspace, stream=None, check=Tru
                            None if in_b is None else C.byref(in_b), C.byref(out), ws_ptr, ws_bytes, _stream_ptr(stream))
     if check and rc != 0:
         raise BimambaError(rc, "bimamba_fwd")
+    return rc
+
+
+def make_input_grads(g):
+    """g: dict of device tensors dx, dz [Bt,L,Dn], ddt [Bt,L,H] (io dtype, unit channel stride) and dB, dC
+    [Bt,L,G,N] float32 contiguous."""
+    for k in ("dB", "dC"):
+        assert g[k].dtype == torch.float32 and g[k].is_contiguous(), k
+    return InputGrads(make_tensor(g["dx"]), make_tensor(g["dz"]), make_tensor(g["ddt"]), g["dB"].data_ptr(), g["dC"].data_ptr())
+
+
+def make_param_grads(g):
+    """g: dict of float32 contiguous device tensors dconv_w, dA, dD and optionally dconv_b, ddt_bias."""
+    for k in ("dconv_w", "dconv_b", "dA", "dD", "ddt_bias"):
+        t = g.get(k)
+        if t is not None:
+            assert t.dtype == torch.float32 and t.is_contiguous(), k
+    return ParamGrads(_ptr(g["dconv_w"]), _ptr(g.get("dconv_b")), _ptr(g["dA"]), _ptr(g["dD"]), _ptr(g.get("ddt_bias")))
+
+
+def bimamba_bwd_workspace_bytes(desc):
+    return int(lib().bimamba_bwd_workspace_bytes(C.byref(desc)))
+
+
+def bimamba_bwd(desc, pf, pb, in_f, in_b, dout, din_f, din_b, dpf, dpb, workspace, stream=None, check=True):
+    """Enqueue the gradients of bimamba_fwd.  dout: Tensor; din_f/din_b: InputGrads (din_b None with shared
+    activations); dpf/dpb: ParamGrads; workspace: uint8 device tensor of bimamba_bwd_workspace_bytes(desc)."""
+    ws_ptr = None if workspace is None else C.c_void_p(workspace.data_ptr())
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().bimamba_bwd(C.byref(desc), C.byref(pf), C.byref(pb), C.byref(in_f), None if in_b is None else C.byref(in_b),
+                           C.byref(dout), C.byref(din_f), None if din_b is None else C.byref(din_b), C.byref(dpf),
+                           C.byref(dpb), ws_ptr, ws_bytes, _stream_ptr(stream))
+    if check and rc != 0:
+        raise BimambaError(rc, "bimamba_bwd")
     return rc
 
 

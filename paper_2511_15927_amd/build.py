@@ -33,7 +33,7 @@ def newest_dep(src, newest_all):
     """Modification time an object must beat: its source and the headers that source includes."""
     text = open(src).read()
     deps = [src, os.path.join(ROOT, "include", "bimamba.h")]
-    for h in ("kernels.h", "launch.h", "ssd_kernels.h"):
+    for h in ("kernels.h", "launch.h", "ssd_kernels.h", "ssd_wide.h", "bwd_kernels.h"):
         if h in text or (h == "kernels.h"):
             deps.append(os.path.join(CSRC, h))
     return max(os.path.getmtime(p) for p in deps)
@@ -48,6 +48,7 @@ def build(force: bool = True, jobs: int = 8):
         units.append((os.path.join(CSRC, "scan_inst.hip"), os.path.join(OBJ, "scan_n%d_s%d.o" % (n, s)),
                       ["-DBM_N=%d" % n, "-DBM_S=%d" % s]))
     units.append((os.path.join(CSRC, "ssd_inst.hip"), os.path.join(OBJ, "ssd_inst.o"), []))
+    units.append((os.path.join(CSRC, "bwd_inst.hip"), os.path.join(OBJ, "bwd_inst.o"), []))
     newest = max(os.path.getmtime(p) for p in sources())
     todo = [u for u in units if force or not os.path.exists(u[1]) or os.path.getmtime(u[1]) < newest_dep(u[0], newest)]
     cmds = [["hipcc"] + FLAGS + extra + ["-c", src, "-o", obj] for src, obj, extra in todo]

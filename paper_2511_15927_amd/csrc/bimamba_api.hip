@@ -2,6 +2,7 @@
 #include "bimamba.h"
 #include "kernels.h"
 #include "launch.h"
+#include "bwd_kernels.h"
 #include "ssd_kernels.h"
 
 #include <hip/hip_runtime.h>
@@ -305,6 +306,7 @@ int check_tensor(const bimamba_tensor& t, int channels, size_t elem, const bimam
     const bool empty = d->batch == 0 || d->seqlen == 0;  // nothing is read or written: the pointer may be NULL
     if (!t.ptr && !empty) return BIMAMBA_ERR_NULL_POINTER;
     if (!is_aligned(t.ptr, elem)) return BIMAMBA_ERR_MISALIGNED;
+    if (empty) return BIMAMBA_OK;                         // no element exists, so no stride is ever used
     if (t.stride_token < channels) return BIMAMBA_ERR_BAD_SHAPE;
     if (t.stride_token > kMaxTokenStride) return BIMAMBA_ERR_UNSUPPORTED;  // row offsets inside a tile are 32-bit
     if (d->batch > 1 && t.stride_batch < (int64_t)d->seqlen * t.stride_token - (t.stride_token - channels))
@@ -632,6 +634,160 @@ int bimamba_block_fwd_static(const bimamba_desc* desc, const bimamba_params* pf,
     if ((rc = static_scratch(&ws))) return rc;
     return run(desc, pf, pb, in_f, in_b, h_in, tail_in, h_out, tail_out, out, ws, BIMAMBA_STATIC_SCRATCH_BYTES, hip_stream,
                true);
+}
+
+// ---- gradients -------------------------------------------------------------------------------------------------
+namespace {
+struct BwdPlan {
+    int chunk, nchunk;
+    size_t off_bc[2], off_state, off_dx, off_dz, off_ddt, total;
+};
+
+int check_bwd_desc(const bimamba_desc* d)
+{
+    const int rc = check_desc(d);
+    if (rc) return rc;
+    if (d->n_heads != d->d_inner || d->a_kind != BIMAMBA_A_PER_HEAD_STATE || d->d_kind != BIMAMBA_D_PER_CHANNEL ||
+        d->conv_bc || !bm::bwd_supported(d->d_state))
+        return BIMAMBA_ERR_UNSUPPORTED;
+    return BIMAMBA_OK;
+}
+
+BwdPlan make_bwd_plan(const bimamba_desc* d)
+{
+    BwdPlan p{};
+    p.chunk = bm::bwd_chunk_tokens(d->d_state);
+    p.nchunk = d->seqlen > 0 ? (d->seqlen + p.chunk - 1) / p.chunk : 1;
+    const size_t bc = align_up((size_t)d->batch * d->seqlen * d->n_groups * 2 * d->d_state * sizeof(float), 256);
+    const size_t plane = align_up((size_t)2 * d->batch * d->seqlen * d->d_inner * sizeof(float), 256);
+    size_t off = 0;
+    p.off_bc[0] = off; off += bc;
+    p.off_bc[1] = off; off += bc;    // sized for separate activations
+    p.off_state = off; off += align_up((size_t)2 * d->batch * p.nchunk * d->d_inner * d->d_state * sizeof(float), 256);
+    p.off_dx = off; off += plane;
+    p.off_dz = off; off += plane;
+    p.off_ddt = off; off += plane;
+    p.total = off;
+    return p;
+}
+}  // namespace
+
+int bimamba_bwd(const bimamba_desc* d, const bimamba_params* pf, const bimamba_params* pb, const bimamba_inputs* in_f,
+                const bimamba_inputs* in_b, const bimamba_tensor* dout, const bimamba_input_grads* din_f,
+                const bimamba_input_grads* din_b, const bimamba_param_grads* dpf, const bimamba_param_grads* dpb,
+                void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    int rc = check_bwd_desc(d);
+    if (rc) return rc;
+    const size_t elem = d->io_dtype == BIMAMBA_BF16 ? 2 : 4;
+    if ((rc = check_params(pf))) return rc;
+    if ((rc = check_params(pb))) return rc;
+    if (!in_f || !dout || !din_f || !dpf || !dpb) return BIMAMBA_ERR_NULL_POINTER;
+    if (!in_b) in_b = in_f;
+    if ((rc = check_inputs(in_f, d, elem))) return rc;
+    if ((rc = check_inputs(in_b, d, elem))) return rc;
+    const bool shared = same_inputs(in_f, in_b);
+    if (shared ? din_b != nullptr && din_b != din_f : din_b == nullptr) return BIMAMBA_ERR_NULL_POINTER;
+    if (shared) din_b = nullptr;
+    const int out_ch = d->combine == BIMAMBA_COMBINE_SEPARATE ? 2 * d->d_inner : d->d_inner;
+    if ((rc = check_tensor(*dout, out_ch, elem, d))) return rc;
+    const bool live = d->batch > 0 && d->seqlen > 0;
+    for (const bimamba_input_grads* g : {din_f, din_b}) {
+        if (!g) continue;
+        if ((rc = check_tensor(g->dx, d->d_inner, elem, d))) return rc;
+        if ((rc = check_tensor(g->dz, d->d_inner, elem, d))) return rc;
+        if ((rc = check_tensor(g->ddt, d->n_heads, elem, d))) return rc;
+        if (live && (!g->dB || !g->dC)) return BIMAMBA_ERR_NULL_POINTER;
+        if (!is_aligned(g->dB, 4) || !is_aligned(g->dC, 4)) return BIMAMBA_ERR_MISALIGNED;
+    }
+    if (dpf == dpb) return BIMAMBA_ERR_ALIAS;
+    for (const bimamba_param_grads* g : {dpf, dpb}) {
+        if (!g->dconv_w || !g->dA || !g->dD) return BIMAMBA_ERR_NULL_POINTER;
+        if (!is_aligned(g->dconv_w, 4) || !is_aligned(g->dA, 4) || !is_aligned(g->dD, 4) || !is_aligned(g->dconv_b, 4) ||
+            !is_aligned(g->ddt_bias, 4))
+            return BIMAMBA_ERR_MISALIGNED;
+    }
+    const BwdPlan plan = make_bwd_plan(d);
+    if (!workspace) return BIMAMBA_ERR_NULL_POINTER;
+    if (!is_aligned(workspace, 16)) return BIMAMBA_ERR_MISALIGNED;
+    if (workspace_bytes < plan.total) return BIMAMBA_ERR_WORKSPACE_TOO_SMALL;
+
+    const hipError_t pending = hipPeekAtLastError();
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(workspace);
+    const int GN = d->n_groups * d->d_state;
+    const bool bf16 = d->io_dtype == BIMAMBA_BF16;
+
+    // parameter gradients are sums over the batch: zero them even for an empty call
+    for (const bimamba_param_grads* g : {dpf, dpb}) {
+        bm::launch_bwd_zero(g->dconv_w, (long long)d->d_inner * d->d_conv, st);
+        bm::launch_bwd_zero(g->dconv_b, d->d_inner, st);
+        bm::launch_bwd_zero(g->dA, (long long)d->d_inner * d->d_state, st);
+        bm::launch_bwd_zero(g->dD, d->d_inner, st);
+        bm::launch_bwd_zero(g->ddt_bias, d->d_inner, st);
+    }
+    if (live) {
+        const int nbuf = shared ? 1 : 2;
+        for (int s = 0; s < nbuf; s++) {
+            const bimamba_inputs* in = s == 0 ? in_f : in_b;
+            PrepArgs pa{};
+            pa.B = targ(in->B);
+            pa.C = targ(in->C);
+            pa.dst = reinterpret_cast<float*>(ws + plan.off_bc[s]);
+            pa.batch = d->batch; pa.L = d->seqlen; pa.G = d->n_groups; pa.N = d->d_state; pa.K = d->d_conv;
+            pa.Dn = d->d_inner; pa.tail_ch = d->d_inner; pa.conv_bc = 0; pa.dir = s == 0 ? 1 : -1;
+            const long long total = (long long)d->batch * d->seqlen * 2 * GN;
+            const dim3 grid((unsigned)((total + 255) / 256));
+            if (bf16) hipLaunchKernelGGL(prep_bc_kernel<IoBF16>, grid, dim3(256), 0, st, pa);
+            else hipLaunchKernelGGL(prep_bc_kernel<IoF32>, grid, dim3(256), 0, st, pa);
+        }
+        const long long bc_elems = (long long)d->batch * d->seqlen * GN;
+        bm::launch_bwd_zero(din_f->dB, bc_elems, st);
+        bm::launch_bwd_zero(din_f->dC, bc_elems, st);
+        if (din_b) {
+            bm::launch_bwd_zero(din_b->dB, bc_elems, st);
+            bm::launch_bwd_zero(din_b->dC, bc_elems, st);
+        }
+        BwdArgs a{};
+        for (int s = 0; s < 2; s++) {
+            const bimamba_inputs* in = s == 0 ? in_f : in_b;
+            const bimamba_params* p = s == 0 ? pf : pb;
+            const bimamba_param_grads* g = s == 0 ? dpf : dpb;
+            const bimamba_input_grads* gi = (s == 0 || !din_b) ? din_f : din_b;
+            DirArgs& da = a.dir[s];
+            da.x = targ(in->x); da.z = targ(in->z); da.dt = targ(in->dt);
+            da.bc = reinterpret_cast<const float*>(ws + plan.off_bc[shared ? 0 : s]);
+            da.conv_w = p->conv_w; da.conv_b = p->conv_b; da.A = p->A; da.D = p->D; da.dt_bias = p->dt_bias;
+            a.dB[s] = gi->dB; a.dC[s] = gi->dC;
+            a.dA[s] = g->dA; a.dD[s] = g->dD; a.dconv_w[s] = g->dconv_w; a.dconv_b[s] = g->dconv_b; a.ddt_bias[s] = g->ddt_bias;
+        }
+        a.dout = targ(*dout);
+        a.state = reinterpret_cast<float*>(ws + plan.off_state);
+        a.dx = reinterpret_cast<float*>(ws + plan.off_dx);
+        a.dz = reinterpret_cast<float*>(ws + plan.off_dz);
+        a.ddt = reinterpret_cast<float*>(ws + plan.off_ddt);
+        a.L = d->seqlen; a.Dn = d->d_inner; a.G = d->n_groups; a.K = d->d_conv; a.nchunk = plan.nchunk;
+        a.dt_softplus = d->dt_softplus; a.separate = d->combine == BIMAMBA_COMBINE_SEPARATE;
+        bm::launch_bwd(d->d_state, bf16, a, d->batch, st);
+        const float* planes[3] = {a.dx, a.dz, a.ddt};
+        for (int k = 0; k < 3; k++) {
+            BwdFinishArgs fa{};
+            fa.src = planes[k];
+            const bimamba_tensor& t0 = k == 0 ? din_f->dx : k == 1 ? din_f->dz : din_f->ddt;
+            fa.dst[0] = targ(t0);
+            if (din_b) fa.dst[1] = targ(k == 0 ? din_b->dx : k == 1 ? din_b->dz : din_b->ddt);
+            fa.batch = d->batch; fa.L = d->seqlen; fa.C = d->d_inner;
+            bm::launch_bwd_finish(bf16, fa, st);
+        }
+    }
+    const hipError_t now = hipPeekAtLastError();
+    return (now == hipSuccess || now == pending) ? BIMAMBA_OK : BIMAMBA_ERR_HIP;
+}
+
+size_t bimamba_bwd_workspace_bytes(const bimamba_desc* desc)
+{
+    if (check_bwd_desc(desc)) return 0;
+    return make_bwd_plan(desc).total;
 }
 
 size_t bimamba_workspace_bytes(const bimamba_desc* desc, int block_variant)

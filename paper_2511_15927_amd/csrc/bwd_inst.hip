@@ -1,0 +1,58 @@
+// Host launchers of the gradient kernels (bwd_kernels.h), instantiated for the state counts the selective-scan layout
+// uses with one lane per chain.
+#include "bwd_kernels.h"
+#include "launch.h"
+
+namespace bm {
+
+bool bwd_supported(int d_state) { return d_state == 4 || d_state == 8 || d_state == 16; }
+int bwd_chunk_tokens(int d_state) { return d_state <= 4 ? kBwdChunk<4> : d_state <= 8 ? kBwdChunk<8> : kBwdChunk<16>; }
+
+// Zeroes a float buffer (the accumulation targets of the atomics above); a kernel rather than a memset node so that
+// the call can be captured into a graph.
+__global__ __launch_bounds__(256) void bwd_zero_kernel(float* p, long long n)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0.0f;
+}
+
+template <int N, typename IO>
+static void launch_pair(const BwdArgs& a, int batch, hipStream_t st)
+{
+    const dim3 grid((unsigned)(((a.Dn + 63) / 64 + 1) / 2), 1, (unsigned)batch);
+    hipLaunchKernelGGL((bwd_state_kernel<N, IO>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((bwd_kernel<N, IO>), grid, dim3(256), 0, st, a);
+}
+
+void launch_bwd(int d_state, int io_bf16, const BwdArgs& a, int batch, hipStream_t st)
+{
+#define BM_BWD(n)                                         \
+    case n:                                               \
+        if (io_bf16) launch_pair<n, IoBF16>(a, batch, st); \
+        else launch_pair<n, IoF32>(a, batch, st);          \
+        break;
+    switch (d_state) {
+        BM_BWD(4)
+        BM_BWD(8)
+        BM_BWD(16)
+        default: break;
+    }
+#undef BM_BWD
+}
+
+void launch_bwd_finish(int io_bf16, const BwdFinishArgs& a, hipStream_t st)
+{
+    const long long n = a.batch * a.L * a.C;
+    if (n <= 0) return;
+    const dim3 grid((unsigned)((n + 255) / 256));
+    if (io_bf16) hipLaunchKernelGGL(bwd_finish_kernel<IoBF16>, grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(bwd_finish_kernel<IoF32>, grid, dim3(256), 0, st, a);
+}
+
+void launch_bwd_zero(float* p, long long n, hipStream_t st)
+{
+    if (!p || n <= 0) return;
+    hipLaunchKernelGGL(bwd_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n);
+}
+
+}  // namespace bm

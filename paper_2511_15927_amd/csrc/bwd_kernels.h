@@ -1,0 +1,333 @@
+// Gradients of the bidirectional mixer path in the selective-scan layout (one head per channel: Delta, A and D per
+// channel; B and C shared by the channels of a group; no conv on B and C), for gfx950.
+//
+// The paper trains these models (App. A.2) but gives no backward algorithm; what is computed here is the chain rule of
+// the forward definition (Sec. 3.2 eqs. 4-6 in the concrete selective form), evaluated in the reverse of each
+// direction's scan order.  With t+ the token after t in scan order, t- the one before, and dg_t the gradient of the
+// gated output of the direction:
+//   dz_t = dg_t y_t silu'(z_t)                       dy_t = dg_t silu(z_t)
+//   dh_t[n] = C_t[n] dy_t + a_{t+}[n] dh_{t+}[n]
+//   dC_t[n] += sum_channels dy_t h_t[n]              dB_t[n] += sum_channels dh_t[n] Delta_t xc_t
+//   dA[n] += dh_t[n] h_{t-}[n] a_t[n] Delta_t        dD += dy_t xc_t
+//   dDelta_t = sum_n dh_t[n] (h_{t-}[n] a_t[n] A[n] + B_t[n] xc_t)
+//   dxc_t = D dy_t + sum_n dh_t[n] Delta_t B_t[n]    dpre_t = dxc_t silu'(pre_t)
+//   dx_t = sum_j w[K-1-j] dpre_{t + j steps}         dw[k] += dpre_t x_{t - (K-1-k) steps},  dcb += dpre_t
+//
+// Mapping: a lane is one (direction, batch, channel) chain, as in the forward sweep with one lane per chain.  The
+// backward recurrence needs the states in the reverse of the order the forward recurrence makes them, so
+//   bwd_state_kernel  walks each chain forward and stores the state entering every chunk of kBwdChunk tokens;
+//   bwd_kernel        takes the chunks last to first: it recomputes a chunk's states from the stored one into
+//                     registers (kBwdChunk * N values per lane) and then walks the chunk backwards.
+// dB_t and dC_t are sums over the channels of a group: each wave adds its 64 channels with lane-permute adds and one
+// lane adds the result to the caller's fp32 buffer with a hardware atomic.  Parameter gradients are kept per lane and
+// added atomically once per chain (the sum over the batch).  The per-direction gradients of x, z and Delta leave this
+// kernel as fp32 rows of a scratch buffer; bwd_finish_kernel adds the two directions (when they read the same
+// activations) and rounds once to the I/O dtype.
+#pragma once
+#include "kernels.h"
+
+namespace bm {
+
+struct BwdArgs {
+    DirArgs dir[2];          // x, z, dt views, prepared fp32 B|C rows and parameters of each direction
+    TensorArg dout;          // [batch][L][Dn] (ADD) or [batch][L][2 Dn] (SEPARATE), I/O dtype
+    float* state;            // [2][batch][nchunk][Dn][N]: the state entering each chunk (scan order)
+    float* dx;               // [2][batch][L][Dn] fp32, per direction; dz and ddt follow at the same spacing
+    float* dz;
+    float* ddt;
+    float* dB[2];            // [batch][L][G][N] fp32 (both entries equal when the directions share their inputs)
+    float* dC[2];
+    float* dA[2];            // [Dn][N]
+    float* dD[2];            // [Dn]
+    float* dconv_w[2];       // [Dn][K]
+    float* dconv_b[2];       // [Dn] or null
+    float* ddt_bias[2];      // [Dn] or null
+    int L, Dn, G, K, nchunk, dt_softplus, separate;
+};
+
+template <int N>
+constexpr int kBwdChunk = N <= 4 ? 16 : 8;   // tokens per chunk: (chunk + 1) * N state values per lane in registers
+
+__device__ __forceinline__ float dsilu(float v)
+{
+    const float s = __builtin_amdgcn_rcpf(1.0f + fast_exp2(-kLog2e * v));
+    return s * fmaf(v, 1.0f - s, 1.0f);
+}
+__device__ __forceinline__ float sigmoidf(float v) { return __builtin_amdgcn_rcpf(1.0f + fast_exp2(-kLog2e * v)); }
+
+// Sum over the 64 lanes of the wave; the total is valid in lane 63.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float lane_permuted(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xF, true));
+}
+__device__ __forceinline__ float wave_sum_to_last_lane(float v)
+{
+    v += lane_permuted<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
+    v += lane_permuted<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
+    v += lane_permuted<0x141, 0xF>(v);   // row_half_mirror
+    v += lane_permuted<0x140, 0xF>(v);   // row_mirror: every lane of a row of 16 holds the row's sum
+    v += lane_permuted<0x142, 0xA>(v);   // row_bcast15 into rows 1 and 3
+    v += lane_permuted<0x143, 0xC>(v);   // row_bcast31 into rows 2 and 3
+    return v;
+}
+
+// The per-lane view of one chain shared by both kernels: constants, the scan-order token walk and the forward step.
+template <int N, typename IO>
+struct BwdChain {
+    using T = typename IO::T;
+    float a2[N];                 // A * log2(e)
+    float w4[4], cb, dval, dtb;  // conv taps (w4[3] on the current token), conv bias, D, Delta bias
+    const T *xb, *zb, *dtb_ptr;  // the lane's element of token 0 of this batch element
+    long long xs, zs, dts;       // token strides (elements)
+    const float* bc;             // prepared B|C rows of this batch element and group: row t at bc + t * bcs
+    long long bcs;
+    int L, dir;
+
+    __device__ __forceinline__ int token(int scan_index) const { return dir > 0 ? scan_index : L - 1 - scan_index; }
+    __device__ __forceinline__ float raw_x(int scan_index) const
+    {
+        return (scan_index >= 0 && scan_index < L) ? IO::cvt(xb[(long long)token(scan_index) * xs]) : 0.0f;
+    }
+    __device__ __forceinline__ float delta_of(float raw, bool softplus_dt) const { return softplus_dt ? softplus(raw + dtb) : raw; }
+    __device__ __forceinline__ uniform_ro_ptr row(int scan_index) const
+    {
+        return (uniform_ro_ptr)(bc + (long long)token(scan_index) * bcs);
+    }
+};
+
+template <int N, typename IO>
+__device__ __forceinline__ bool bwd_chain_setup(const BwdArgs& a, int w, BwdChain<N, IO>& c, int& s, int& b, int& ch, bool& valid)
+{
+    using T = typename IO::T;
+    s = w & 1;
+    b = blockIdx.z;
+    const int lane = threadIdx.x & 63;
+    const int tile = (int)blockIdx.x * 2 + (w >> 1);
+    if (tile * 64 >= a.Dn) return false;                 // the second tile of the last workgroup may not exist
+    valid = tile * 64 + lane < a.Dn;
+    ch = min(tile * 64 + lane, a.Dn - 1);                 // lanes past the last channel shadow it and contribute nothing
+    const DirArgs& da = a.dir[s];
+    const int grp = (tile * 64) / (a.Dn / a.G);          // uniform: a tile never straddles two B/C groups
+#pragma unroll
+    for (int n = 0; n < N; n++) c.a2[n] = da.A[(size_t)ch * N + n] * kLog2e;
+#pragma unroll
+    for (int i = 0; i < 4; i++) c.w4[3 - i] = i < a.K ? da.conv_w[(size_t)ch * a.K + (a.K - 1 - i)] : 0.0f;
+    c.cb = da.conv_b ? da.conv_b[ch] : 0.0f;
+    c.dval = da.D[ch];
+    c.dtb = (a.dt_softplus && da.dt_bias) ? da.dt_bias[ch] : 0.0f;
+    c.xb = (const T*)da.x.p + (size_t)b * da.x.sb + ch;
+    c.zb = (const T*)da.z.p + (size_t)b * da.z.sb + ch;
+    c.dtb_ptr = (const T*)da.dt.p + (size_t)b * da.dt.sb + ch;
+    c.xs = da.x.st; c.zs = da.z.st; c.dts = da.dt.st;
+    c.bcs = (long long)a.G * 2 * N;
+    c.bc = da.bc + ((size_t)b * a.L * a.G + grp) * (2 * N);
+    c.L = a.L;
+    c.dir = s == 0 ? 1 : -1;
+    return true;
+}
+
+// grid (ceil(ceil(Dn / 64) / 2), 1, batch), block 256: waves 0 / 1 the forward / reverse chain of one channel tile,
+// waves 2 / 3 those of the next.
+template <int N, typename IO>
+__global__ __launch_bounds__(256) void bwd_state_kernel(const BwdArgs a)
+{
+    constexpr int CT = kBwdChunk<N>;
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    BwdChain<N, IO> c;
+    int s, b, ch;
+    bool valid;
+    if (!bwd_chain_setup<N, IO>(a, w, c, s, b, ch, valid)) return;
+    const bool sp = a.dt_softplus != 0;
+    float h[N];
+#pragma unroll
+    for (int n = 0; n < N; n++) h[n] = 0.0f;
+    float x1 = 0.0f, x2 = 0.0f, x3 = 0.0f;   // raw x one, two, three tokens back in scan order
+    float* dst = a.state + (((size_t)s * gridDim.z + b) * a.nchunk * a.Dn + ch) * N;
+    for (int k = 0; k < a.nchunk; k++) {
+        if (valid) {
+#pragma unroll
+            for (int n = 0; n < N; n++) dst[n] = h[n];
+        }
+        dst += (size_t)a.Dn * N;
+        if (k == a.nchunk - 1) break;    // the state after the last chunk feeds nothing
+        // the whole chunk's activations are requested before the first is used
+        typename IO::T xr[CT], dr[CT];
+#pragma unroll
+        for (int i = 0; i < CT; i++) {
+            const long long t = c.token(min(k * CT + i, a.L - 1));
+            xr[i] = c.xb[t * c.xs];
+            dr[i] = c.dtb_ptr[t * c.dts];
+        }
+#pragma unroll
+        for (int i = 0; i < CT; i++) {
+            if (k * CT + i >= a.L) break;
+            const float x0 = IO::cvt(xr[i]);
+            const float pre = fmaf(c.w4[0], x3, fmaf(c.w4[1], x2, fmaf(c.w4[2], x1, fmaf(c.w4[3], x0, c.cb))));
+            x3 = x2; x2 = x1; x1 = x0;
+            const float xc = silu(pre);
+            const float delta = c.delta_of(IO::cvt(dr[i]), sp);
+            const float u = delta * xc;
+            uniform_ro_ptr row = c.row(k * CT + i);
+#pragma unroll
+            for (int n = 0; n < N; n++) h[n] = fmaf(fast_exp2(delta * c.a2[n]), h[n], u * row[n]);
+        }
+    }
+}
+
+template <int N, typename IO>
+__global__ __launch_bounds__(256) void bwd_kernel(const BwdArgs a)
+{
+    using T = typename IO::T;
+    constexpr int CT = kBwdChunk<N>;
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = threadIdx.x & 63;
+    BwdChain<N, IO> c;
+    int s, b, ch;
+    bool valid;
+    if (!bwd_chain_setup<N, IO>(a, w, c, s, b, ch, valid)) return;
+    const bool sp = a.dt_softplus != 0;
+    const int grp = ((int)blockIdx.x * 2 + (w >> 1)) * 64 / (a.Dn / a.G);
+    const T* dob = (const T*)a.dout.p + (size_t)b * a.dout.sb + ch + (a.separate ? s * a.Dn : 0);
+    const size_t plane = ((size_t)s * gridDim.z + b) * a.L * a.Dn + ch;     // this chain's column in the per-direction rows
+    float* const dB = a.dB[s] + ((size_t)b * a.L * a.G + grp) * N;
+    float* const dC = a.dC[s] + ((size_t)b * a.L * a.G + grp) * N;
+
+    float dh[N], gA[N];
+#pragma unroll
+    for (int n = 0; n < N; n++) dh[n] = gA[n] = 0.0f;
+    float gD = 0.0f, gcb = 0.0f, gbias = 0.0f, gw[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    float dp1 = 0.0f, dp2 = 0.0f, dp3 = 0.0f;   // dpre of the tokens one, two, three steps later in scan order
+
+    for (int k = a.nchunk - 1; k >= 0; k--) {
+        const int first = k * CT;                                   // scan index of the chunk's first token
+        const int count = min(CT, a.L - first);
+        // the chunk's activations, and the three raw x before it
+        T xr[CT], dr[CT], zr[CT], gr[CT];
+#pragma unroll
+        for (int i = 0; i < CT; i++) {
+            const long long t = c.token(min(first + i, a.L - 1));
+            xr[i] = c.xb[t * c.xs];
+            dr[i] = c.dtb_ptr[t * c.dts];
+            zr[i] = c.zb[t * c.zs];
+            gr[i] = dob[t * a.dout.st];
+        }
+        float xraw[CT + 3];
+        xraw[0] = c.raw_x(first - 3);
+        xraw[1] = c.raw_x(first - 2);
+        xraw[2] = c.raw_x(first - 1);
+        const float* src = a.state + ((((size_t)s * gridDim.z + b) * a.nchunk + k) * a.Dn + ch) * N;
+        float hs[CT + 1][N];   // hs[i] = the state entering token i of the chunk
+#pragma unroll
+        for (int n = 0; n < N; n++) hs[0][n] = src[n];
+        float xc[CT], delta[CT], pre[CT];
+        // forward over the chunk, keeping every state
+#pragma unroll
+        for (int i = 0; i < CT; i++) {
+            xraw[i + 3] = IO::cvt(xr[i]);
+            pre[i] = fmaf(c.w4[0], xraw[i], fmaf(c.w4[1], xraw[i + 1], fmaf(c.w4[2], xraw[i + 2], fmaf(c.w4[3], xraw[i + 3], c.cb))));
+            xc[i] = silu(pre[i]);
+            delta[i] = c.delta_of(IO::cvt(dr[i]), sp);
+            if (i < count) {
+                const float u = delta[i] * xc[i];
+                uniform_ro_ptr row = c.row(first + i);
+#pragma unroll
+                for (int n = 0; n < N; n++) hs[i + 1][n] = fmaf(fast_exp2(delta[i] * c.a2[n]), hs[i][n], u * row[n]);
+            } else {
+#pragma unroll
+                for (int n = 0; n < N; n++) hs[i + 1][n] = hs[i][n];
+            }
+        }
+        // backward over the chunk, last token first
+#pragma unroll
+        for (int i = CT - 1; i >= 0; i--) {
+            if (i >= count) continue;
+            const int tok = c.token(first + i);
+            uniform_ro_ptr row = c.row(first + i);
+            const float zv = IO::cvt(zr[i]);
+            const float dg = valid ? IO::cvt(gr[i]) : 0.0f;          // shadow lanes add nothing to the sums below
+            float y = c.dval * xc[i];
+#pragma unroll
+            for (int n = 0; n < N; n++) y = fmaf(row[N + n], hs[i + 1][n], y);
+            const float dz = dg * y * dsilu(zv);
+            const float dy = dg * silu(zv);
+            gD = fmaf(dy, xc[i], gD);
+            float ddelta = 0.0f, dxc = c.dval * dy;
+            const float u_over = delta[i] * xc[i];
+#pragma unroll
+            for (int n = 0; n < N; n++) {
+                const float an = fast_exp2(delta[i] * c.a2[n]);
+                dh[n] = fmaf(row[N + n], dy, dh[n]);
+                const float for_c = wave_sum_to_last_lane(dy * hs[i + 1][n]);
+                const float for_b = wave_sum_to_last_lane(dh[n] * u_over);
+                if (lane == 63) {
+                    unsafeAtomicAdd(dC + (size_t)tok * a.G * N + n, for_c);
+                    unsafeAtomicAdd(dB + (size_t)tok * a.G * N + n, for_b);
+                }
+                const float da = dh[n] * hs[i][n] * an;              // dh * h_prev * a
+                gA[n] = fmaf(da, delta[i], gA[n]);
+                ddelta = fmaf(da, c.a2[n] * kLn2, ddelta);          // A = a2 * ln 2
+                ddelta = fmaf(dh[n] * row[n], xc[i], ddelta);
+                dxc = fmaf(dh[n] * delta[i], row[n], dxc);
+                dh[n] *= an;
+            }
+            float ddt = ddelta;
+            if (sp) {
+                ddt *= sigmoidf(IO::cvt(dr[i]) + c.dtb);
+                gbias += ddt;
+            }
+            const float dpre = dxc * dsilu(pre[i]);
+            gcb += dpre;
+            gw[3] = fmaf(dpre, xraw[i + 3], gw[3]);
+            gw[2] = fmaf(dpre, xraw[i + 2], gw[2]);
+            gw[1] = fmaf(dpre, xraw[i + 1], gw[1]);
+            gw[0] = fmaf(dpre, xraw[i], gw[0]);
+            const float dxv = fmaf(c.w4[3], dpre, fmaf(c.w4[2], dp1, fmaf(c.w4[1], dp2, c.w4[0] * dp3)));
+            dp3 = dp2; dp2 = dp1; dp1 = dpre;
+            if (valid) {
+                const size_t at = plane + (size_t)tok * a.Dn;
+                a.dx[at] = dxv;
+                a.dz[at] = dz;
+                a.ddt[at] = ddt;
+            }
+        }
+    }
+    if (valid) {
+        const int K = a.K;
+#pragma unroll
+        for (int n = 0; n < N; n++) unsafeAtomicAdd(a.dA[s] + (size_t)ch * N + n, gA[n]);
+        unsafeAtomicAdd(a.dD[s] + ch, gD);
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+            if (i < K) unsafeAtomicAdd(a.dconv_w[s] + (size_t)ch * K + (K - 1 - i), gw[3 - i]);
+        if (a.dconv_b[s]) unsafeAtomicAdd(a.dconv_b[s] + ch, gcb);
+        if (a.ddt_bias[s] && sp) unsafeAtomicAdd(a.ddt_bias[s] + ch, gbias);
+    }
+}
+
+// Adds the two directions' fp32 gradient rows where both read the same activations and rounds once to the I/O dtype.
+struct BwdFinishArgs {
+    const float* src;        // [2][batch][L][C] fp32
+    TensorArg dst[2];        // destination view per direction (dst[1].p null: both directions summed into dst[0])
+    long long batch, L, C;
+};
+
+template <typename IO>
+__global__ __launch_bounds__(256) void bwd_finish_kernel(const BwdFinishArgs a)
+{
+    using T = typename IO::T;
+    const long long per_dir = a.batch * a.L * a.C;
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= per_dir) return;
+    const long long col = i % a.C, t = (i / a.C) % a.L, b = i / (a.C * a.L);
+    const float f = a.src[i], r = a.src[per_dir + i];
+    T* d0 = (T*)a.dst[0].p + b * a.dst[0].sb + t * a.dst[0].st + col;
+    if (a.dst[1].p) {
+        IO::st(d0, f);
+        IO::st((T*)a.dst[1].p + b * a.dst[1].sb + t * a.dst[1].st + col, r);
+    } else {
+        IO::st(d0, f + r);
+    }
+}
+
+}  // namespace bm

@@ -1,0 +1,132 @@
+"""GPU parity of bimamba_bwd (gradients of the full-sequence path, selective-scan layout) against the fp64 oracle's
+gradients, which are themselves pinned by finite differences and automatic differentiation (test_oracle_bwd_pins.py).
+
+Tolerances: a gradient tensor is compared in relative L2 over the whole tensor; fp32 I/O 2e-5 (fp32 arithmetic, sums of
+up to L * batch terms formed with atomics in arbitrary order), bf16 I/O 2e-2 for the tensors that are rounded to bf16
+(dx, dz, ddt) and 2e-5 for the fp32 ones (dB, dC and the parameter gradients see the same fp32 arithmetic in both modes).
+"""
+import numpy as np
+import pytest
+import torch
+
+from helpers import rel_l2, to_np
+from paper_2511_15927_amd import binding as bd
+from paper_2511_15927_amd import synth
+from test_gpu_block import params
+
+pytestmark = pytest.mark.gpu
+
+FP32_TOL, BF16_TOL = 2e-5, 2e-2
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import gpu_util
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return gpu_util
+
+
+def rounded(a, io):
+    t = torch.as_tensor(a, dtype=torch.float32)
+    return (t.to(torch.bfloat16).float() if io == "bf16" else t).numpy()
+
+
+def rel_all(got, ref):
+    """Relative L2 over a whole tensor (parameter gradients have no batch dimension to take a maximum over)."""
+    return float(np.linalg.norm(np.asarray(got) - np.asarray(ref)) / np.linalg.norm(np.asarray(ref)))
+
+
+def compare(cfg, got, ref, sel=None):
+    io_tol = BF16_TOL if cfg["io"] == "bf16" else FP32_TOL
+    gf, gb, qf, qb = got
+    rf, rb, pf, pb = ref
+    pick = (lambda a: a[..., sel]) if sel is not None else (lambda a: a)
+    worst = {}
+    for tag, g, r in (("f", gf, rf), ("b", gb, rb)):
+        if r is None:
+            assert g is None
+            continue
+        for k in ("dx", "dz"):
+            worst[tag + k] = rel_l2(pick(g[k]), r[k])
+            assert worst[tag + k] < io_tol, (tag, k, worst)
+        worst[tag + "ddt"] = rel_l2(pick(g["ddt"]), pick(r["ddt"]))
+        assert worst[tag + "ddt"] < io_tol, (tag, "ddt", worst)
+        if sel is None:
+            for k in ("dB", "dC"):
+                worst[tag + k] = rel_l2(g[k], r[k])
+                assert worst[tag + k] < FP32_TOL, (tag, k, worst)
+    for tag, g, r in (("f", qf, pf), ("b", qb, pb)):
+        for k in ("dconv_w", "dconv_b", "dA", "dD", "ddt_bias"):
+            a, b = (g[k][sel], r[k][sel]) if sel is not None else (g[k], r[k])
+            if not np.any(b):
+                assert not np.any(a), (tag, k)
+                continue
+            worst[tag + k] = rel_all(a, b)
+            assert worst[tag + k] < FP32_TOL, (tag, k, worst)
+    return worst
+
+
+def run_case(gpu, oracle, cfg, seed, untied=False, random_a=True):
+    pf, pb = params(cfg, seed, random_a=random_a)
+    in_f = synth.make_inputs(cfg, seed)
+    in_b = synth.make_inputs(cfg, seed + 500) if untied else None
+    width = cfg["d_inner"] * (2 if cfg["combine"] else 1)
+    g = torch.Generator().manual_seed(seed + 9)
+    dout = rounded(torch.randn(cfg["batch"], cfg["seqlen"], width, generator=g), cfg["io"])
+    got = gpu.gpu_bwd(cfg, pf, pb, in_f, in_b, dout)
+    ref = oracle.bimamba_bwd(cfg, to_np(pf), to_np(pb), to_np(in_f), None if in_b is None else to_np(in_b), dout)
+    return compare(cfg, got, ref)
+
+
+@pytest.mark.parametrize("L", [1, 2, 7, 8, 9, 16, 23, 100])
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+def test_lengths_around_the_chunks(gpu, oracle, L, io):
+    run_case(gpu, oracle, synth.mixer_cfg(2, L, 72, io=io), 10 + L)
+
+
+@pytest.mark.parametrize("N", [4, 8, 16])
+@pytest.mark.parametrize("K", [1, 2, 3, 4])
+def test_state_sizes_and_conv_widths(gpu, oracle, N, K):
+    run_case(gpu, oracle, synth.mixer_cfg(2, 37, 130, d_state=N, d_conv=K, io="f32"), 30 + N + K)
+
+
+@pytest.mark.parametrize("mode", ["separate", "untied", "untied_separate", "softplus", "groups", "progression_a"])
+def test_modes(gpu, oracle, mode):
+    kw = {}
+    if "separate" in mode:
+        kw["combine"] = synth.COMBINE_SEPARATE
+    if mode == "softplus":
+        kw["dt_softplus"] = 1
+    Dn = 256 if mode == "groups" else 96
+    if mode == "groups":
+        kw["n_groups"] = 2
+    cfg = synth.mixer_cfg(3, 45, Dn, io="f32", **kw)
+    run_case(gpu, oracle, cfg, 77, untied="untied" in mode, random_a=mode != "progression_a")
+
+
+def test_empty_call_zeroes_the_parameter_gradients(gpu, oracle):
+    cfg = synth.mixer_cfg(0, 16, 64, io="f32")
+    pf, pb = params(cfg, 1)
+    got = gpu.gpu_bwd(cfg, pf, pb, synth.make_inputs(cfg, 1), None, np.zeros((0, 16, 64), dtype=np.float32))
+    assert got[0]["dx"].shape == (0, 16, 64)
+    for q in got[2:]:
+        assert all(not np.any(v) for v in q.values())
+
+
+def test_unsupported_layouts_are_refused_on_the_host(gpu):
+    for cfg in (synth.m2_cfg(1, 64, 128, headdim=64, d_state=64), synth.mixer_cfg(1, 8, 64, d_state=32)):
+        assert bd.bimamba_bwd_workspace_bytes(bd.make_desc(cfg)) == 0
+
+
+def test_headline_width_sampled(gpu, oracle):
+    """d_inner 4096, bf16, a few hundred tokens: the x / z / Delta and per-channel parameter gradients on sampled
+    channels (B and C gradients are sums over all channels and are covered by the small cases)."""
+    cfg = synth.mixer_cfg(2, 300, 4096)
+    pf, pb = params(cfg, 5, random_a=False)
+    inp = synth.make_inputs(cfg, 5)
+    g = torch.Generator().manual_seed(3)
+    dout = rounded(torch.randn(2, 300, 4096, generator=g), "bf16")
+    sel = list(range(3, 4096, 511))
+    got = gpu.gpu_bwd(cfg, pf, pb, inp, None, dout)
+    ref = oracle.bimamba_bwd(cfg, to_np(pf), to_np(pb), to_np(inp), None, dout[..., sel], sel=sel)
+    compare(cfg, got, ref, sel=sel)
