@@ -640,7 +640,8 @@ int bimamba_block_fwd_static(const bimamba_desc* desc, const bimamba_params* pf,
 namespace {
 struct BwdPlan {
     int chunk, nchunk;
-    size_t off_bc[2], off_state, off_dx, off_dz, off_ddt, total;
+    int tiles_per_group;
+    size_t off_bc[2], off_state, off_dx, off_dz, off_ddt, off_part[2], total;
 };
 
 int check_bwd_desc(const bimamba_desc* d)
@@ -667,6 +668,11 @@ BwdPlan make_bwd_plan(const bimamba_desc* d)
     p.off_dx = off; off += plane;
     p.off_dz = off; off += plane;
     p.off_ddt = off; off += plane;
+    // per-wave partial sums of dB | dC: one slot per channel tile of a group and direction
+    p.tiles_per_group = (d->d_inner / d->n_groups + 63) / 64;
+    const size_t part = align_up((size_t)d->batch * d->seqlen * d->n_groups * p.tiles_per_group * 2 * d->d_state * sizeof(float), 256);
+    p.off_part[0] = off; off += part;
+    p.off_part[1] = off; off += part;
     p.total = off;
     return p;
 }
@@ -741,13 +747,6 @@ int bimamba_bwd(const bimamba_desc* d, const bimamba_params* pf, const bimamba_p
             if (bf16) hipLaunchKernelGGL(prep_bc_kernel<IoBF16>, grid, dim3(256), 0, st, pa);
             else hipLaunchKernelGGL(prep_bc_kernel<IoF32>, grid, dim3(256), 0, st, pa);
         }
-        const long long bc_elems = (long long)d->batch * d->seqlen * GN;
-        bm::launch_bwd_zero(din_f->dB, bc_elems, st);
-        bm::launch_bwd_zero(din_f->dC, bc_elems, st);
-        if (din_b) {
-            bm::launch_bwd_zero(din_b->dB, bc_elems, st);
-            bm::launch_bwd_zero(din_b->dC, bc_elems, st);
-        }
         BwdArgs a{};
         for (int s = 0; s < 2; s++) {
             const bimamba_inputs* in = s == 0 ? in_f : in_b;
@@ -758,7 +757,9 @@ int bimamba_bwd(const bimamba_desc* d, const bimamba_params* pf, const bimamba_p
             da.x = targ(in->x); da.z = targ(in->z); da.dt = targ(in->dt);
             da.bc = reinterpret_cast<const float*>(ws + plan.off_bc[shared ? 0 : s]);
             da.conv_w = p->conv_w; da.conv_b = p->conv_b; da.A = p->A; da.D = p->D; da.dt_bias = p->dt_bias;
-            a.dB[s] = gi->dB; a.dC[s] = gi->dC;
+            (void)gi;
+            // shared activations: both directions' waves fill slots of one buffer (the two parts are adjacent)
+            a.bc_part[s] = reinterpret_cast<float*>(ws + plan.off_part[shared ? 0 : s]);
             a.dA[s] = g->dA; a.dD[s] = g->dD; a.dconv_w[s] = g->dconv_w; a.dconv_b[s] = g->dconv_b; a.ddt_bias[s] = g->ddt_bias;
         }
         a.dout = targ(*dout);
@@ -768,7 +769,18 @@ int bimamba_bwd(const bimamba_desc* d, const bimamba_params* pf, const bimamba_p
         a.ddt = reinterpret_cast<float*>(ws + plan.off_ddt);
         a.L = d->seqlen; a.Dn = d->d_inner; a.G = d->n_groups; a.K = d->d_conv; a.nchunk = plan.nchunk;
         a.dt_softplus = d->dt_softplus; a.separate = d->combine == BIMAMBA_COMBINE_SEPARATE;
+        a.bc_slots = plan.tiles_per_group * (shared ? 2 : 1);
+        a.bc_slot_of_rev = shared ? plan.tiles_per_group : 0;
         bm::launch_bwd(d->d_state, bf16, a, d->batch, st);
+        for (int s = 0; s < (shared ? 1 : 2); s++) {
+            const bimamba_input_grads* gi = s == 0 ? din_f : din_b;
+            BwdBcArgs ba{};
+            ba.part = a.bc_part[s];
+            ba.dB = gi->dB; ba.dC = gi->dC;
+            ba.rows = (long long)d->batch * d->seqlen * d->n_groups;
+            ba.slots = a.bc_slots; ba.N = d->d_state;
+            bm::launch_bwd_bc(ba, st);
+        }
         const float* planes[3] = {a.dx, a.dz, a.ddt};
         for (int k = 0; k < 3; k++) {
             BwdFinishArgs fa{};

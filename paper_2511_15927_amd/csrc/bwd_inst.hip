@@ -16,6 +16,27 @@ __global__ __launch_bounds__(256) void bwd_zero_kernel(float* p, long long n)
     if (i < n) p[i] = 0.0f;
 }
 
+__global__ __launch_bounds__(256) void bwd_bc_kernel(const BwdBcArgs a)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    const int two_n = 2 * a.N;
+    if (i >= a.rows * two_n) return;
+    const long long r = i / two_n;
+    const int v = (int)(i % two_n);
+    const float* src = a.part + r * a.slots * two_n + v;
+    float acc = 0.0f;
+    for (int k = 0; k < a.slots; k++) acc += src[(long long)k * two_n];
+    if (v < a.N) a.dB[r * a.N + v] = acc;
+    else a.dC[r * a.N + v - a.N] = acc;
+}
+
+void launch_bwd_bc(const BwdBcArgs& a, hipStream_t st)
+{
+    const long long n = a.rows * 2 * a.N;
+    if (n <= 0) return;
+    hipLaunchKernelGGL(bwd_bc_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
+}
+
 template <int N, typename IO>
 static void launch_pair(const BwdArgs& a, int batch, hipStream_t st)
 {

@@ -35,8 +35,9 @@ struct BwdArgs {
     float* dx;               // [2][batch][L][Dn] fp32, per direction; dz and ddt follow at the same spacing
     float* dz;
     float* ddt;
-    float* dB[2];            // [batch][L][G][N] fp32 (both entries equal when the directions share their inputs)
-    float* dC[2];
+    float* bc_part[2];       // per direction: [batch][L][G][slots][2N] fp32 partial sums of dB | dC, one slot per wave
+    int bc_slots;            // slots per group: channel tiles of a group (x 2 when both directions feed one buffer)
+    int bc_slot_of_rev;      // slot offset of the reverse direction's waves (0 when it has a buffer of its own)
     float* dA[2];            // [Dn][N]
     float* dD[2];            // [Dn]
     float* dconv_w[2];       // [Dn][K]
@@ -55,21 +56,66 @@ __device__ __forceinline__ float dsilu(float v)
 }
 __device__ __forceinline__ float sigmoidf(float v) { return __builtin_amdgcn_rcpf(1.0f + fast_exp2(-kLog2e * v)); }
 
-// Sum over the 64 lanes of the wave; the total is valid in lane 63.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float lane_permuted(float x)
+// Sums NV values per lane over the 64 lanes of the wave and leaves the total of value j in the lanes
+// j * (64 / NV) ... (j + 1) * (64 / NV) - 1 (returned by every lane: the total of value lane / (64 / NV)).
+// A reduce-scatter: each step halves the values a lane still carries.  The lane whose bit is clear keeps the first half
+// and receives its partner's first half, the other lane the second half, so NV - 1 + log2(64 / NV) adds do the work of
+// 6 * NV.  Partners: the other 32-lane half and the other row of 16 by the swap instructions of gfx950, then inside a
+// row by lane-permute operands (selection by lane group through their bank mask where the bit picks banks).
+template <int CTRL, int ROW_MASK, int BANK_MASK>
+__device__ __forceinline__ float lane_permuted(float old, float x)
 {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xF, true));
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(x), CTRL, ROW_MASK, BANK_MASK, false));
 }
-__device__ __forceinline__ float wave_sum_to_last_lane(float v)
+template <int CTRL>
+__device__ __forceinline__ float from_partner(float x)
 {
-    v += lane_permuted<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
-    v += lane_permuted<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
-    v += lane_permuted<0x141, 0xF>(v);   // row_half_mirror
-    v += lane_permuted<0x140, 0xF>(v);   // row_mirror: every lane of a row of 16 holds the row's sum
-    v += lane_permuted<0x142, 0xA>(v);   // row_bcast15 into rows 1 and 3
-    v += lane_permuted<0x143, 0xC>(v);   // row_bcast31 into rows 2 and 3
-    return v;
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+template <int NV>
+__device__ __forceinline__ float wave_reduce_scatter(float (&v)[NV], int lane)
+{
+    static_assert(NV == 8 || NV == 16 || NV == 32, "8, 16 or 32 values per lane");
+    // lane bit 5: the other half of the wave
+#pragma unroll
+    for (int i = 0; i < NV / 2; i++) {
+        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[i]), __float_as_uint(v[NV / 2 + i]), false, false);
+        v[i] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    }
+    // lane bit 4: the neighbouring row of 16
+#pragma unroll
+    for (int i = 0; i < NV / 4; i++) {
+        const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v[i]), __float_as_uint(v[NV / 4 + i]), false, false);
+        v[i] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    }
+    // lane bit 3: banks 2 and 3 of a row keep the second half; the partner is 8 lanes away (row rotate by 8)
+#pragma unroll
+    for (int i = 0; i < NV / 8; i++) {
+        const float keep = lane_permuted<0xE4, 0xF, 0xC>(v[i], v[NV / 8 + i]);
+        const float send = lane_permuted<0xE4, 0xF, 0xC>(v[NV / 8 + i], v[i]);
+        v[i] = keep + from_partner<0x128>(send);
+    }
+    if constexpr (NV >= 16) {
+        // lane bit 2: banks 1 and 3; the partner is the mirror lane of the other bank of the half row
+#pragma unroll
+        for (int i = 0; i < NV / 16; i++) {
+            const float keep = lane_permuted<0xE4, 0xF, 0xA>(v[i], v[NV / 16 + i]);
+            const float send = lane_permuted<0xE4, 0xF, 0xA>(v[NV / 16 + i], v[i]);
+            v[i] = keep + from_partner<0x141>(send);
+        }
+    }
+    if constexpr (NV >= 32) {
+        // lane bit 1: inside a quad
+        const bool upper = (lane & 2) != 0;
+        const float keep = upper ? v[1] : v[0], send = upper ? v[0] : v[1];
+        v[0] = keep + from_partner<0x4E>(send);
+    }
+    // what is left of the lane index carries the same value: plain sums, quads first (the mirror needs equal quads)
+    float t = v[0];
+    t += from_partner<0xB1>(t);                              // quad_perm [1,0,3,2]
+    if constexpr (NV <= 16) t += from_partner<0x4E>(t);     // quad_perm [2,3,0,1]
+    if constexpr (NV <= 8) t += from_partner<0x141>(t);     // row_half_mirror
+    return t;
 }
 
 // The per-lane view of one chain shared by both kernels: constants, the scan-order token walk and the forward step.
@@ -190,8 +236,12 @@ __global__ __launch_bounds__(256) void bwd_kernel(const BwdArgs a)
     const int grp = ((int)blockIdx.x * 2 + (w >> 1)) * 64 / (a.Dn / a.G);
     const T* dob = (const T*)a.dout.p + (size_t)b * a.dout.sb + ch + (a.separate ? s * a.Dn : 0);
     const size_t plane = ((size_t)s * gridDim.z + b) * a.L * a.Dn + ch;     // this chain's column in the per-direction rows
-    float* const dB = a.dB[s] + ((size_t)b * a.L * a.G + grp) * N;
-    float* const dC = a.dC[s] + ((size_t)b * a.L * a.G + grp) * N;
+    // this wave's slot of the dB | dC partial sums: [batch][L][G][slots][2N]
+    const int tiles_per_group = (a.Dn / a.G + 63) / 64;
+    const int slot = ((int)blockIdx.x * 2 + (w >> 1)) % tiles_per_group + (s == 1 ? a.bc_slot_of_rev : 0);
+    float* const part = a.bc_part[s] + (((size_t)b * a.L * a.G + grp) * a.bc_slots + slot) * (2 * N);
+    const size_t part_token = (size_t)a.G * a.bc_slots * 2 * N;
+    constexpr int kLanesPerValue = 64 / (2 * N);
 
     float dh[N], gA[N];
 #pragma unroll
@@ -254,22 +304,24 @@ __global__ __launch_bounds__(256) void bwd_kernel(const BwdArgs a)
             gD = fmaf(dy, xc[i], gD);
             float ddelta = 0.0f, dxc = c.dval * dy;
             const float u_over = delta[i] * xc[i];
+            float bc_terms[2 * N];                                   // this channel's terms of dB_t (first N) and dC_t
 #pragma unroll
             for (int n = 0; n < N; n++) {
                 const float an = fast_exp2(delta[i] * c.a2[n]);
                 dh[n] = fmaf(row[N + n], dy, dh[n]);
-                const float for_c = wave_sum_to_last_lane(dy * hs[i + 1][n]);
-                const float for_b = wave_sum_to_last_lane(dh[n] * u_over);
-                if (lane == 63) {
-                    unsafeAtomicAdd(dC + (size_t)tok * a.G * N + n, for_c);
-                    unsafeAtomicAdd(dB + (size_t)tok * a.G * N + n, for_b);
-                }
+                bc_terms[n] = dh[n] * u_over;
+                bc_terms[N + n] = dy * hs[i + 1][n];
                 const float da = dh[n] * hs[i][n] * an;              // dh * h_prev * a
                 gA[n] = fmaf(da, delta[i], gA[n]);
                 ddelta = fmaf(da, c.a2[n] * kLn2, ddelta);          // A = a2 * ln 2
                 ddelta = fmaf(dh[n] * row[n], xc[i], ddelta);
                 dxc = fmaf(dh[n] * delta[i], row[n], dxc);
                 dh[n] *= an;
+            }
+            {
+                // the wave's 64 channels summed: value j ends up in lanes j * kLanesPerValue ..., one of which stores it
+                const float total = wave_reduce_scatter<2 * N>(bc_terms, lane);
+                if (lane % kLanesPerValue == 0) part[(size_t)tok * part_token + lane / kLanesPerValue] = total;
             }
             float ddt = ddelta;
             if (sp) {
@@ -329,5 +381,17 @@ __global__ __launch_bounds__(256) void bwd_finish_kernel(const BwdFinishArgs a)
         IO::st(d0, f + r);
     }
 }
+
+
+// dB and dC from the per-wave partial sums: one thread per (batch, token, group, value) adds its slots in a fixed order.
+struct BwdBcArgs {
+    const float* part;   // [batch][L][G][slots][2N]
+    float* dB;           // [batch][L][G][N]
+    float* dC;
+    long long rows;      // batch * L * G
+    int slots, N;
+};
+
+__global__ __launch_bounds__(256) void bwd_bc_kernel(const BwdBcArgs a);
 
 }  // namespace bm
