@@ -182,6 +182,72 @@ def decode_loop_bench(args, torch, bd, shapes, synth):
     print(json.dumps(result))
 
 
+def bwd_bench(args, torch, bd, shapes, synth):
+    """Gradients of the full-sequence path (the paper trains the model, App. A.2): one step is one bimamba_bwd call at
+    the headline shape (batch 8, L 8192, d_inner 4096, N 16, bf16 I/O, shared activations, ADD)."""
+    cfg = dict(synth.CONFIGS["headline"])
+    seed = synth.config_seed(9)
+    Bt, L, Dn, N, K, G = (cfg[k] for k in ("batch", "seqlen", "d_inner", "d_state", "d_conv", "n_groups"))
+    desc = bd.make_desc(cfg)
+    pf, pb = synth.make_params(cfg, seed, 0), synth.make_params(cfg, seed, 1)
+    inp = synth.make_inputs(cfg, seed)
+    dpf, dpb, dinp = bd.to_device(pf), bd.to_device(pb), bd.to_device(inp, cfg)
+    io = bd.io_dtype(cfg)
+    g = torch.Generator().manual_seed(seed + 1)
+    dout_host = synth.round_io(torch.randn(Bt, L, Dn, generator=g), cfg["io"])
+    dout = dout_host.to(device="cuda", dtype=io)
+    gi = dict(dx=torch.empty(Bt, L, Dn, dtype=io, device="cuda"), dz=torch.empty(Bt, L, Dn, dtype=io, device="cuda"),
+              ddt=torch.empty(Bt, L, Dn, dtype=io, device="cuda"), dB=torch.empty(Bt, L, G, N, device="cuda"),
+              dC=torch.empty(Bt, L, G, N, device="cuda"))
+    mk = lambda: dict(dconv_w=torch.empty(Dn, K, device="cuda"), dconv_b=torch.empty(Dn, device="cuda"),
+                      dA=torch.empty(Dn, N, device="cuda"), dD=torch.empty(Dn, device="cuda"), ddt_bias=torch.empty(Dn, device="cuda"))
+    qf, qb = mk(), mk()
+    ws = torch.empty(bd.bimamba_bwd_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    call = (desc, bd.make_params(dpf), bd.make_params(dpb), bd.make_inputs(dinp), None, bd.make_tensor(dout),
+            bd.make_input_grads(gi), None, bd.make_param_grads(qf), bd.make_param_grads(qb), ws)
+    for _ in range(args.warmup):
+        bd.bimamba_bwd(*call)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        bd.bimamba_bwd(*call)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    flops, nbytes = shapes.algorithmic_flops_bwd(cfg), shapes.algorithmic_bytes_bwd(cfg)
+    ach = flops / (ms * 1e-3) / 1e12
+    result = {
+        "metric": "bidirectional-scan tokens/s/GPU at d_inner=4096,L=8K; HBM GB/s vs peak",
+        "value": Bt * L / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "headline_bwd", "what_a_step_is": "one bimamba_bwd call: gradients of the headline forward call",
+                   "batch": Bt, "seq_len": L, "d_inner": Dn, "d_state": N, "io_dtype": cfg["io"], "state_dtype": "f32",
+                   "inputs": "shared by both directions", "combine": "add",
+                   "workspace_bytes": int(ws.numel())},
+        "roofline": {"bound": "alu", "achieved": ach, "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
+                     "frac": ach / PEAK_FP32_VECTOR_TFLOPS, "algorithmic_flops": flops, "traffic": None,
+                     "kernel": "bwd_state_kernel + bwd_kernel + bwd_bc_kernel + bwd_finish_kernel (whole call)", "kernel_ms": ms,
+                     "frac_of_unpacked_fp32_peak": ach / PEAK_FP32_UNPACKED_TFLOPS},
+        "hbm": {"achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                "frac": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, "algorithmic_bytes": nbytes},
+    }
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle as orc
+        npy = lambda d: {k: (None if v is None else v.numpy()) for k, v in d.items()}
+        sel = list(range(0, Dn, Dn // 64))
+        one = dict(cfg, batch=1)
+        one_in = {k: v[:1] for k, v in inp.items()}
+        t0 = time.perf_counter()
+        ref = orc.bimamba_bwd(one, npy(pf), npy(pb), npy(one_in), None, dout_host[:1][..., sel].numpy(), sel=sel)
+        cpu_s = time.perf_counter() - t0
+        got = gi["dx"][:1][..., sel].float().cpu().numpy().astype(np.float64)
+        result["cpu_baseline"] = {"value": L / (cpu_s * Dn / len(sel)), "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                                  "seconds": cpu_s, "sample": "batch element 0, all %d tokens, %d of %d channels, fp64 "
+                                  "(rate scaled by the channel fraction)" % (L, len(sel), Dn)}
+        result["rel_l2_dx_vs_oracle"] = float(np.linalg.norm(got - ref[0]["dx"]) / np.linalg.norm(ref[0]["dx"]))
+    print(json.dumps(result))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -206,6 +272,8 @@ def main():
     bd.lib()  # fail loudly if the HIP library is not built
     if args.workload.startswith("cfg3_block"):
         return decode_loop_bench(args, torch, bd, shapes, synth)
+    if args.workload == "headline_bwd":
+        return bwd_bench(args, torch, bd, shapes, synth)
     cfg = dict(synth.CONFIGS[args.workload])
     seed = synth.config_seed(9)
     t0 = time.time()

@@ -302,9 +302,11 @@ __global__ __launch_bounds__(256) void bwd_kernel(const BwdArgs a)
             const float dz = dg * y * dsilu(zv);
             const float dy = dg * silu(zv);
             gD = fmaf(dy, xc[i], gD);
-            float ddelta = 0.0f, dxc = c.dval * dy;
             const float u_over = delta[i] * xc[i];
             float bc_terms[2 * N];                                   // this channel's terms of dB_t (first N) and dC_t
+            // sum_n dh[n] B[n] serves both dDelta (times xc) and dxc (times Delta); sum_n (dh h_prev a)[n] a2[n] is
+            // dDelta's decay part up to the factor ln 2 (A = a2 ln 2)
+            float dh_dot_b = 0.0f, decay_part = 0.0f;
 #pragma unroll
             for (int n = 0; n < N; n++) {
                 const float an = fast_exp2(delta[i] * c.a2[n]);
@@ -313,11 +315,12 @@ __global__ __launch_bounds__(256) void bwd_kernel(const BwdArgs a)
                 bc_terms[N + n] = dy * hs[i + 1][n];
                 const float da = dh[n] * hs[i][n] * an;              // dh * h_prev * a
                 gA[n] = fmaf(da, delta[i], gA[n]);
-                ddelta = fmaf(da, c.a2[n] * kLn2, ddelta);          // A = a2 * ln 2
-                ddelta = fmaf(dh[n] * row[n], xc[i], ddelta);
-                dxc = fmaf(dh[n] * delta[i], row[n], dxc);
+                decay_part = fmaf(da, c.a2[n], decay_part);
+                dh_dot_b = fmaf(dh[n], row[n], dh_dot_b);
                 dh[n] *= an;
             }
+            const float ddelta = fmaf(decay_part, kLn2, dh_dot_b * xc[i]);
+            const float dxc = fmaf(c.dval, dy, dh_dot_b * delta[i]);
             {
                 // the wave's 64 channels summed: value j ends up in lanes j * kLanesPerValue ..., one of which stores it
                 const float total = wave_reduce_scatter<2 * N>(bc_terms, lane);

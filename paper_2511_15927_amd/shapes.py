@@ -45,6 +45,27 @@ def algorithmic_flops(cfg):
     return 2 * Bt * L * Dn * per_tc + (Bt * L * Dn if not cfg["combine"] else 0)
 
 
+def algorithmic_flops_bwd(cfg):
+    """fp32 operations the gradients of the selective-scan layout need per call, both directions, counting the forward
+    quantities the backward rule uses (they have to be formed again): per (token, channel, direction) and state the
+    forward's 7, then dh (fma 2), the dB and dC terms (2), dh*h_prev*a (2), its uses in dA (fma 2) and dDelta (fma 2),
+    dh.B (fma 2), dh*a (1) and the two adds of the group sums (2) = 22; per (token, channel, direction) besides the
+    forward's 22: SiLU' twice (6 each), dz, dy, dD (4), dDelta / dxc assembly (4), conv gradient (4 fma for dx, 4 for
+    dw, 1 for db = 17), = 59."""
+    Bt, L, Dn, N = cfg["batch"], cfg["seqlen"], cfg["d_inner"], cfg["d_state"]
+    return 2 * Bt * L * Dn * (59 + 22 * N)
+
+
+def algorithmic_bytes_bwd(cfg, shared_inputs=True):
+    """Bytes the gradient call must move once: x, z, dt, dout read, dx, dz, ddt written per direction's activations
+    (B, C and their fp32 gradients amortise over d_inner)."""
+    e = 2 if cfg["io"] == "bf16" else 4
+    Bt, L, Dn, GN = cfg["batch"], cfg["seqlen"], cfg["d_inner"], cfg["n_groups"] * cfg["d_state"]
+    ndir = 1 if shared_inputs else 2
+    out_w = Dn * (2 if cfg["combine"] else 1)
+    return Bt * L * (ndir * (3 * Dn + 2 * GN) * e + out_w * e + ndir * (3 * Dn * e + 2 * GN * 4))
+
+
 SSD_CHUNK = 64
 
 
