@@ -641,7 +641,7 @@ namespace {
 struct BwdPlan {
     int chunk, nchunk;
     int tiles_per_group;
-    size_t off_bc[2], off_state, off_dx, off_dz, off_ddt, off_part[2], total;
+    size_t off_bc[2], off_state, off_parked, off_part[2], total;
 };
 
 int check_bwd_desc(const bimamba_desc* d)
@@ -660,14 +660,12 @@ BwdPlan make_bwd_plan(const bimamba_desc* d)
     p.chunk = bm::bwd_chunk_tokens(d->d_state);
     p.nchunk = d->seqlen > 0 ? (d->seqlen + p.chunk - 1) / p.chunk : 1;
     const size_t bc = align_up((size_t)d->batch * d->seqlen * d->n_groups * 2 * d->d_state * sizeof(float), 256);
-    const size_t plane = align_up((size_t)2 * d->batch * d->seqlen * d->d_inner * sizeof(float), 256);
+    const size_t parked = align_up((size_t)d->batch * d->seqlen * d->d_inner * sizeof(Parked), 256);
     size_t off = 0;
     p.off_bc[0] = off; off += bc;
     p.off_bc[1] = off; off += bc;    // sized for separate activations
     p.off_state = off; off += align_up((size_t)2 * d->batch * p.nchunk * d->d_inner * d->d_state * sizeof(float), 256);
-    p.off_dx = off; off += plane;
-    p.off_dz = off; off += plane;
-    p.off_ddt = off; off += plane;
+    p.off_parked = off; off += parked;
     // per-wave partial sums of dB | dC: one slot per channel tile of a group and direction
     p.tiles_per_group = (d->d_inner / d->n_groups + 63) / 64;
     const size_t part = align_up((size_t)d->batch * d->seqlen * d->n_groups * p.tiles_per_group * 2 * d->d_state * sizeof(float), 256);
@@ -757,18 +755,17 @@ int bimamba_bwd(const bimamba_desc* d, const bimamba_params* pf, const bimamba_p
             da.x = targ(in->x); da.z = targ(in->z); da.dt = targ(in->dt);
             da.bc = reinterpret_cast<const float*>(ws + plan.off_bc[shared ? 0 : s]);
             da.conv_w = p->conv_w; da.conv_b = p->conv_b; da.A = p->A; da.D = p->D; da.dt_bias = p->dt_bias;
-            (void)gi;
             // shared activations: both directions' waves fill slots of one buffer (the two parts are adjacent)
             a.bc_part[s] = reinterpret_cast<float*>(ws + plan.off_part[shared ? 0 : s]);
+            a.gdx[s] = targ(gi->dx); a.gdz[s] = targ(gi->dz); a.gddt[s] = targ(gi->ddt);
             a.dA[s] = g->dA; a.dD[s] = g->dD; a.dconv_w[s] = g->dconv_w; a.dconv_b[s] = g->dconv_b; a.ddt_bias[s] = g->ddt_bias;
         }
         a.dout = targ(*dout);
         a.state = reinterpret_cast<float*>(ws + plan.off_state);
-        a.dx = reinterpret_cast<float*>(ws + plan.off_dx);
-        a.dz = reinterpret_cast<float*>(ws + plan.off_dz);
-        a.ddt = reinterpret_cast<float*>(ws + plan.off_ddt);
+        a.parked = reinterpret_cast<Parked*>(ws + plan.off_parked);
         a.L = d->seqlen; a.Dn = d->d_inner; a.G = d->n_groups; a.K = d->d_conv; a.nchunk = plan.nchunk;
         a.dt_softplus = d->dt_softplus; a.separate = d->combine == BIMAMBA_COMBINE_SEPARATE;
+        a.park = shared;
         a.bc_slots = plan.tiles_per_group * (shared ? 2 : 1);
         a.bc_slot_of_rev = shared ? plan.tiles_per_group : 0;
         bm::launch_bwd(d->d_state, bf16, a, d->batch, st);
@@ -780,16 +777,6 @@ int bimamba_bwd(const bimamba_desc* d, const bimamba_params* pf, const bimamba_p
             ba.rows = (long long)d->batch * d->seqlen * d->n_groups;
             ba.slots = a.bc_slots; ba.N = d->d_state;
             bm::launch_bwd_bc(ba, st);
-        }
-        const float* planes[3] = {a.dx, a.dz, a.ddt};
-        for (int k = 0; k < 3; k++) {
-            BwdFinishArgs fa{};
-            fa.src = planes[k];
-            const bimamba_tensor& t0 = k == 0 ? din_f->dx : k == 1 ? din_f->dz : din_f->ddt;
-            fa.dst[0] = targ(t0);
-            if (din_b) fa.dst[1] = targ(k == 0 ? din_b->dx : k == 1 ? din_b->dz : din_b->ddt);
-            fa.batch = d->batch; fa.L = d->seqlen; fa.C = d->d_inner;
-            bm::launch_bwd_finish(bf16, fa, st);
         }
     }
     const hipError_t now = hipPeekAtLastError();

@@ -61,15 +61,6 @@ void launch_bwd(int d_state, int io_bf16, const BwdArgs& a, int batch, hipStream
 #undef BM_BWD
 }
 
-void launch_bwd_finish(int io_bf16, const BwdFinishArgs& a, hipStream_t st)
-{
-    const long long n = a.batch * a.L * a.C;
-    if (n <= 0) return;
-    const dim3 grid((unsigned)((n + 255) / 256));
-    if (io_bf16) hipLaunchKernelGGL(bwd_finish_kernel<IoBF16>, grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL(bwd_finish_kernel<IoF32>, grid, dim3(256), 0, st, a);
-}
-
 void launch_bwd_zero(float* p, long long n, hipStream_t st)
 {
     if (!p || n <= 0) return;

@@ -20,21 +20,27 @@
 //                     registers (kBwdChunk * N values per lane) and then walks the chunk backwards.
 // dB_t and dC_t are sums over the channels of a group: each wave adds its 64 channels with lane-permute adds and one
 // lane adds the result to the caller's fp32 buffer with a hardware atomic.  Parameter gradients are kept per lane and
-// added atomically once per chain (the sum over the batch).  The per-direction gradients of x, z and Delta leave this
-// kernel as fp32 rows of a scratch buffer; bwd_finish_kernel adds the two directions (when they read the same
-// activations) and rounds once to the I/O dtype.
+// added atomically once per chain (the sum over the batch).  When both directions read the same activations their
+// gradients of x, z and Delta have to be added: the two waves of a channel tile walk the tokens in opposite orders
+// and meet in the middle, as in the forward sweep; each parks its fp32 values for the half it reaches first and, past
+// one workgroup barrier, adds what the other parked to its own values for the other half and rounds once to the I/O dtype.
 #pragma once
 #include "kernels.h"
 
 namespace bm {
 
+// The fp32 gradients of x, z and Delta of one (token, channel) as one direction leaves them for the other to add.
+struct Parked {
+    float dx, dz, ddt;
+};
+
 struct BwdArgs {
     DirArgs dir[2];          // x, z, dt views, prepared fp32 B|C rows and parameters of each direction
     TensorArg dout;          // [batch][L][Dn] (ADD) or [batch][L][2 Dn] (SEPARATE), I/O dtype
     float* state;            // [2][batch][nchunk][Dn][N]: the state entering each chunk (scan order)
-    float* dx;               // [2][batch][L][Dn] fp32, per direction; dz and ddt follow at the same spacing
-    float* dz;
-    float* ddt;
+    Parked* parked;          // [batch][L][Dn]: values of the direction that reaches a token first (park only)
+    TensorArg gdx[2], gdz[2], gddt[2];   // the caller's gradient views per direction (equal when park)
+    int park;                // both directions read the same activations: their gradients are added (see above)
     float* bc_part[2];       // per direction: [batch][L][G][slots][2N] fp32 partial sums of dB | dC, one slot per wave
     int bc_slots;            // slots per group: channel tiles of a group (x 2 when both directions feed one buffer)
     int bc_slot_of_rev;      // slot offset of the reverse direction's waves (0 when it has a buffer of its own)
@@ -149,9 +155,10 @@ __device__ __forceinline__ bool bwd_chain_setup(const BwdArgs& a, int w, BwdChai
     s = w & 1;
     b = blockIdx.z;
     const int lane = threadIdx.x & 63;
-    const int tile = (int)blockIdx.x * 2 + (w >> 1);
-    if (tile * 64 >= a.Dn) return false;                 // the second tile of the last workgroup may not exist
-    valid = tile * 64 + lane < a.Dn;
+    int tile = (int)blockIdx.x * 2 + (w >> 1);
+    const bool exists = tile * 64 < a.Dn;                // the second tile of the last workgroup may not exist:
+    if (!exists) tile -= 1;                              // its waves shadow the first (they compute and store nothing)
+    valid = exists && tile * 64 + lane < a.Dn;
     ch = min(tile * 64 + lane, a.Dn - 1);                 // lanes past the last channel shadow it and contribute nothing
     const DirArgs& da = a.dir[s];
     const int grp = (tile * 64) / (a.Dn / a.G);          // uniform: a tile never straddles two B/C groups
@@ -170,7 +177,7 @@ __device__ __forceinline__ bool bwd_chain_setup(const BwdArgs& a, int w, BwdChai
     c.bc = da.bc + ((size_t)b * a.L * a.G + grp) * (2 * N);
     c.L = a.L;
     c.dir = s == 0 ? 1 : -1;
-    return true;
+    return exists;
 }
 
 // grid (ceil(ceil(Dn / 64) / 2), 1, batch), block 256: waves 0 / 1 the forward / reverse chain of one channel tile,
@@ -231,14 +238,35 @@ __global__ __launch_bounds__(256) void bwd_kernel(const BwdArgs a)
     BwdChain<N, IO> c;
     int s, b, ch;
     bool valid;
-    if (!bwd_chain_setup<N, IO>(a, w, c, s, b, ch, valid)) return;
+    // a wave without a tile of its own still runs (as a shadow of its neighbour): the barrier below counts four waves
+    const bool exists = bwd_chain_setup<N, IO>(a, w, c, s, b, ch, valid);
     const bool sp = a.dt_softplus != 0;
-    const int grp = ((int)blockIdx.x * 2 + (w >> 1)) * 64 / (a.Dn / a.G);
+    const int my_tile = min((int)blockIdx.x * 2 + (w >> 1), (a.Dn + 63) / 64 - 1);
+    const int grp = my_tile * 64 / (a.Dn / a.G);
     const T* dob = (const T*)a.dout.p + (size_t)b * a.dout.sb + ch + (a.separate ? s * a.Dn : 0);
-    const size_t plane = ((size_t)s * gridDim.z + b) * a.L * a.Dn + ch;     // this chain's column in the per-direction rows
+    const size_t plane = (size_t)b * a.L * a.Dn + ch;                       // this chain's column in the parked rows
+    T* const odx = (T*)a.gdx[s].p + (size_t)b * a.gdx[s].sb + ch;
+    T* const odz = (T*)a.gdz[s].p + (size_t)b * a.gdz[s].sb + ch;
+    T* const oddt = (T*)a.gddt[s].p + (size_t)b * a.gddt[s].sb + ch;
+    // In scan order both waves walk j = L-1 .. 0 and park j >= jm: tokens [L/2, L) for the forward direction's wave,
+    // [0, L/2) for the reverse one's.  The other wave's values for j < jm are fetched two tokens ahead (q0, q1): a
+    // load issued where its value is needed would stall the one wave this SIMD holds for a memory round trip.
+    const int jm = a.park ? (s == 0 ? a.L / 2 : a.L - a.L / 2) : a.L;
+    float q0[3] = {0.0f, 0.0f, 0.0f}, q1[3] = {0.0f, 0.0f, 0.0f};
+    auto fetch_parked = [&](float (&q)[3], int j) {
+        const Parked v = a.parked[plane + (size_t)c.token(max(j, 0)) * a.Dn];
+        q[0] = v.dx; q[1] = v.dz; q[2] = v.ddt;
+    };
+    // the barrier is a workgroup-scope release / acquire: past it, what the other wave of the tile parked is visible
+    auto meet = [&]() {
+        __syncthreads();
+        fetch_parked(q0, jm - 1);
+        fetch_parked(q1, jm - 2);
+    };
+    if (a.park && jm >= a.L) meet();                     // a one-token call: the reverse direction's wave parks nothing
     // this wave's slot of the dB | dC partial sums: [batch][L][G][slots][2N]
     const int tiles_per_group = (a.Dn / a.G + 63) / 64;
-    const int slot = ((int)blockIdx.x * 2 + (w >> 1)) % tiles_per_group + (s == 1 ? a.bc_slot_of_rev : 0);
+    const int slot = my_tile % tiles_per_group + (s == 1 ? a.bc_slot_of_rev : 0);
     float* const part = a.bc_part[s] + (((size_t)b * a.L * a.G + grp) * a.bc_slots + slot) * (2 * N);
     const size_t part_token = (size_t)a.G * a.bc_slots * 2 * N;
     constexpr int kLanesPerValue = 64 / (2 * N);
@@ -324,7 +352,7 @@ __global__ __launch_bounds__(256) void bwd_kernel(const BwdArgs a)
             {
                 // the wave's 64 channels summed: value j ends up in lanes j * kLanesPerValue ..., one of which stores it
                 const float total = wave_reduce_scatter<2 * N>(bc_terms, lane);
-                if (lane % kLanesPerValue == 0) part[(size_t)tok * part_token + lane / kLanesPerValue] = total;
+                if (exists && lane % kLanesPerValue == 0) part[(size_t)tok * part_token + lane / kLanesPerValue] = total;
             }
             float ddt = ddelta;
             if (sp) {
@@ -339,11 +367,20 @@ __global__ __launch_bounds__(256) void bwd_kernel(const BwdArgs a)
             gw[0] = fmaf(dpre, xraw[i], gw[0]);
             const float dxv = fmaf(c.w4[3], dpre, fmaf(c.w4[2], dp1, fmaf(c.w4[1], dp2, c.w4[0] * dp3)));
             dp3 = dp2; dp2 = dp1; dp1 = dpre;
-            if (valid) {
-                const size_t at = plane + (size_t)tok * a.Dn;
-                a.dx[at] = dxv;
-                a.dz[at] = dz;
-                a.ddt[at] = ddt;
+            const int j = first + i;
+            if (j >= jm) {                                // never taken unless a.park
+                if (valid) a.parked[plane + (size_t)tok * a.Dn] = Parked{dxv, dz, ddt};
+                if (j == jm) meet();
+            } else {
+                const float px = q0[0], pz = q0[1], pd = q0[2];
+#pragma unroll
+                for (int e = 0; e < 3; e++) q0[e] = q1[e];
+                if (a.park) fetch_parked(q1, j - 2);
+                if (valid) {
+                    IO::st(odx + (long long)tok * a.gdx[s].st, dxv + px);
+                    IO::st(odz + (long long)tok * a.gdz[s].st, dz + pz);
+                    IO::st(oddt + (long long)tok * a.gddt[s].st, ddt + pd);
+                }
             }
         }
     }
@@ -359,32 +396,6 @@ __global__ __launch_bounds__(256) void bwd_kernel(const BwdArgs a)
         if (a.ddt_bias[s] && sp) unsafeAtomicAdd(a.ddt_bias[s] + ch, gbias);
     }
 }
-
-// Adds the two directions' fp32 gradient rows where both read the same activations and rounds once to the I/O dtype.
-struct BwdFinishArgs {
-    const float* src;        // [2][batch][L][C] fp32
-    TensorArg dst[2];        // destination view per direction (dst[1].p null: both directions summed into dst[0])
-    long long batch, L, C;
-};
-
-template <typename IO>
-__global__ __launch_bounds__(256) void bwd_finish_kernel(const BwdFinishArgs a)
-{
-    using T = typename IO::T;
-    const long long per_dir = a.batch * a.L * a.C;
-    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= per_dir) return;
-    const long long col = i % a.C, t = (i / a.C) % a.L, b = i / (a.C * a.L);
-    const float f = a.src[i], r = a.src[per_dir + i];
-    T* d0 = (T*)a.dst[0].p + b * a.dst[0].sb + t * a.dst[0].st + col;
-    if (a.dst[1].p) {
-        IO::st(d0, f);
-        IO::st((T*)a.dst[1].p + b * a.dst[1].sb + t * a.dst[1].st + col, r);
-    } else {
-        IO::st(d0, f + r);
-    }
-}
-
 
 // dB and dC from the per-wave partial sums: one thread per (batch, token, group, value) adds its slots in a fixed order.
 struct BwdBcArgs {

@@ -37,12 +37,10 @@ void launch_ssd_duo(int d_state, int headdim, const SsdStatePair& sp, int batch,
 void launch_ssd_state(int d_state, int headdim, const SsdStatePair& sp, int subs, int batch, hipStream_t st);
 
 struct BwdArgs;
-struct BwdFinishArgs;
 struct BwdBcArgs;
 void launch_bwd_bc(const BwdBcArgs& a, hipStream_t st);
 bool bwd_supported(int d_state);
 int bwd_chunk_tokens(int d_state);
 void launch_bwd(int d_state, int io_bf16, const BwdArgs& a, int batch, hipStream_t st);
-void launch_bwd_finish(int io_bf16, const BwdFinishArgs& a, hipStream_t st);
 void launch_bwd_zero(float* p, long long n, hipStream_t st);
 }  // namespace bm
