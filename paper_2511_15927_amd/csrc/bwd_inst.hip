@@ -41,7 +41,9 @@ template <int N, typename IO>
 static void launch_pair(const BwdArgs& a, int batch, hipStream_t st)
 {
     const dim3 grid((unsigned)(((a.Dn + 63) / 64 + 1) / 2), 1, (unsigned)batch);
-    hipLaunchKernelGGL((bwd_state_kernel<N, IO>), grid, dim3(256), 0, st, a);
+    constexpr int kStateTile = 64 / kBwdStateLanes<N>;    // channels per wave of the state pass
+    const dim3 state_grid((unsigned)(((a.Dn + kStateTile - 1) / kStateTile + 1) / 2), 1, (unsigned)batch);
+    hipLaunchKernelGGL((bwd_state_kernel<N, IO>), state_grid, dim3(256), 0, st, a);
     hipLaunchKernelGGL((bwd_kernel<N, IO>), grid, dim3(256), 0, st, a);
 }
 

@@ -148,20 +148,22 @@ struct BwdChain {
     }
 };
 
-template <int N, typename IO>
+// S lanes per chain: a wave's tile is 64 / S channels, lane l on channel l / S of it.
+template <int N, typename IO, int S = 1>
 __device__ __forceinline__ bool bwd_chain_setup(const BwdArgs& a, int w, BwdChain<N, IO>& c, int& s, int& b, int& ch, bool& valid)
 {
     using T = typename IO::T;
+    constexpr int CPW = 64 / S;
     s = w & 1;
     b = blockIdx.z;
     const int lane = threadIdx.x & 63;
     int tile = (int)blockIdx.x * 2 + (w >> 1);
-    const bool exists = tile * 64 < a.Dn;                // the second tile of the last workgroup may not exist:
+    const bool exists = tile * CPW < a.Dn;               // the second tile of the last workgroup may not exist:
     if (!exists) tile -= 1;                              // its waves shadow the first (they compute and store nothing)
-    valid = exists && tile * 64 + lane < a.Dn;
-    ch = min(tile * 64 + lane, a.Dn - 1);                 // lanes past the last channel shadow it and contribute nothing
+    valid = exists && tile * CPW + lane / S < a.Dn;
+    ch = min(tile * CPW + lane / S, a.Dn - 1);            // lanes past the last channel shadow it and contribute nothing
     const DirArgs& da = a.dir[s];
-    const int grp = (tile * 64) / (a.Dn / a.G);          // uniform: a tile never straddles two B/C groups
+    const int grp = (tile * CPW) / (a.Dn / a.G);         // uniform: a tile never straddles two B/C groups
 #pragma unroll
     for (int n = 0; n < N; n++) c.a2[n] = da.A[(size_t)ch * N + n] * kLog2e;
 #pragma unroll
@@ -180,38 +182,67 @@ __device__ __forceinline__ bool bwd_chain_setup(const BwdArgs& a, int w, BwdChai
     return exists;
 }
 
-// grid (ceil(ceil(Dn / 64) / 2), 1, batch), block 256: waves 0 / 1 the forward / reverse chain of one channel tile,
-// waves 2 / 3 those of the next.
+// Lanes per chain of the state pass.  This pass has no sums across channels, so splitting the states of a chain over
+// two lanes costs only the repeated per-channel part (conv, SiLU, Delta: a third of the stream) and puts two waves on
+// every SIMD where one lane per chain leaves one, which issues an instruction only every seven cycles.
+template <int N>
+constexpr int kBwdStateLanes = N >= 8 ? 2 : 1;
+
+// grid (ceil(ceil(Dn / (64 / S)) / 2), 1, batch), block 256: waves 0 / 1 the forward / reverse chain of one channel
+// tile, waves 2 / 3 those of the next; S = kBwdStateLanes<N>, lane l of a wave holds states (l % S) * N / S ... of its chain.
 template <int N, typename IO>
-__global__ __launch_bounds__(256) void bwd_state_kernel(const BwdArgs a)
+__global__ __launch_bounds__(256, kBwdStateLanes<N>) void bwd_state_kernel(const BwdArgs a)
 {
     constexpr int CT = kBwdChunk<N>;
+    constexpr int S = kBwdStateLanes<N>;
+    constexpr int NS = N / S;
+    static_assert(NS % 4 == 0, "a lane's states are loaded and stored four at a time");
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     BwdChain<N, IO> c;
     int s, b, ch;
     bool valid;
-    if (!bwd_chain_setup<N, IO>(a, w, c, s, b, ch, valid)) return;
+    if (!bwd_chain_setup<N, IO, S>(a, w, c, s, b, ch, valid)) return;
     const bool sp = a.dt_softplus != 0;
-    float h[N];
+    const int part = (int)(threadIdx.x & 63) % S;        // which NS of the chain's states this lane holds
+    float a2[NS], h[NS];
 #pragma unroll
-    for (int n = 0; n < N; n++) h[n] = 0.0f;
+    for (int n = 0; n < NS; n++) {
+        a2[n] = c.a2[n];
+#pragma unroll
+        for (int e = 1; e < S; e++) a2[n] = part == e ? c.a2[e * NS + n] : a2[n];
+        h[n] = 0.0f;
+    }
     float x1 = 0.0f, x2 = 0.0f, x3 = 0.0f;   // raw x one, two, three tokens back in scan order
-    float* dst = a.state + (((size_t)s * gridDim.z + b) * a.nchunk * a.Dn + ch) * N;
-    for (int k = 0; k < a.nchunk; k++) {
-        if (valid) {
-#pragma unroll
-            for (int n = 0; n < N; n++) dst[n] = h[n];
-        }
-        dst += (size_t)a.Dn * N;
-        if (k == a.nchunk - 1) break;    // the state after the last chunk feeds nothing
-        // the whole chunk's activations are requested before the first is used
-        typename IO::T xr[CT], dr[CT];
+    float* dst = a.state + (((size_t)s * gridDim.z + b) * a.nchunk * a.Dn + ch) * N + part * NS;
+    // A SIMD with one or two waves has little to hide a memory round trip behind: the activations of the next chunk
+    // are requested before the current chunk is worked through.  That includes the chunk's B rows: the same address
+    // in every lane of a part, but as scalar loads their round trips would lie open in front of every other token (a
+    // wave waits for all of its scalar loads at once, so none can be kept in flight across a use); as vector loads
+    // into the registers such a SIMD has to spare they arrive a chunk early.
+    typename IO::T xr[CT], dr[CT], xnext[CT], dnext[CT];
+    Float4 br[CT][NS / 4], bnext[CT][NS / 4];
+    unsigned in_vgpr = (unsigned)(part * NS * sizeof(float));
+    keep_narrow(in_vgpr);                                // an offset the compiler cannot prove uniform
+    auto request = [&](typename IO::T (&xq)[CT], typename IO::T (&dq)[CT], Float4 (&bq)[CT][NS / 4], int k) {
 #pragma unroll
         for (int i = 0; i < CT; i++) {
             const long long t = c.token(min(k * CT + i, a.L - 1));
-            xr[i] = c.xb[t * c.xs];
-            dr[i] = c.dtb_ptr[t * c.dts];
+            xq[i] = c.xb[t * c.xs];
+            dq[i] = c.dtb_ptr[t * c.dts];
+            const Float4* row = (const Float4*)((const char*)(c.bc + t * c.bcs) + in_vgpr);
+#pragma unroll
+            for (int q = 0; q < NS / 4; q++) bq[i][q] = row[q];
         }
+    };
+    request(xr, dr, br, 0);
+    for (int k = 0; k < a.nchunk; k++) {
+        if (valid) {
+#pragma unroll
+            for (int n = 0; n < NS; n++) dst[n] = h[n];
+        }
+        dst += (size_t)a.Dn * N;
+        if (k == a.nchunk - 1) break;    // the state after the last chunk feeds nothing
+        request(xnext, dnext, bnext, k + 1);
 #pragma unroll
         for (int i = 0; i < CT; i++) {
             if (k * CT + i >= a.L) break;
@@ -221,9 +252,15 @@ __global__ __launch_bounds__(256) void bwd_state_kernel(const BwdArgs a)
             const float xc = silu(pre);
             const float delta = c.delta_of(IO::cvt(dr[i]), sp);
             const float u = delta * xc;
-            uniform_ro_ptr row = c.row(k * CT + i);
 #pragma unroll
-            for (int n = 0; n < N; n++) h[n] = fmaf(fast_exp2(delta * c.a2[n]), h[n], u * row[n]);
+            for (int n = 0; n < NS; n++) h[n] = fmaf(fast_exp2(delta * a2[n]), h[n], u * br[i][n / 4][n % 4]);
+        }
+#pragma unroll
+        for (int i = 0; i < CT; i++) {
+            xr[i] = xnext[i];
+            dr[i] = dnext[i];
+#pragma unroll
+            for (int q = 0; q < NS / 4; q++) br[i][q] = bnext[i][q];
         }
     }
 }
@@ -277,27 +314,38 @@ __global__ __launch_bounds__(256) void bwd_kernel(const BwdArgs a)
     float gD = 0.0f, gcb = 0.0f, gbias = 0.0f, gw[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     float dp1 = 0.0f, dp2 = 0.0f, dp3 = 0.0f;   // dpre of the tokens one, two, three steps later in scan order
 
+    // as in the state pass: the next chunk's activations are requested before this chunk is worked through
+    T xr[CT], dr[CT], zr[CT], gr[CT], xnext[CT], dnext[CT], znext[CT], gnext[CT];
+    auto request = [&](T (&xq)[CT], T (&dq)[CT], T (&zq)[CT], T (&gq)[CT], int k) {
+#pragma unroll
+        for (int i = 0; i < CT; i++) {
+            const long long t = c.token(min(max(k, 0) * CT + i, a.L - 1));
+            xq[i] = c.xb[t * c.xs];
+            dq[i] = c.dtb_ptr[t * c.dts];
+            zq[i] = c.zb[t * c.zs];
+            gq[i] = dob[t * a.dout.st];
+        }
+    };
+    float hnext[N];                                      // the state entering the next chunk to be walked
+    auto request_state = [&](int k) {
+        const float* src = a.state + ((((size_t)s * gridDim.z + b) * a.nchunk + max(k, 0)) * a.Dn + ch) * N;
+#pragma unroll
+        for (int n = 0; n < N; n++) hnext[n] = src[n];
+    };
+    request(xr, dr, zr, gr, a.nchunk - 1);
+    request_state(a.nchunk - 1);
     for (int k = a.nchunk - 1; k >= 0; k--) {
         const int first = k * CT;                                   // scan index of the chunk's first token
         const int count = min(CT, a.L - first);
-        // the chunk's activations, and the three raw x before it
-        T xr[CT], dr[CT], zr[CT], gr[CT];
-#pragma unroll
-        for (int i = 0; i < CT; i++) {
-            const long long t = c.token(min(first + i, a.L - 1));
-            xr[i] = c.xb[t * c.xs];
-            dr[i] = c.dtb_ptr[t * c.dts];
-            zr[i] = c.zb[t * c.zs];
-            gr[i] = dob[t * a.dout.st];
-        }
+        request(xnext, dnext, znext, gnext, k - 1);
         float xraw[CT + 3];
-        xraw[0] = c.raw_x(first - 3);
-        xraw[1] = c.raw_x(first - 2);
-        xraw[2] = c.raw_x(first - 1);
-        const float* src = a.state + ((((size_t)s * gridDim.z + b) * a.nchunk + k) * a.Dn + ch) * N;
+        // the three raw x before the chunk are the last three of the chunk requested above (whole: only the last can be short)
+#pragma unroll
+        for (int e = 0; e < 3; e++) xraw[e] = k > 0 ? IO::cvt(xnext[CT - 3 + e]) : 0.0f;
         float hs[CT + 1][N];   // hs[i] = the state entering token i of the chunk
 #pragma unroll
-        for (int n = 0; n < N; n++) hs[0][n] = src[n];
+        for (int n = 0; n < N; n++) hs[0][n] = hnext[n];
+        request_state(k - 1);
         float xc[CT], delta[CT], pre[CT];
         // forward over the chunk, keeping every state
 #pragma unroll
@@ -382,6 +430,13 @@ __global__ __launch_bounds__(256) void bwd_kernel(const BwdArgs a)
                     IO::st(oddt + (long long)tok * a.gddt[s].st, ddt + pd);
                 }
             }
+        }
+#pragma unroll
+        for (int i = 0; i < CT; i++) {
+            xr[i] = xnext[i];
+            dr[i] = dnext[i];
+            zr[i] = znext[i];
+            gr[i] = gnext[i];
         }
     }
     if (valid) {
