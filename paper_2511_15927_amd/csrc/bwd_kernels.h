@@ -280,33 +280,67 @@ __global__ __launch_bounds__(256) void bwd_kernel(const BwdArgs a)
     const bool sp = a.dt_softplus != 0;
     const int my_tile = min((int)blockIdx.x * 2 + (w >> 1), (a.Dn + 63) / 64 - 1);
     const int grp = my_tile * 64 / (a.Dn / a.G);
-    const T* dob = (const T*)a.dout.p + (size_t)b * a.dout.sb + ch + (a.separate ? s * a.Dn : 0);
-    const size_t plane = (size_t)b * a.L * a.Dn + ch;                       // this chain's column in the parked rows
-    T* const odx = (T*)a.gdx[s].p + (size_t)b * a.gdx[s].sb + ch;
-    T* const odz = (T*)a.gdz[s].p + (size_t)b * a.gdz[s].sb + ch;
-    T* const oddt = (T*)a.gddt[s].p + (size_t)b * a.gddt[s].sb + ch;
+    // Addresses: every tensor is walked through a wave-uniform byte pointer (kept in scalar registers and stepped by
+    // scalar adds) plus a byte offset of the lane that is fixed for the whole walk.  Per-lane pointers indexed by the
+    // token cost a few scalar multiplies per access, a fifth of this kernel's instructions when it was written that
+    // way.  (Forcing the stores into the scalar-base form as well, by keeping the lane offsets 32 bits wide in the
+    // blocks of the stores, was measured slower: the pointers then stay live in scalar registers up to each store and
+    // the B and C rows push them out into lanes of a vector register.)
+    const DirArgs& da = a.dir[s];
+    unsigned lo_t = (unsigned)(ch * sizeof(T));                              // x, z, dt, dout, dx, dz, ddt
+    unsigned lo_pk = (unsigned)(ch * sizeof(Parked));
+    unsigned lo_state = (unsigned)(ch * N * sizeof(float));
+    constexpr int kLanesPerValue = 64 / (2 * N);
+    unsigned lo_part = (unsigned)((lane / kLanesPerValue) * sizeof(float));
+    struct Walked {
+        const char* base;    // token 0 of this batch element (and direction, where the tensor has one half per direction)
+        int stride;          // bytes per token (the host bounds token strides at 2^26 elements, channels included)
+    };
+    const Walked wx{(const char*)da.x.p + (size_t)b * da.x.sb * sizeof(T), (int)(da.x.st * (long long)sizeof(T))};
+    const Walked wdt{(const char*)da.dt.p + (size_t)b * da.dt.sb * sizeof(T), (int)(da.dt.st * (long long)sizeof(T))};
+    const Walked wz{(const char*)da.z.p + (size_t)b * da.z.sb * sizeof(T), (int)(da.z.st * (long long)sizeof(T))};
+    const Walked wg{(const char*)a.dout.p + ((size_t)b * a.dout.sb + (a.separate ? s * a.Dn : 0)) * sizeof(T),
+                    (int)(a.dout.st * (long long)sizeof(T))};
+    const Walked wodx{(const char*)a.gdx[s].p + (size_t)b * a.gdx[s].sb * sizeof(T), (int)(a.gdx[s].st * (long long)sizeof(T))};
+    const Walked wodz{(const char*)a.gdz[s].p + (size_t)b * a.gdz[s].sb * sizeof(T), (int)(a.gdz[s].st * (long long)sizeof(T))};
+    const Walked woddt{(const char*)a.gddt[s].p + (size_t)b * a.gddt[s].sb * sizeof(T), (int)(a.gddt[s].st * (long long)sizeof(T))};
+    const Walked wpk{(const char*)(a.parked + (size_t)b * a.L * a.Dn), a.Dn * (int)sizeof(Parked)};
+    // this wave's slot of the dB | dC partial sums: [batch][L][G][slots][2N]
+    const int tiles_per_group = (a.Dn / a.G + 63) / 64;
+    const int slot = my_tile % tiles_per_group + (s == 1 ? a.bc_slot_of_rev : 0);
+    const Walked wpart{(const char*)(a.bc_part[s] + (((size_t)b * a.L * a.G + grp) * a.bc_slots + slot) * (2 * N)),
+                       a.G * a.bc_slots * 2 * N * (int)sizeof(float)};
+    const Walked wrow{(const char*)c.bc, (int)(c.bcs * (long long)sizeof(float))};
+    const char* const state_base = (const char*)(a.state + ((size_t)s * gridDim.z + b) * a.nchunk * a.Dn * N);
+    const long long state_stride = (long long)a.Dn * N * (long long)sizeof(float);
+    auto at_scan = [&](const Walked& t, int scan_index) { return t.base + (long long)c.token(scan_index) * t.stride; };
+    // the per-token pointers start at the last token in scan order and move one token against it per step
+    const char* p_odx = at_scan(wodx, a.L - 1);
+    const char* p_odz = at_scan(wodz, a.L - 1);
+    const char* p_oddt = at_scan(woddt, a.L - 1);
+    const char* p_pk = at_scan(wpk, a.L - 1);
+    const char* p_part = at_scan(wpart, a.L - 1);
+    const char* p_row = at_scan(wrow, a.L - 1);
+    const int s_odx = c.dir * wodx.stride, s_odz = c.dir * wodz.stride, s_oddt = c.dir * woddt.stride;
+    const int s_pk = c.dir * wpk.stride, s_part = c.dir * wpart.stride, s_row = c.dir * wrow.stride;
+    const int s_x = c.dir * wx.stride, s_dt = c.dir * wdt.stride, s_z = c.dir * wz.stride, s_g = c.dir * wg.stride;
+
     // In scan order both waves walk j = L-1 .. 0 and park j >= jm: tokens [L/2, L) for the forward direction's wave,
     // [0, L/2) for the reverse one's.  The other wave's values for j < jm are fetched two tokens ahead (q0, q1): a
     // load issued where its value is needed would stall the one wave this SIMD holds for a memory round trip.
     const int jm = a.park ? (s == 0 ? a.L / 2 : a.L - a.L / 2) : a.L;
     float q0[3] = {0.0f, 0.0f, 0.0f}, q1[3] = {0.0f, 0.0f, 0.0f};
-    auto fetch_parked = [&](float (&q)[3], int j) {
-        const Parked v = a.parked[plane + (size_t)c.token(max(j, 0)) * a.Dn];
+    auto fetch_parked = [&](float (&q)[3], const char* row) {
+        const Parked v = *(const Parked*)(row + lo_pk);
         q[0] = v.dx; q[1] = v.dz; q[2] = v.ddt;
     };
     // the barrier is a workgroup-scope release / acquire: past it, what the other wave of the tile parked is visible
     auto meet = [&]() {
         __syncthreads();
-        fetch_parked(q0, jm - 1);
-        fetch_parked(q1, jm - 2);
+        if (jm >= 1) fetch_parked(q0, at_scan(wpk, jm - 1));
+        if (jm >= 2) fetch_parked(q1, at_scan(wpk, jm - 2));
     };
     if (a.park && jm >= a.L) meet();                     // a one-token call: the reverse direction's wave parks nothing
-    // this wave's slot of the dB | dC partial sums: [batch][L][G][slots][2N]
-    const int tiles_per_group = (a.Dn / a.G + 63) / 64;
-    const int slot = my_tile % tiles_per_group + (s == 1 ? a.bc_slot_of_rev : 0);
-    float* const part = a.bc_part[s] + (((size_t)b * a.L * a.G + grp) * a.bc_slots + slot) * (2 * N);
-    const size_t part_token = (size_t)a.G * a.bc_slots * 2 * N;
-    constexpr int kLanesPerValue = 64 / (2 * N);
 
     float dh[N], gA[N];
 #pragma unroll
@@ -316,38 +350,45 @@ __global__ __launch_bounds__(256) void bwd_kernel(const BwdArgs a)
 
     // as in the state pass: the next chunk's activations are requested before this chunk is worked through
     T xr[CT], dr[CT], zr[CT], gr[CT], xnext[CT], dnext[CT], znext[CT], gnext[CT];
-    auto request = [&](T (&xq)[CT], T (&dq)[CT], T (&zq)[CT], T (&gq)[CT], int k) {
-#pragma unroll
-        for (int i = 0; i < CT; i++) {
-            const long long t = c.token(min(max(k, 0) * CT + i, a.L - 1));
-            xq[i] = c.xb[t * c.xs];
-            dq[i] = c.dtb_ptr[t * c.dts];
-            zq[i] = c.zb[t * c.zs];
-            gq[i] = dob[t * a.dout.st];
-        }
-    };
+    T xprev[3] = {};                                     // raw x of the three tokens before the chunk in xr
     float hnext[N];                                      // the state entering the next chunk to be walked
     auto request_state = [&](int k) {
-        const float* src = a.state + ((((size_t)s * gridDim.z + b) * a.nchunk + max(k, 0)) * a.Dn + ch) * N;
+        const float* src = (const float*)(state_base + k * state_stride + lo_state);
 #pragma unroll
         for (int n = 0; n < N; n++) hnext[n] = src[n];
     };
-    request(xr, dr, zr, gr, a.nchunk - 1);
-    request_state(a.nchunk - 1);
+    {   // the chunk walked first is the only one that can be short: its missing tokens repeat the last one
+        const int k = a.nchunk - 1;
+#pragma unroll
+        for (int i = 0; i < CT; i++) {
+            const int j = min(k * CT + i, a.L - 1);
+            xr[i] = *(const T*)(at_scan(wx, j) + lo_t);
+            dr[i] = *(const T*)(at_scan(wdt, j) + lo_t);
+            zr[i] = *(const T*)(at_scan(wz, j) + lo_t);
+            gr[i] = *(const T*)(at_scan(wg, j) + lo_t);
+        }
+        if (k > 0) {
+#pragma unroll
+            for (int e = 0; e < 3; e++) xprev[e] = *(const T*)(at_scan(wx, k * CT - 3 + e) + lo_t);
+        }
+        request_state(k);
+    }
     for (int k = a.nchunk - 1; k >= 0; k--) {
         const int first = k * CT;                                   // scan index of the chunk's first token
         const int count = min(CT, a.L - first);
-        request(xnext, dnext, znext, gnext, k - 1);
+        keep_narrow(lo_t);
+        keep_narrow(lo_pk);
+        keep_narrow(lo_state);
+        keep_narrow(lo_part);
         float xraw[CT + 3];
-        // the three raw x before the chunk are the last three of the chunk requested above (whole: only the last can be short)
 #pragma unroll
-        for (int e = 0; e < 3; e++) xraw[e] = k > 0 ? IO::cvt(xnext[CT - 3 + e]) : 0.0f;
+        for (int e = 0; e < 3; e++) xraw[e] = k > 0 ? IO::cvt(xprev[e]) : 0.0f;
         float hs[CT + 1][N];   // hs[i] = the state entering token i of the chunk
 #pragma unroll
         for (int n = 0; n < N; n++) hs[0][n] = hnext[n];
-        request_state(k - 1);
         float xc[CT], delta[CT], pre[CT];
         // forward over the chunk, keeping every state
+        const char* fwd_row = at_scan(wrow, first);
 #pragma unroll
         for (int i = 0; i < CT; i++) {
             xraw[i + 3] = IO::cvt(xr[i]);
@@ -356,20 +397,41 @@ __global__ __launch_bounds__(256) void bwd_kernel(const BwdArgs a)
             delta[i] = c.delta_of(IO::cvt(dr[i]), sp);
             if (i < count) {
                 const float u = delta[i] * xc[i];
-                uniform_ro_ptr row = c.row(first + i);
+                uniform_ro_ptr row = (uniform_ro_ptr)fwd_row;
 #pragma unroll
                 for (int n = 0; n < N; n++) hs[i + 1][n] = fmaf(fast_exp2(delta[i] * c.a2[n]), hs[i][n], u * row[n]);
             } else {
 #pragma unroll
                 for (int n = 0; n < N; n++) hs[i + 1][n] = hs[i][n];
             }
+            fwd_row += s_row;
         }
         // backward over the chunk, last token first
 #pragma unroll
         for (int i = CT - 1; i >= 0; i--) {
+            // Half way through the walk the states of the chunk's later tokens are dead: their registers take the
+            // next chunk (whole: one scalar step per tensor and token), its entering state and the three x before it.
+            if (i == CT / 2 - 1 && k > 0) {
+                const char* nx = at_scan(wx, first - CT);
+                const char* nd = at_scan(wdt, first - CT);
+                const char* nz = at_scan(wz, first - CT);
+                const char* ng = at_scan(wg, first - CT);
+                if (k > 1) {
+#pragma unroll
+                    for (int e = 0; e < 3; e++) xprev[e] = *(const T*)(nx - (3 - e) * (long long)s_x + lo_t);
+                }
+#pragma unroll
+                for (int e = 0; e < CT; e++) {
+                    xnext[e] = *(const T*)(nx + lo_t);
+                    dnext[e] = *(const T*)(nd + lo_t);
+                    znext[e] = *(const T*)(nz + lo_t);
+                    gnext[e] = *(const T*)(ng + lo_t);
+                    nx += s_x; nd += s_dt; nz += s_z; ng += s_g;
+                }
+                request_state(k - 1);
+            }
             if (i >= count) continue;
-            const int tok = c.token(first + i);
-            uniform_ro_ptr row = c.row(first + i);
+            uniform_ro_ptr row = (uniform_ro_ptr)p_row;
             const float zv = IO::cvt(zr[i]);
             const float dg = valid ? IO::cvt(gr[i]) : 0.0f;          // shadow lanes add nothing to the sums below
             float y = c.dval * xc[i];
@@ -400,7 +462,7 @@ __global__ __launch_bounds__(256) void bwd_kernel(const BwdArgs a)
             {
                 // the wave's 64 channels summed: value j ends up in lanes j * kLanesPerValue ..., one of which stores it
                 const float total = wave_reduce_scatter<2 * N>(bc_terms, lane);
-                if (exists && lane % kLanesPerValue == 0) part[(size_t)tok * part_token + lane / kLanesPerValue] = total;
+                if (exists && lane % kLanesPerValue == 0) *(float*)(const_cast<char*>(p_part) + lo_part) = total;
             }
             float ddt = ddelta;
             if (sp) {
@@ -417,19 +479,21 @@ __global__ __launch_bounds__(256) void bwd_kernel(const BwdArgs a)
             dp3 = dp2; dp2 = dp1; dp1 = dpre;
             const int j = first + i;
             if (j >= jm) {                                // never taken unless a.park
-                if (valid) a.parked[plane + (size_t)tok * a.Dn] = Parked{dxv, dz, ddt};
+                if (valid) *(Parked*)(const_cast<char*>(p_pk) + lo_pk) = Parked{dxv, dz, ddt};
                 if (j == jm) meet();
             } else {
                 const float px = q0[0], pz = q0[1], pd = q0[2];
 #pragma unroll
                 for (int e = 0; e < 3; e++) q0[e] = q1[e];
-                if (a.park) fetch_parked(q1, j - 2);
+                if (a.park && j >= 2) fetch_parked(q1, p_pk - 2 * (long long)s_pk);
                 if (valid) {
-                    IO::st(odx + (long long)tok * a.gdx[s].st, dxv + px);
-                    IO::st(odz + (long long)tok * a.gdz[s].st, dz + pz);
-                    IO::st(oddt + (long long)tok * a.gddt[s].st, ddt + pd);
+                    IO::st((T*)(const_cast<char*>(p_odx) + lo_t), dxv + px);
+                    IO::st((T*)(const_cast<char*>(p_odz) + lo_t), dz + pz);
+                    IO::st((T*)(const_cast<char*>(p_oddt) + lo_t), ddt + pd);
                 }
             }
+            p_odx -= s_odx; p_odz -= s_odz; p_oddt -= s_oddt;
+            p_pk -= s_pk; p_part -= s_part; p_row -= s_row;
         }
 #pragma unroll
         for (int i = 0; i < CT; i++) {
