@@ -104,6 +104,21 @@ def test_modes(gpu, oracle, mode):
     run_case(gpu, oracle, cfg, 77, untied="untied" in mode, random_a=mode != "progression_a")
 
 
+@pytest.mark.parametrize("seed", range(32))
+def test_random_descriptor(gpu, oracle, seed):
+    """Seeded random draws from the supported space: state count, conv width, length (around the chunks of 8 or 16 and
+    the meeting point of the two walks), channel counts with ragged tiles and shadow waves, groups, modes, dtypes."""
+    rng = np.random.default_rng(4100 + seed)
+    N = int(rng.choice([4, 8, 16]))
+    G = int(rng.choice([1, 1, 2]))
+    Dn = int(rng.choice([128, 256, 384])) if G == 2 else int(rng.choice([1, 7, 64, 100, 130, 192, 200]))
+    L = int(rng.choice([1, 2, 3, 5, 15, 17, 31, 33, 48, 65, 97]))
+    cfg = synth.mixer_cfg(int(rng.integers(1, 4)), L, Dn, d_state=N, d_conv=int(rng.integers(1, 5)), n_groups=G,
+                          io=str(rng.choice(["f32", "bf16"])), combine=int(rng.integers(0, 2)),
+                          dt_softplus=int(rng.integers(0, 2)))
+    run_case(gpu, oracle, cfg, 600 + seed, untied=bool(rng.integers(0, 2)), random_a=bool(rng.integers(0, 2)))
+
+
 def test_empty_call_zeroes_the_parameter_gradients(gpu, oracle):
     cfg = synth.mixer_cfg(0, 16, 64, io="f32")
     pf, pb = params(cfg, 1)
