@@ -189,8 +189,8 @@ int bimamba_block_fwd_static(const bimamba_desc* desc, const bimamba_params* pf,
 
 /* Gradients with respect to the activations one direction read.  dx, dz [batch, L, d_inner] and ddt [batch, L, n_heads]
  * are views in io_dtype like the inputs (written, one rounding each); dB, dC are contiguous fp32
- * [batch, L, n_groups, d_state] device arrays (sums over the channels of a group are formed in fp32 with atomics; the
- * library zeroes them first, it does not accumulate into what the caller left there). */
+ * [batch, L, n_groups, d_state] device arrays (sums over the channels of a group, formed in fp32 in a fixed order;
+ * overwritten, not accumulated into). */
 typedef struct bimamba_input_grads {
     bimamba_tensor dx, dz, ddt;
     float* dB;
@@ -198,7 +198,8 @@ typedef struct bimamba_input_grads {
 } bimamba_input_grads;
 
 /* Gradients with respect to one direction's parameters: device pointers, fp32, contiguous, shaped like bimamba_params;
- * sums over batch and tokens, zeroed by the library first.  dconv_b / ddt_bias may be NULL (not wanted). */
+ * sums over batch and tokens, zeroed by the library first; the sum over the batch is formed with fp32 atomics, so
+ * its last bits can differ between two calls with batch > 2.  dconv_b / ddt_bias may be NULL (not wanted). */
 typedef struct bimamba_param_grads {
     float* dconv_w;
     float* dconv_b;
@@ -228,7 +229,8 @@ int bimamba_bwd(const bimamba_desc* desc, const bimamba_params* pf, const bimamb
                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Workspace of bimamba_bwd: fp32 B|C rows, the state entering every chunk of 8 (16 for d_state 4) tokens for both
- * directions (2 * batch * ceil(L / chunk) * d_inner * d_state floats) and three fp32 planes of 2 * batch * L * d_inner. */
+ * directions (2 * batch * ceil(L / chunk) * d_inner * d_state floats), 12 bytes per (batch, token, channel) for the
+ * values one direction leaves for the other to add, and the per-wave partial sums of dB and dC. */
 size_t bimamba_bwd_workspace_bytes(const bimamba_desc* desc);
 
 /* Bytes of device scratch the two calls above need for this descriptor (0 on an invalid descriptor).  Pure host code. */

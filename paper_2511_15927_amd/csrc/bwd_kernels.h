@@ -13,13 +13,15 @@
 //   dxc_t = D dy_t + sum_n dh_t[n] Delta_t B_t[n]    dpre_t = dxc_t silu'(pre_t)
 //   dx_t = sum_j w[K-1-j] dpre_{t + j steps}         dw[k] += dpre_t x_{t - (K-1-k) steps},  dcb += dpre_t
 //
-// Mapping: a lane is one (direction, batch, channel) chain, as in the forward sweep with one lane per chain.  The
-// backward recurrence needs the states in the reverse of the order the forward recurrence makes them, so
+// Mapping: a lane is one (direction, batch, channel) chain, as in the forward sweep with one lane per chain (two
+// lanes per chain in the state pass for 8 and 16 states).  The backward recurrence needs the states in the reverse of
+// the order the forward recurrence makes them, so
 //   bwd_state_kernel  walks each chain forward and stores the state entering every chunk of kBwdChunk tokens;
 //   bwd_kernel        takes the chunks last to first: it recomputes a chunk's states from the stored one into
 //                     registers (kBwdChunk * N values per lane) and then walks the chunk backwards.
-// dB_t and dC_t are sums over the channels of a group: each wave adds its 64 channels with lane-permute adds and one
-// lane adds the result to the caller's fp32 buffer with a hardware atomic.  Parameter gradients are kept per lane and
+// dB_t and dC_t are sums over the channels of a group: each wave adds its 64 channels with a reduce-scatter over its
+// lanes and stores the sums into its own slot of a partial buffer; bwd_bc_kernel adds the slots in a fixed order (no
+// atomics on activation gradients: the result does not depend on timing).  Parameter gradients are kept per lane and
 // added atomically once per chain (the sum over the batch).  When both directions read the same activations their
 // gradients of x, z and Delta have to be added: the two waves of a channel tile walk the tokens in opposite orders
 // and meet in the middle, as in the forward sweep; each parks its fp32 values for the half it reaches first and, past
