@@ -221,6 +221,8 @@ typedef struct bimamba_param_grads {
  * Supported: the selective-scan layout, i.e. n_heads == d_inner (Delta, A, D per channel), a_kind PER_HEAD_STATE,
  * d_kind PER_CHANNEL, conv_bc 0, d_state 4, 8 or 16; every other descriptor returns BIMAMBA_ERR_UNSUPPORTED.
  * Nothing may overlap: the gradient views among themselves, the inputs, dout.  (Not checked.)
+ * The call enqueues kernels only (its accumulation targets are cleared by a fill kernel, not a memset node) and asks
+ * the runtime nothing at first use, so it can be captured into a HIP graph as it is.
  */
 int bimamba_bwd(const bimamba_desc* desc, const bimamba_params* pf, const bimamba_params* pb,
                 const bimamba_inputs* in_f, const bimamba_inputs* in_b, const bimamba_tensor* dout,

@@ -119,6 +119,65 @@ def test_random_descriptor(gpu, oracle, seed):
     run_case(gpu, oracle, cfg, 600 + seed, untied=bool(rng.integers(0, 2)), random_a=bool(rng.integers(0, 2)))
 
 
+def test_gradient_call_replayed_from_a_hip_graph(gpu):
+    """bimamba_bwd captured into a HIP graph (it clears its accumulation targets with kernels, not memset nodes):
+    every replay, with eager work and synchronisation between replays and fresh contents in the static buffers, must
+    equal the eager call on the same contents: bit for bit for the activation gradients (fixed summation order), to
+    rounding for the parameter gradients (their sum over the batch is formed with atomics)."""
+    cfg = synth.mixer_cfg(3, 45, 200, io="bf16")
+    Bt, L, Dn, N, K = 3, 45, 200, cfg["d_state"], cfg["d_conv"]
+    pf, pb = params(cfg, 5)
+    dpf, dpb = bd.to_device(pf), bd.to_device(pb)
+    desc = bd.make_desc(cfg)
+    static_in = bd.to_device(synth.make_inputs(cfg, 5), cfg)
+    dout = torch.zeros(Bt, L, Dn, dtype=torch.bfloat16, device="cuda")
+    io = torch.bfloat16
+    gi = dict(dx=torch.empty(Bt, L, Dn, dtype=io, device="cuda"), dz=torch.empty(Bt, L, Dn, dtype=io, device="cuda"),
+              ddt=torch.empty(Bt, L, Dn, dtype=io, device="cuda"), dB=torch.empty(Bt, L, 1, N, device="cuda"),
+              dC=torch.empty(Bt, L, 1, N, device="cuda"))
+    mk = lambda: dict(dconv_w=torch.empty(Dn, K, device="cuda"), dconv_b=torch.empty(Dn, device="cuda"),
+                      dA=torch.empty(Dn, N, device="cuda"), dD=torch.empty(Dn, device="cuda"), ddt_bias=torch.empty(Dn, device="cuda"))
+    qf, qb = mk(), mk()
+    ws = torch.empty(bd.bimamba_bwd_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    args = (desc, bd.make_params(dpf), bd.make_params(dpb), bd.make_inputs(static_in), None, bd.make_tensor(dout),
+            bd.make_input_grads(gi), None, bd.make_param_grads(qf), bd.make_param_grads(qb), ws)
+
+    def call():
+        bd.bimamba_bwd(*args)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    outs = list(gi.values()) + list(qf.values()) + list(qb.values())
+    n_exact = len(gi)
+    for rep in range(3):
+        fresh = bd.to_device(synth.make_inputs(cfg, 70 + rep), cfg)
+        for k in static_in:
+            static_in[k].copy_(fresh[k])
+        dout.copy_(torch.randn(Bt, L, Dn, generator=torch.Generator().manual_seed(80 + rep)).to(io))
+        call()
+        torch.cuda.synchronize()
+        want = [t.clone() for t in outs]
+        for t in outs:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (got, ref) in enumerate(zip(outs, want)):
+            if i < n_exact:
+                assert torch.equal(got, ref), (rep, i)
+            elif not bool(ref.any()):
+                assert not bool(got.any()), (rep, i)      # e.g. the Delta bias without softplus
+            else:
+                assert rel_all(got.cpu().numpy(), ref.cpu().numpy()) < 1e-6, (rep, i)
+
+
 def test_empty_call_zeroes_the_parameter_gradients(gpu, oracle):
     cfg = synth.mixer_cfg(0, 16, 64, io="f32")
     pf, pb = params(cfg, 1)
