@@ -178,6 +178,56 @@ def test_gradient_call_replayed_from_a_hip_graph(gpu):
                 assert rel_all(got.cpu().numpy(), ref.cpu().numpy()) < 1e-6, (rep, i)
 
 
+@pytest.mark.parametrize("untied", [False, True])
+def test_column_slices_with_their_own_token_strides(gpu, oracle, untied):
+    """x, z, dt as column slices of one wide buffer per direction, dout a slice of another, dx, dz, ddt slices of a
+    third: every tensor has its own row pitch, and the kernels step through each with its own stride.  Nothing outside
+    the gradient views may be written."""
+    cfg = synth.mixer_cfg(2, 37, 72, io="bf16", combine=synth.COMBINE_SEPARATE)
+    Bt, L, Dn, N, K = 2, 37, 72, cfg["d_state"], cfg["d_conv"]
+    io = torch.bfloat16
+    pf, pb = params(cfg, 3)
+    ins = [synth.make_inputs(cfg, 3)] + ([synth.make_inputs(cfg, 503)] if untied else [])
+    g = torch.Generator().manual_seed(12)
+    dout = rounded(torch.randn(Bt, L, 2 * Dn, generator=g), "bf16")
+
+    def sliced(t, width, at):
+        wide = torch.zeros(Bt, L, width, dtype=io, device="cuda")
+        view = wide[..., at:at + t.shape[-1]]
+        view.copy_(torch.as_tensor(t).to(io))
+        return wide, view
+
+    dev_in, grads, wides = [], [], []
+    for inp in ins:
+        d = bd.to_device(inp, cfg)
+        d["x"] = sliced(inp["x"], 3 * Dn + 40, 8)[1]
+        d["z"] = sliced(inp["z"], 2 * Dn + 24, 16)[1]
+        d["dt"] = sliced(inp["dt"], Dn + 8, 0)[1]
+        dev_in.append(d)
+        wide = torch.zeros(Bt, L, 3 * Dn + 48, dtype=io, device="cuda")
+        wides.append(wide)
+        grads.append(dict(dx=wide[..., 8:8 + Dn], dz=wide[..., 16 + Dn:16 + 2 * Dn], ddt=wide[..., 40 + 2 * Dn:40 + 3 * Dn],
+                          dB=torch.empty(Bt, L, 1, N, device="cuda"), dC=torch.empty(Bt, L, 1, N, device="cuda")))
+    do = sliced(dout, 2 * Dn + 64, 32)[1]
+    mk = lambda: dict(dconv_w=torch.empty(Dn, K, device="cuda"), dconv_b=torch.empty(Dn, device="cuda"),
+                      dA=torch.empty(Dn, N, device="cuda"), dD=torch.empty(Dn, device="cuda"), ddt_bias=torch.empty(Dn, device="cuda"))
+    qf, qb = mk(), mk()
+    desc = bd.make_desc(cfg)
+    dpf, dpb = bd.to_device(pf), bd.to_device(pb)
+    ws = torch.empty(bd.bimamba_bwd_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    bd.bimamba_bwd(desc, bd.make_params(dpf), bd.make_params(dpb), bd.make_inputs(dev_in[0]),
+                   bd.make_inputs(dev_in[1]) if untied else None, bd.make_tensor(do), bd.make_input_grads(grads[0]),
+                   bd.make_input_grads(grads[1]) if untied else None, bd.make_param_grads(qf), bd.make_param_grads(qb), ws)
+    torch.cuda.synchronize()
+    host = lambda d: {k: v.float().cpu().numpy().astype(np.float64) for k, v in d.items()}
+    got = (host(grads[0]), host(grads[1]) if untied else None, host(qf), host(qb))
+    ref = oracle.bimamba_bwd(cfg, to_np(pf), to_np(pb), to_np(ins[0]), to_np(ins[1]) if untied else None, dout)
+    compare(cfg, got, ref)
+    for wide in wides:
+        for lo, hi in ((0, 8), (8 + Dn, 16 + Dn), (16 + 2 * Dn, 40 + 2 * Dn), (40 + 3 * Dn, 48 + 3 * Dn)):
+            assert float(wide[..., lo:hi].abs().max()) == 0.0
+
+
 def test_empty_call_zeroes_the_parameter_gradients(gpu, oracle):
     cfg = synth.mixer_cfg(0, 16, 64, io="f32")
     pf, pb = params(cfg, 1)
