@@ -75,7 +75,7 @@ enum bimamba_status {
     BIMAMBA_ERR_HIP = -6,                 /* a launch of this call failed (errors pending from earlier, unrelated calls are
                                              neither reported nor cleared) */
     BIMAMBA_ERR_SCRATCH_EXCEEDED = -7,    /* bimamba_block_fwd_static: the call needs more than BIMAMBA_STATIC_SCRATCH_BYTES */
-    BIMAMBA_ERR_ALIAS = -8                /* out may overlap an input view (checked on the host) */
+    BIMAMBA_ERR_ALIAS = -8                /* out may overlap an input view; bimamba_bwd: dpf == dpb (checked on the host) */
 };
 
 enum bimamba_dtype { BIMAMBA_F32 = 0, BIMAMBA_BF16 = 1 };

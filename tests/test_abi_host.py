@@ -62,6 +62,47 @@ def test_null_and_shape_errors_are_decided_on_the_host():
     assert call_fwd(desc, p, p, wide, out) == -3                 # token stride beyond what a tile's 32-bit row offsets reach
 
 
+def call_bwd(desc, pf, pb, inp, inp_b, dout, gi, gi_b, qf, qb, ws=0x1000, ws_bytes=1 << 40):
+    ref = lambda v: C.byref(v) if v is not None else None
+    return bd.lib().bimamba_bwd(C.byref(desc), ref(pf), ref(pb), ref(inp), ref(inp_b), ref(dout), ref(gi), ref(gi_b),
+                                ref(qf), ref(qb), C.c_void_p(ws), ws_bytes, None)
+
+
+def test_gradient_call_errors_are_decided_on_the_host():
+    cfg, desc, p, inp, dout = good()
+    t = lambda ch, at=0x1000: bd.Tensor(at, 64 * ch, ch)
+    gi, gi2 = bd.InputGrads(t(128), t(128), t(128), 0x1000, 0x1000), bd.InputGrads(t(128), t(128), t(128), 0x1000, 0x1000)
+    qf, qb = bd.ParamGrads(0x1000, None, 0x1000, 0x1000, None), bd.ParamGrads(0x1000, None, 0x1000, 0x1000, None)
+    need = bd.bimamba_bwd_workspace_bytes(desc)
+    assert need > 0
+    assert call_bwd(desc, p, p, inp, None, dout, gi, None, qf, qb, ws_bytes=need - 1) == -5
+    assert call_bwd(desc, p, p, inp, None, dout, gi, None, qf, qb, ws=None) == -1
+    assert call_bwd(desc, p, p, inp, None, dout, gi, None, qf, qb, ws=0x1008) == -4
+    assert call_bwd(desc, None, p, inp, None, dout, gi, None, qf, qb) == -1
+    assert call_bwd(desc, p, p, None, None, dout, gi, None, qf, qb) == -1
+    assert call_bwd(desc, p, p, inp, None, None, gi, None, qf, qb) == -1
+    assert call_bwd(desc, p, p, inp, None, dout, None, None, qf, qb) == -1
+    assert call_bwd(desc, p, p, inp, None, dout, gi, None, None, qb) == -1
+    assert call_bwd(desc, p, p, inp, None, dout, gi, None, qf, qf) == -8        # the two directions' parameter gradients alias
+    # shared activations take one set of input gradients, separate activations need two
+    assert call_bwd(desc, p, p, inp, None, dout, gi, gi2, qf, qb) == -1
+    other = bd.Inputs(t(128, 0x9000), inp.z, inp.dt, inp.B, inp.C)
+    assert call_bwd(desc, p, p, inp, other, dout, gi, None, qf, qb) == -1
+    no_db = bd.InputGrads(t(128), t(128), t(128), None, 0x1000)
+    assert call_bwd(desc, p, p, inp, None, dout, no_db, None, qf, qb) == -1
+    odd = bd.InputGrads(t(128), t(128), t(128), 0x1002, 0x1000)
+    assert call_bwd(desc, p, p, inp, None, dout, odd, None, qf, qb) == -4
+    narrow = bd.InputGrads(bd.Tensor(0x1000, 64 * 128, 100), t(128), t(128), 0x1000, 0x1000)
+    assert call_bwd(desc, p, p, inp, None, dout, narrow, None, qf, qb) == -2
+    assert call_bwd(desc, p, p, inp, None, dout, gi, None, bd.ParamGrads(None, None, 0x1000, 0x1000, None), qb) == -1
+    # layouts the gradient kernels do not cover are refused, whatever else is passed
+    m2 = bd.make_desc(synth.m2_cfg(2, 64, 128, headdim=64, d_state=64))
+    assert call_bwd(m2, p, p, inp, None, dout, gi, None, qf, qb) == -3
+    assert bd.bimamba_bwd_workspace_bytes(m2) == 0
+    n32 = bd.make_desc(synth.mixer_cfg(2, 64, 128, d_state=32))
+    assert call_bwd(n32, p, p, inp, None, dout, gi, None, qf, qb) == -3
+
+
 @pytest.mark.parametrize("field,value,code", [
     ("struct_size", 8, -2), ("batch", -1, -2), ("seqlen", -5, -2), ("d_inner", 0, -2), ("n_heads", 3, -2),
     ("n_groups", 5, -2), ("d_state", 12, -3), ("d_conv", 5, -3), ("d_conv", 0, -2), ("io_dtype", 7, -3),
