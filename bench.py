@@ -24,8 +24,10 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16 matrix
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200,
+                    help="timed steps; the chip takes a few milliseconds of continuous work to reach its sustained rate, so "
+                         "short runs read 2-8 %% low")
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="headline", help="name in synth.CONFIGS (default: d_inner=4096, L=8192, batch 8, bf16)")
     ap.add_argument("--general-a", action="store_true", help="draw A with no structure across states")
     ap.add_argument("--no-cpu-baseline", action="store_true")
