@@ -230,8 +230,9 @@ int bimamba_bwd(const bimamba_desc* desc, const bimamba_params* pf, const bimamb
                 const bimamba_param_grads* dpf, const bimamba_param_grads* dpb,
                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Workspace of bimamba_bwd: fp32 B|C rows, the state entering every chunk of 8 (16 for d_state 4) tokens for both
- * directions (2 * batch * ceil(L / chunk) * d_inner * d_state floats), 12 bytes per (batch, token, channel) for the
+/* Workspace of bimamba_bwd: fp32 B|C rows, the state entering every chunk of tokens for both directions
+ * (2 * batch * ceil(L / chunk) * d_inner * d_state floats; chunk = 8 tokens, 16 for d_state 4, while the
+ * call has at most as many waves as the device has SIMDs; beyond that 8 tokens, 4 for d_state 16), 12 bytes per (batch, token, channel) for the
  * values one direction leaves for the other to add, and the per-wave partial sums of dB and dC. */
 size_t bimamba_bwd_workspace_bytes(const bimamba_desc* desc);
 

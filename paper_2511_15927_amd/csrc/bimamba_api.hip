@@ -639,6 +639,7 @@ int bimamba_block_fwd_static(const bimamba_desc* desc, const bimamba_params* pf,
 // ---- gradients -------------------------------------------------------------------------------------------------
 namespace {
 struct BwdPlan {
+    bool dense;   // the two-waves-per-SIMD form of the kernels (shorter chunks for 16 states)
     int chunk, nchunk;
     int tiles_per_group;
     size_t off_bc[2], off_state, off_parked, off_part[2], total;
@@ -657,7 +658,8 @@ int check_bwd_desc(const bimamba_desc* d)
 BwdPlan make_bwd_plan(const bimamba_desc* d)
 {
     BwdPlan p{};
-    p.chunk = bm::bwd_chunk_tokens(d->d_state);
+    p.dense = bm::bwd_dense(d->d_inner, d->batch);
+    p.chunk = bm::bwd_chunk_tokens(d->d_state, p.dense);
     p.nchunk = d->seqlen > 0 ? (d->seqlen + p.chunk - 1) / p.chunk : 1;
     const size_t bc = align_up((size_t)d->batch * d->seqlen * d->n_groups * 2 * d->d_state * sizeof(float), 256);
     const size_t parked = align_up((size_t)d->batch * d->seqlen * d->d_inner * sizeof(Parked), 256);
@@ -768,7 +770,7 @@ int bimamba_bwd(const bimamba_desc* d, const bimamba_params* pf, const bimamba_p
         a.park = shared;
         a.bc_slots = plan.tiles_per_group * (shared ? 2 : 1);
         a.bc_slot_of_rev = shared ? plan.tiles_per_group : 0;
-        bm::launch_bwd(d->d_state, bf16, a, d->batch, st);
+        bm::launch_bwd(d->d_state, bf16, plan.dense, a, d->batch, st);
         for (int s = 0; s < (shared ? 1 : 2); s++) {
             const bimamba_input_grads* gi = s == 0 ? din_f : din_b;
             BwdBcArgs ba{};

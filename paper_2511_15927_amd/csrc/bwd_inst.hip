@@ -6,7 +6,14 @@
 namespace bm {
 
 bool bwd_supported(int d_state) { return d_state == 4 || d_state == 8 || d_state == 16; }
-int bwd_chunk_tokens(int d_state) { return d_state <= 4 ? kBwdChunk<4> : d_state <= 8 ? kBwdChunk<8> : kBwdChunk<16>; }
+int bwd_chunk_tokens(int d_state, bool dense)
+{
+    if (dense) return d_state <= 4 ? kBwdChunk<4, true> : d_state <= 8 ? kBwdChunk<8, true> : kBwdChunk<16, true>;
+    return d_state <= 4 ? kBwdChunk<4, false> : d_state <= 8 ? kBwdChunk<8, false> : kBwdChunk<16, false>;
+}
+
+// The dense form (two waves per SIMD) once the walk has more waves than the chip has SIMDs; see kBwdChunk.
+bool bwd_dense(int d_inner, int batch) { return 2LL * ((d_inner + 63) / 64) * batch > 4LL * cu_count(); }
 
 // Zeroes a float buffer (the accumulation targets of the atomics above); a kernel rather than a memset node so that
 // the call can be captured into a graph.
@@ -37,22 +44,29 @@ void launch_bwd_bc(const BwdBcArgs& a, hipStream_t st)
     hipLaunchKernelGGL(bwd_bc_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
 }
 
-template <int N, typename IO>
+template <int N, typename IO, bool DENSE>
 static void launch_pair(const BwdArgs& a, int batch, hipStream_t st)
 {
     const dim3 grid((unsigned)(((a.Dn + 63) / 64 + 1) / 2), 1, (unsigned)batch);
     constexpr int kStateTile = 64 / kBwdStateLanes<N>;    // channels per wave of the state pass
     const dim3 state_grid((unsigned)(((a.Dn + kStateTile - 1) / kStateTile + 1) / 2), 1, (unsigned)batch);
-    hipLaunchKernelGGL((bwd_state_kernel<N, IO>), state_grid, dim3(256), 0, st, a);
-    hipLaunchKernelGGL((bwd_kernel<N, IO>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((bwd_state_kernel<N, IO, DENSE>), state_grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((bwd_kernel<N, IO, DENSE>), grid, dim3(256), 0, st, a);
 }
 
-void launch_bwd(int d_state, int io_bf16, const BwdArgs& a, int batch, hipStream_t st)
+template <int N, typename IO>
+static void launch_form(bool dense, const BwdArgs& a, int batch, hipStream_t st)
 {
-#define BM_BWD(n)                                         \
-    case n:                                               \
-        if (io_bf16) launch_pair<n, IoBF16>(a, batch, st); \
-        else launch_pair<n, IoF32>(a, batch, st);          \
+    if (dense) launch_pair<N, IO, true>(a, batch, st);
+    else launch_pair<N, IO, false>(a, batch, st);
+}
+
+void launch_bwd(int d_state, int io_bf16, bool dense, const BwdArgs& a, int batch, hipStream_t st)
+{
+#define BM_BWD(n)                                                \
+    case n:                                                      \
+        if (io_bf16) launch_form<n, IoBF16>(dense, a, batch, st); \
+        else launch_form<n, IoF32>(dense, a, batch, st);          \
         break;
     switch (d_state) {
         BM_BWD(4)

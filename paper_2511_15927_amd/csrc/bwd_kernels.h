@@ -54,8 +54,12 @@ struct BwdArgs {
     int L, Dn, G, K, nchunk, dt_softplus, separate;
 };
 
-template <int N>
-constexpr int kBwdChunk = N <= 4 ? 16 : 8;   // tokens per chunk: (chunk + 1) * N state values per lane in registers
+// Tokens per chunk: (chunk + 1) * N state values per lane live in registers during the walk.  DENSE is the form for
+// launches with more waves than SIMDs: it has to leave room for a second wave on the SIMD (256 registers), which for 16
+// states means chunks of four tokens and twice the stored states (and eight instead of sixteen for 4).  Measured at d_inner 4096 and 64 K tokens: batch 8
+// (one wave per SIMD) 17.2 ms in the plain form, 18.8 ms in the dense one; batch 16 and 32: 17.2 against 13.7 ms.
+template <int N, bool DENSE>
+constexpr int kBwdChunk = DENSE ? (N <= 8 ? 8 : 4) : (N <= 4 ? 16 : 8);
 
 __device__ __forceinline__ float dsilu(float v)
 {
@@ -192,10 +196,10 @@ constexpr int kBwdStateLanes = N >= 8 ? 2 : 1;
 
 // grid (ceil(ceil(Dn / (64 / S)) / 2), 1, batch), block 256: waves 0 / 1 the forward / reverse chain of one channel
 // tile, waves 2 / 3 those of the next; S = kBwdStateLanes<N>, lane l of a wave holds states (l % S) * N / S ... of its chain.
-template <int N, typename IO>
+template <int N, typename IO, bool DENSE>
 __global__ __launch_bounds__(256, kBwdStateLanes<N>) void bwd_state_kernel(const BwdArgs a)
 {
-    constexpr int CT = kBwdChunk<N>;
+    constexpr int CT = kBwdChunk<N, DENSE>;
     constexpr int S = kBwdStateLanes<N>;
     constexpr int NS = N / S;
     static_assert(NS % 4 == 0, "a lane's states are loaded and stored four at a time");
@@ -267,11 +271,11 @@ __global__ __launch_bounds__(256, kBwdStateLanes<N>) void bwd_state_kernel(const
     }
 }
 
-template <int N, typename IO>
-__global__ __launch_bounds__(256) void bwd_kernel(const BwdArgs a)
+template <int N, typename IO, bool DENSE>
+__global__ __launch_bounds__(256, DENSE ? 2 : 1) void bwd_kernel(const BwdArgs a)
 {
     using T = typename IO::T;
-    constexpr int CT = kBwdChunk<N>;
+    constexpr int CT = kBwdChunk<N, DENSE>;
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = threadIdx.x & 63;
     BwdChain<N, IO> c;

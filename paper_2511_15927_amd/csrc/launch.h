@@ -40,7 +40,8 @@ struct BwdArgs;
 struct BwdBcArgs;
 void launch_bwd_bc(const BwdBcArgs& a, hipStream_t st);
 bool bwd_supported(int d_state);
-int bwd_chunk_tokens(int d_state);
-void launch_bwd(int d_state, int io_bf16, const BwdArgs& a, int batch, hipStream_t st);
+int bwd_chunk_tokens(int d_state, bool dense);
+bool bwd_dense(int d_inner, int batch);
+void launch_bwd(int d_state, int io_bf16, bool dense, const BwdArgs& a, int batch, hipStream_t st);
 void launch_bwd_zero(float* p, long long n, hipStream_t st);
 }  // namespace bm

@@ -228,6 +228,14 @@ def test_column_slices_with_their_own_token_strides(gpu, oracle, untied):
             assert float(wide[..., lo:hi].abs().max()) == 0.0
 
 
+@pytest.mark.parametrize("N", [4, 8, 16])
+@pytest.mark.parametrize("L", [1, 5, 37, 70])
+def test_more_waves_than_simds_takes_the_dense_form(gpu, oracle, N, L):
+    """Batch 9 at d_inner 4096 is 1152 waves for 1024 SIMDs: the kernels built for two waves per SIMD (shorter chunks
+    for 4 and 16 states) and the plan that sizes their stored states; every channel compared."""
+    run_case(gpu, oracle, synth.mixer_cfg(9, L, 4096, d_state=N, io="bf16" if L % 2 else "f32"), 900 + N + L)
+
+
 def test_empty_call_zeroes_the_parameter_gradients(gpu, oracle):
     cfg = synth.mixer_cfg(0, 16, 64, io="f32")
     pf, pb = params(cfg, 1)
